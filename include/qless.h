@@ -1,0 +1,135 @@
+/*
+ * qless.h -- C ABI of the MI355X (gfx950) QLESS gradient-datastore and influence engine.
+ *
+ * The four calls follow the pipeline of the QLESS paper (arXiv 2502.01703):
+ *   qless_project   Eq.(1)        random projection of per-example gradients, d -> k
+ *   qless_quantize  Eq.(4),(5)    absmax b-bit quantisation into the packed gradient datastore
+ *   qless_score     Eq.(6),(7)    normalised quantised cosine, learning-rate weighted over
+ *                                 checkpoints, reduced by max over validation examples
+ *   qless_topk      Sec. 4.1      selection of the highest-scoring training examples
+ *
+ * Conventions common to every call
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
+ *     host memory read before the call returns.  The library allocates and frees nothing on
+ *     the device and keeps no state between calls.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream);
+ *     no call synchronises.  Outputs are valid once the caller has synchronised the stream.
+ *   - Every call returns a qless_status.  Arguments are validated on the host before anything
+ *     is launched; on any status other than QLESS_OK no output has been touched.
+ *   - Workspace sizes come from the matching *_workspace() query with the same shape
+ *     arguments; a workspace may be reused by later calls on the same stream.
+ *   - Inputs must be finite (no NaN/Inf); this is not checked.
+ */
+#ifndef QLESS_H
+#define QLESS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QLESS_OK = 0,
+    QLESS_ERR_INVALID_ARG = 1,   /* null pointer, negative size, leading dimension too small */
+    QLESS_ERR_UNSUPPORTED = 2,   /* bits not in {1,2,4,8}, k not a multiple of 64, ... */
+    QLESS_ERR_WORKSPACE = 3,     /* workspace missing or smaller than the query's answer */
+    QLESS_ERR_DEVICE = 4         /* the HIP runtime reported an error at launch */
+} qless_status;
+
+typedef enum { QLESS_F32 = 0, QLESS_BF16 = 1 } qless_dtype;
+typedef enum { QLESS_RADEMACHER = 0, QLESS_GAUSSIAN = 1 } qless_proj;
+
+#define QLESS_MAX_CHECKPOINTS 16
+
+const char *qless_status_string(qless_status s);
+
+/* ---------------------------------------------------------------------------------------------
+ * Projection, Eq.(1) (Sec. 2.2; matrix families of Sec. 2.4):  P[i][m] = sum_j R[m][d_offset+j] G[i][j]
+ *
+ * R is k x (any number of columns), never stored: entry (m, j) is a pure function of
+ * (seed, m, j).  QLESS_RADEMACHER: entries +-1 (unscaled).  QLESS_GAUSSIAN: entries from a
+ * 256-level table of standard-normal quantiles rounded to bfloat16.
+ *
+ *   G          device, n x d_len, row-major with leading dimension ldG (elements), dtype dt
+ *   d_offset   column of R that G's column 0 multiplies; lets a caller feed a long gradient in
+ *              slices (per layer).  Must be a multiple of 32; d_offset + d_len <= 2^36.
+ *   k          projected dimension, a positive multiple of 64
+ *   accumulate 0: P = R G      non-zero: P = P + R G   (slices are summed in call order)
+ *   P          device, n x k fp32, leading dimension ldP >= k
+ *   ws         device workspace of at least qless_project_workspace(n, d_len, k) bytes
+ * Arithmetic: gradient values enter as bfloat16 (fp32 input is rounded to nearest-even),
+ * products are exact, sums are fp32 in a fixed order (results are run-to-run identical).
+ * n == 0 or d_len == 0 is valid (P is zero-filled unless accumulating).
+ * ------------------------------------------------------------------------------------------- */
+size_t qless_project_workspace(int64_t n, int64_t d_len, int32_t k);
+qless_status qless_project(const void *G, qless_dtype dt, int64_t n, int64_t d_len, int64_t ldG,
+                           int64_t d_offset, int32_t k, qless_proj kind, uint64_t seed,
+                           int accumulate, float *P, int64_t ldP,
+                           void *ws, size_t ws_bytes, void *stream);
+
+/* Diagnostic: the generator's raw 32-bit words, out[r * nwords + t] = word(seed, m0 + r, w0 + t,
+ * salt) for r < nrows, t < nwords (device, uint32).  Rademacher signs are read from salt 0
+ * (32 columns per word), Gaussian table indices from salt 1 (4 columns per word). */
+qless_status qless_generator_words(uint64_t seed, uint32_t m0, int32_t nrows, uint32_t w0,
+                                   int32_t nwords, uint32_t salt, uint32_t *out, void *stream);
+/* Diagnostic: the 256 Gaussian table values as fp32 (host output). */
+qless_status qless_gaussian_table(float *host_out256);
+
+/* ---------------------------------------------------------------------------------------------
+ * Quantisation, Eq.(4),(5) (Sec. 2.3, 3.1); bits = 1 is the sign code (Table 3, Sec. 5).
+ * Per row:  S = max_m |P[m]|;  bits >= 2: q = clamp(rne(P * fl32(alpha / S)), -alpha, alpha) with
+ * alpha = 2^(bits-1) - 1;  bits == 1: q = -1 if P < 0 else +1.  A zero row gives q = 0
+ * (bits >= 2) or all +1 (bits == 1) and S = 0.
+ *
+ *   P      device, n x k fp32, leading dimension ldP >= k;  k a positive multiple of 64
+ *   codes  device, n rows of k*bits/8 bytes, packed:
+ *            8: int8 at byte m        4: two's-complement nibbles, element 2t low, 2t+1 high
+ *            2: k/8 bytes "non-zero" plane then k/8 bytes "negative" plane, element m at bit
+ *               m%8 of byte m/8       1: the "negative" plane only
+ *   S      device, n fp32: the stored scale of Sec. 3.1
+ *   rnorm  device, n fp32: 1 / ||q||_2  (0 for an all-zero code), the factor of Eq.(6)
+ * ------------------------------------------------------------------------------------------- */
+qless_status qless_quantize(const float *P, int64_t ldP, int64_t n, int32_t k, int bits,
+                            void *codes, float *S, float *rnorm, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Influence scores, Eq.(6),(7) (Sec. 3.2) and the max over validation examples:
+ *   acc(z, z') = sum_{i<C} eta[i] * <q_{z,i}, q_{z',i}> * rnorm_i(z) * rnorm'_i(z')
+ *   score[z]   = max_{z' < M} acc(z, z')
+ * The integer dot product is exact; the fp32 epilogue is
+ *   ((float)D * rnorm_i(z)) * (eta[i] * rnorm'_i(z')),  added over i = 0..C-1 starting from +0,
+ * each operation rounded once (no fused multiply-add).
+ *
+ *   train_codes, val_codes   host arrays of C device pointers to N (resp. M) packed rows
+ *   train_rnorm, val_rnorm   host arrays of C device pointers to N (resp. M) fp32
+ *   eta        host, C learning-rate weights;  1 <= C <= QLESS_MAX_CHECKPOINTS
+ *   score      device, N fp32, or NULL
+ *   full       device, N x M fp32 row-major receiving acc, or NULL (at least one of the two)
+ *   ws         device workspace of at least qless_score_workspace(N, M, k, bits, C) bytes
+ * N == 0 is valid; M >= 1.
+ * ------------------------------------------------------------------------------------------- */
+size_t qless_score_workspace(int64_t N, int32_t M, int32_t k, int bits, int C);
+qless_status qless_score(const void *const *train_codes, const float *const *train_rnorm,
+                         const void *const *val_codes, const float *const *val_rnorm,
+                         const float *eta, int C, int64_t N, int32_t M, int32_t k, int bits,
+                         float *score, float *full, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Selection (Sec. 4.1: the top 5 % by score): indices of the k_sel largest scores ordered by
+ * (score descending, index ascending); +0 and -0 compare equal.
+ *
+ *   score  device, N fp32 (N < 2^32)     idx  device, k_sel int64
+ *   val    device, k_sel fp32 receiving score[idx[t]], or NULL
+ *   ws     device workspace of at least qless_topk_workspace(N, k_sel) bytes
+ * 0 <= k_sel <= N.
+ * ------------------------------------------------------------------------------------------- */
+size_t qless_topk_workspace(int64_t N, int64_t k_sel);
+qless_status qless_topk(const float *score, int64_t N, int64_t k_sel, int64_t *idx, float *val,
+                        void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QLESS_H */

@@ -1,0 +1,220 @@
+// qless_topk: indices of the k_sel largest scores, ordered by (score descending, index ascending)
+// (paper Sec. 4.1: the top 5 % of the training examples by influence score).
+//
+// Every example gets a 64-bit key  (order-preserving image of the fp32 score) << 32 | (2^32-1 - index);
+// keys are distinct and "larger key" is exactly "selected earlier".  Steps:
+//   1. build keys;  2. radix-select the k_sel-th largest key, 8 passes of 8 bits (histogram +
+//   one-workgroup digit pick);  3. compact all keys >= threshold (exactly k_sel of them);
+//   4. sort them descending with a bitonic network (LDS for spans up to 4096, global steps
+//   above);  5. decode indices and gather the scores.
+#include "common.h"
+
+namespace qless {
+
+constexpr int kSortBlock = 4096;   // keys sorted per workgroup in LDS (32 KB)
+
+struct TopkPlan {
+    int64_t padded;                // power of two >= k_sel (>= kSortBlock)
+    size_t off_keys, off_sel, off_hist, off_state, total;
+};
+
+static TopkPlan topk_plan(int64_t N, int64_t k_sel) {
+    TopkPlan p{};
+    int64_t pad = kSortBlock;
+    while (pad < k_sel) pad <<= 1;
+    p.padded = pad;
+    size_t o = 0;
+    p.off_keys = o;  o += (size_t)(N > 0 ? N : 1) * 8;
+    p.off_sel = o;   o += (size_t)pad * 8;
+    p.off_hist = o;  o += 256 * 4;
+    p.off_state = o; o += 64;
+    p.total = o;
+    return p;
+}
+
+struct SelectState {
+    unsigned long long prefix;     // high digits of the threshold found so far
+    unsigned long long remaining;  // rank still to locate inside the current prefix bucket
+    unsigned int count;            // compaction cursor
+    unsigned int pad;
+};
+
+__device__ inline uint32_t order_key(float f) {
+    if (f == 0.0f) f = 0.0f;                       // -0 and +0 compare equal
+    const uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__global__ void topk_keys_kernel(const float *score, int64_t N, unsigned long long *keys,
+                                 unsigned int *hist, SelectState *state, unsigned long long k_sel) {
+    const int64_t i0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i0 == 0) { state->prefix = 0; state->remaining = k_sel; state->count = 0; }
+    if (i0 < 256) hist[i0] = 0;
+    for (int64_t i = i0; i < N; i += (int64_t)gridDim.x * blockDim.x)
+        keys[i] = ((unsigned long long)order_key(score[i]) << 32) | (0xFFFFFFFFull - (unsigned long long)i);
+}
+
+// histogram of digit `pass` (0 = most significant byte) over keys whose higher digits equal prefix
+__global__ void __launch_bounds__(256)
+topk_hist_kernel(const unsigned long long *keys, int64_t N, int pass, const SelectState *state,
+                 unsigned int *hist) {
+    __shared__ unsigned int h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const unsigned long long prefix = state->prefix;
+    const int shift = 56 - 8 * pass;
+    // bits above the current digit: pass 0 has none (mask 0), later passes compare them all
+    const unsigned long long himask = pass == 0 ? 0ull : (~0ull << (shift + 8));
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const unsigned long long key = keys[i];
+        const bool match = ((key ^ prefix) & himask) == 0;
+        if (match) atomicAdd(&h[(key >> shift) & 0xFF], 1u);
+    }
+    __syncthreads();
+    if (h[threadIdx.x]) atomicAdd(&hist[threadIdx.x], h[threadIdx.x]);
+}
+
+// one workgroup: walk the 256 bins from the top, find the digit holding the remaining rank
+__global__ void __launch_bounds__(256)
+topk_pick_kernel(int pass, SelectState *state, unsigned int *hist) {
+    __shared__ unsigned int h[256];
+    h[threadIdx.x] = hist[threadIdx.x];
+    __syncthreads();
+    hist[threadIdx.x] = 0;                          // ready for the next pass
+    if (threadIdx.x == 0) {
+        unsigned long long rem = state->remaining;
+        const int shift = 56 - 8 * pass;
+        int d = 255;
+        if (rem > 0) {
+            for (; d > 0; --d) {
+                if (h[d] >= rem) break;
+                rem -= h[d];
+            }
+        }
+        state->prefix |= (unsigned long long)d << shift;
+        state->remaining = rem;
+    }
+}
+
+__global__ void topk_compact_kernel(const unsigned long long *keys, int64_t N, SelectState *state,
+                                    unsigned long long *sel, int64_t k_sel, int64_t padded) {
+    const unsigned long long thr = state->prefix;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < padded;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        if (i >= k_sel) sel[i] = 0;                 // padding sorts last (real keys are > 0)
+        if (i < N) {
+            const unsigned long long key = keys[i];
+            if (k_sel > 0 && key >= thr) {
+                const unsigned int pos = atomicAdd(&state->count, 1u);
+                if ((int64_t)pos < k_sel) sel[pos] = key;
+            }
+        }
+    }
+    // keys beyond `padded` (N > padded) are visited by a second loop
+    for (int64_t i = padded + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const unsigned long long key = keys[i];
+        if (k_sel > 0 && key >= thr) {
+            const unsigned int pos = atomicAdd(&state->count, 1u);
+            if ((int64_t)pos < k_sel) sel[pos] = key;
+        }
+    }
+}
+
+// Bitonic network, descending.  Stage size kk (sub-sequence length), step jj (partner distance).
+__device__ inline void cmpswap_desc(unsigned long long &x, unsigned long long &y, bool desc) {
+    if ((x < y) == desc) { const unsigned long long t = x; x = y; y = t; }
+}
+
+// all steps with jj < kSortBlock for stages kk_from..kk_to inside LDS
+__global__ void __launch_bounds__(1024)
+topk_bitonic_local_kernel(unsigned long long *data, int64_t kk_from, int64_t kk_to) {
+    __shared__ unsigned long long s[kSortBlock];
+    const int64_t base = (int64_t)blockIdx.x * kSortBlock;
+    for (int t = threadIdx.x; t < kSortBlock; t += 1024) s[t] = data[base + t];
+    __syncthreads();
+    for (int64_t kk = kk_from; kk <= kk_to; kk <<= 1) {
+        int64_t jj = kk >> 1;
+        if (jj >= kSortBlock) jj = kSortBlock >> 1;
+        for (; jj > 0; jj >>= 1) {
+            for (int t = threadIdx.x; t < kSortBlock / 2; t += 1024) {
+                const int lo = (int)(((int64_t)t / jj) * 2 * jj + ((int64_t)t % jj));
+                const int hi = lo + (int)jj;
+                const bool desc = (((base + lo) & kk) == 0);
+                unsigned long long x = s[lo], y = s[hi];
+                cmpswap_desc(x, y, desc);
+                s[lo] = x; s[hi] = y;
+            }
+            __syncthreads();
+        }
+    }
+    for (int t = threadIdx.x; t < kSortBlock; t += 1024) data[base + t] = s[t];
+}
+
+__global__ void topk_bitonic_global_kernel(unsigned long long *data, int64_t n, int64_t kk, int64_t jj) {
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n / 2;
+         t += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t lo = (t / jj) * 2 * jj + (t % jj), hi = lo + jj;
+        const bool desc = ((lo & kk) == 0);
+        unsigned long long x = data[lo], y = data[hi];
+        if ((x < y) == desc) { data[lo] = y; data[hi] = x; }
+    }
+}
+
+__global__ void topk_emit_kernel(const unsigned long long *sel, int64_t k_sel, const float *score,
+                                 int64_t N, int64_t *idx, float *val) {
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < k_sel;
+         t += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t i = (int64_t)(0xFFFFFFFFull - (sel[t] & 0xFFFFFFFFull));
+        idx[t] = i;
+        if (val) val[t] = score[i < N ? i : N - 1];
+    }
+}
+
+}  // namespace qless
+
+using namespace qless;
+
+extern "C" size_t qless_topk_workspace(int64_t N, int64_t k_sel) {
+    if (N < 0 || k_sel < 0) return 0;
+    return topk_plan(N, k_sel).total;
+}
+
+extern "C" qless_status qless_topk(const float *score, int64_t N, int64_t k_sel, int64_t *idx,
+                                   float *val, void *ws, size_t ws_bytes, void *stream) {
+    if (N < 0 || k_sel < 0 || k_sel > N) return QLESS_ERR_INVALID_ARG;
+    if (N > 0 && !score) return QLESS_ERR_INVALID_ARG;
+    if (k_sel > 0 && !idx) return QLESS_ERR_INVALID_ARG;
+    if (N >= ((int64_t)1 << 32)) return QLESS_ERR_UNSUPPORTED;
+    if (k_sel == 0) return QLESS_OK;
+    const TopkPlan p = topk_plan(N, k_sel);
+    if (!ws || ws_bytes < p.total) return QLESS_ERR_WORKSPACE;
+    if ((uintptr_t)ws % 8) return QLESS_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    unsigned char *w = (unsigned char *)ws;
+    unsigned long long *keys = (unsigned long long *)(w + p.off_keys);
+    unsigned long long *sel = (unsigned long long *)(w + p.off_sel);
+    unsigned int *hist = (unsigned int *)(w + p.off_hist);
+    SelectState *state = (SelectState *)(w + p.off_state);
+
+    auto blocks_for = [](int64_t n) { int64_t b = (n + 255) / 256; if (b < 1) b = 1; if (b > 2048) b = 2048; return (unsigned)b; };
+    hipLaunchKernelGGL(topk_keys_kernel, dim3(blocks_for(N)), dim3(256), 0, st, score, N, keys, hist, state,
+                       (unsigned long long)k_sel);
+    for (int pass = 0; pass < 8; ++pass) {
+        hipLaunchKernelGGL(topk_hist_kernel, dim3(blocks_for(N)), dim3(256), 0, st, keys, N, pass, state, hist);
+        hipLaunchKernelGGL(topk_pick_kernel, dim3(1), dim3(256), 0, st, pass, state, hist);
+    }
+    const int64_t span = N > p.padded ? N : p.padded;
+    hipLaunchKernelGGL(topk_compact_kernel, dim3(blocks_for(span)), dim3(256), 0, st, keys, N, state, sel, k_sel, p.padded);
+    // sort the selected keys, descending
+    const unsigned nblk = (unsigned)(p.padded / kSortBlock);
+    hipLaunchKernelGGL(topk_bitonic_local_kernel, dim3(nblk), dim3(1024), 0, st, sel, (int64_t)2, (int64_t)kSortBlock);
+    for (int64_t kk = 2 * kSortBlock; kk <= p.padded; kk <<= 1) {
+        for (int64_t jj = kk >> 1; jj >= kSortBlock; jj >>= 1)
+            hipLaunchKernelGGL(topk_bitonic_global_kernel, dim3(blocks_for(p.padded / 2)), dim3(256), 0, st, sel, p.padded, kk, jj);
+        hipLaunchKernelGGL(topk_bitonic_local_kernel, dim3(nblk), dim3(1024), 0, st, sel, kk, kk);
+    }
+    hipLaunchKernelGGL(topk_emit_kernel, dim3(blocks_for(k_sel)), dim3(256), 0, st, sel, k_sel, score, N, idx, val);
+    return launch_status();
+}

@@ -1,0 +1,205 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element, on seeded
+inputs that span several tiles and ragged tails.  Bars:
+  projection   per-vector relative L2 error <= 1e-2 (fp32-accumulated bf16 products)
+  codes        byte-identical to the oracle's canonical codes, from the same P
+  scores       bit-identical, from the same codes;   top-k indices identical
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_01703_amd import binding as Q
+from paper_2502_01703_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def _rel_l2(got, ref):
+    ref = ref.astype(np.float64)
+    num = np.linalg.norm(got.astype(np.float64) - ref, axis=1)
+    den = np.linalg.norm(ref, axis=1)
+    return num / np.maximum(den, 1e-300)
+
+
+# ---------------------------------------------------------------------------------- generator
+def test_generator_words_match_oracle_and_golden_file():
+    _say("generator words window 128x64, seeds 0 / 2^40+5")
+    for seed, m0, w0, salt in ((0, 0, 0, 0), ((1 << 40) + 5, 8000, 4194300, 0), (7, 3, 100, 1)):
+        got = Q.generator_words(seed, m0, 128, w0, 64, salt).cpu().numpy().view(np.uint32)
+        ref = np.array([[oracle.word(seed, m0 + r, (w0 + t) & 0xFFFFFFFF, salt) for t in range(64)]
+                        for r in range(128)], dtype=np.uint32)
+        np.testing.assert_array_equal(got, ref)
+    path = os.path.join(os.path.dirname(__file__), "golden", "generator_words.txt")
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        seed, m, w, salt, hx = line.split()
+        got = Q.generator_words(int(seed), int(m), 1, int(w), 1, int(salt)).cpu().numpy().view(np.uint32)
+        assert int(got[0, 0]) == int(hx, 16)
+
+
+# --------------------------------------------------------------------------------- projection
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("kind", [Q.RADEMACHER, Q.GAUSSIAN])
+@pytest.mark.parametrize("n,d,k", [(70, 5000, 576), (3, 333, 64), (130, 4099, 1088)])
+def test_projection_parity_ragged(dtype, kind, n, d, k):
+    _say("project n=%d d=%d k=%d kind=%d %s" % (n, d, k, kind, dtype))
+    g = torch.Generator().manual_seed(n * 1000 + d)
+    G = (torch.randn(n, d, generator=g) * torch.exp(torch.randn(n, 1, generator=g))).to(dtype)
+    ref = oracle.project(G, k, kind=kind, seed=42)
+    got = Q.project(G.to(DEV), k, kind=kind, seed=42).cpu().numpy()
+    err = _rel_l2(got, ref)
+    assert err.max() <= 1e-2, err.max()
+    if dtype == torch.bfloat16:
+        assert err.max() <= 1e-4          # exact products, fp32 sums: only summation rounding
+    rms = np.sqrt((ref.astype(np.float64) ** 2).mean(1, keepdims=True))
+    assert (np.abs(got - ref) <= 4e-2 * rms).all()
+
+
+def test_projection_config1_full_and_deterministic():
+    _say("project config 1: 1024 x 16384 -> 512, fp32, Rademacher seed 0")
+    train, val, planted = synth.config1()
+    ref = oracle.project(train, 512, seed=0)
+    Gd = train.to(DEV)
+    got = Q.project(Gd, 512, seed=0)
+    again = Q.project(Gd, 512, seed=0)
+    assert torch.equal(got, again)
+    err = _rel_l2(got.cpu().numpy(), ref)
+    assert err.max() <= 1e-2, err.max()
+    assert err.mean() <= 5e-3
+
+
+def test_projection_offset_slices_accumulate_and_strides():
+    _say("project slices with d_offset/accumulate, padded row stride, seed high bits")
+    g = torch.Generator().manual_seed(5)
+    n, d, k, a = 9, 1000, 128, 352
+    big = torch.randn(n, d + 24, generator=g).to(torch.bfloat16).to(DEV)
+    G = big[:, :d]                                    # row stride d + 24
+    seed = (9 << 32) + 1
+    ref = oracle.project(G.cpu().contiguous(), k, seed=seed)
+    whole = Q.project(G, k, seed=seed)
+    assert _rel_l2(whole.cpu().numpy(), ref).max() <= 1e-4
+    part = Q.project(G[:, :a], k, seed=seed)
+    Q.project(G[:, a:], k, seed=seed, d_offset=a, out=part, accumulate=True)
+    assert _rel_l2(part.cpu().numpy(), ref).max() <= 1e-4
+    # unaligned base pointer and odd stride take the element-wise load path
+    odd = torch.randn(n, d + 3, generator=g).to(torch.bfloat16).to(DEV)[:, 1:d + 1]
+    ref2 = oracle.project(odd.cpu().contiguous(), k, seed=3)
+    assert _rel_l2(Q.project(odd, k, seed=3).cpu().numpy(), ref2).max() <= 1e-4
+    # empty inputs
+    z = Q.project(torch.zeros(4, 0, dtype=torch.bfloat16, device=DEV), 64)
+    assert z.shape == (4, 64) and float(z.abs().max()) == 0.0
+    assert Q.project(torch.zeros(0, 64, dtype=torch.bfloat16, device=DEV), 64).shape == (0, 64)
+
+
+# --------------------------------------------------------------------------------- quantiser
+@pytest.mark.parametrize("bits", [8, 4, 2, 1])
+@pytest.mark.parametrize("n,k", [(37, 8192), (5, 64), (19, 576), (3, 16384), (2, 32768)])
+def test_quantize_codes_identical(bits, n, k):
+    _say("quantize bits=%d n=%d k=%d" % (bits, n, k))
+    g = torch.Generator().manual_seed(bits * 100 + n)
+    P = torch.randn(n, k, generator=g) * torch.exp(2 * torch.randn(n, 1, generator=g))
+    P[0, : k // 2] = 0.0
+    if n > 2:
+        P[1] = 0.0                                   # all-zero row
+        P[2, 0] = -0.0
+    codes, S, rn = oracle.quantize(P.numpy(), bits)
+    gc, gS, grn = Q.quantize(P.to(DEV), bits)
+    np.testing.assert_array_equal(gc.cpu().numpy(), codes)
+    np.testing.assert_array_equal(gS.cpu().numpy(), S)
+    np.testing.assert_array_equal(grn.cpu().numpy(), rn)
+
+
+def test_quantize_strided_rows_and_literal_formula_boundary_rate():
+    _say("quantize strided P; canonical-vs-literal mismatch rate")
+    g = torch.Generator().manual_seed(77)
+    big = torch.randn(33, 2048 + 5, generator=g).to(DEV)
+    P = big[:, 1:2049]                               # unaligned base, odd stride
+    for bits in (8, 4, 2, 1):
+        codes, S, rn = oracle.quantize(P.cpu().contiguous().numpy(), bits)
+        gc, gS, grn = Q.quantize(P, bits)
+        np.testing.assert_array_equal(gc.cpu().numpy(), codes)
+        np.testing.assert_array_equal(grn.cpu().numpy(), rn)
+    # vs the paper's real-number formula evaluated in fp64: <= 1e-4 of entries, off by one
+    P2 = torch.randn(64, 8192, generator=g)
+    for bits in (8, 4, 2):
+        gq = oracle.unpack(Q.quantize(P2.to(DEV), bits)[0].cpu().numpy(), 8192, bits)
+        lit, _ = oracle.quantize_unpacked(P2.numpy(), bits, literal=True)
+        diff = gq != lit
+        assert diff.mean() <= 1e-4
+        if diff.any():
+            assert np.abs(gq.astype(int) - lit.astype(int)).max() == 1
+
+
+# ------------------------------------------------------------------------------------ scoring
+def _datastore(n, k, bits, C, seed):
+    rng = np.random.default_rng(seed)
+    out = [oracle.quantize((rng.standard_normal((n, k)) *
+                            np.exp(rng.standard_normal((n, 1)))).astype(np.float32), bits)
+           for _ in range(C)]
+    return [o[0] for o in out], [o[2] for o in out]
+
+
+@pytest.mark.parametrize("bits", [8, 4, 2, 1])
+@pytest.mark.parametrize("N,M,k,C", [(300, 70, 576, 3), (257, 1, 64, 1), (129, 8, 1024, 2),
+                                     (64, 33, 8192, 4), (1000, 130, 2048, 2)])
+def test_score_bit_exact(bits, N, M, k, C):
+    _say("score bits=%d N=%d M=%d k=%d C=%d" % (bits, N, M, k, C))
+    tc, tr = _datastore(N, k, bits, C, 1000 + bits)
+    vc, vr = _datastore(M, k, bits, C, 2000 + bits)
+    if bits > 1:
+        tc[0][5] = 0
+        tr[0][5] = 0.0                                 # an all-zero code vector scores 0
+    eta = [1.0, 0.75, 0.5, 0.25][:C]
+    ref_s, ref_f = oracle.score(tc, tr, vc, vr, eta, k, bits, want_full=True)
+    dev = lambda arrs: [torch.from_numpy(a).to(DEV) for a in arrs]
+    s, f = Q.score(dev(tc), dev(tr), dev(vc), dev(vr), eta, k, bits, want_full=True)
+    np.testing.assert_array_equal(f.cpu().numpy().view(np.uint32), ref_f.view(np.uint32))
+    np.testing.assert_array_equal(s.cpu().numpy().view(np.uint32), ref_s.view(np.uint32))
+    only = Q.score(dev(tc), dev(tr), dev(vc), dev(vr), eta, k, bits)
+    assert torch.equal(only, s)
+
+
+# -------------------------------------------------------------------------------------- top-k
+@pytest.mark.parametrize("N,k_sel", [(1000, 50), (100000, 5000), (100000, 20000), (5000, 5000),
+                                     (4097, 4097), (7, 0), (1, 1), (270000, 13500)])
+def test_topk_identical_with_ties(N, k_sel):
+    _say("topk N=%d k_sel=%d" % (N, k_sel))
+    rng = np.random.default_rng(N + k_sel)
+    s = (rng.integers(-2000, 2000, size=N) / 1024.0).astype(np.float32)      # heavy ties
+    s[rng.integers(0, N, size=max(1, N // 50))] = -0.0
+    s[rng.integers(0, N, size=max(1, N // 50))] = 0.0
+    ref_i, ref_v = oracle.topk(s, k_sel)
+    idx, val = Q.topk(torch.from_numpy(s).to(DEV), k_sel)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ref_i)
+    np.testing.assert_array_equal(val.cpu().numpy().view(np.uint32), ref_v.view(np.uint32))
+
+
+# --------------------------------------------------------------------------------- end to end
+def test_config1_end_to_end_planted_recovery():
+    _say("config 1 end to end on the GPU: project -> quantize(8) -> score -> top-50")
+    train, val, planted = synth.config1()
+    tP = Q.project(train.to(DEV), 512, seed=0)
+    vP = Q.project(val.to(DEV), 512, seed=0)
+    for bits, need in ((8, 32), (1, 30)):
+        tc, _, tr = Q.quantize(tP, bits)
+        vc, _, vr = Q.quantize(vP, bits)
+        sc = Q.score([tc], [tr], [vc], [vr], [1.0], 512, bits)
+        idx, _ = Q.topk(sc, 50)
+        hit = len(set(idx.cpu().tolist()) & set(planted.tolist()))
+        assert hit >= need, (bits, hit)
+        # stage-wise parity on the GPU's own intermediate results
+        oc, _, orn = oracle.quantize(tP.cpu().numpy(), bits)
+        np.testing.assert_array_equal(tc.cpu().numpy(), oc)
+        ovc, _, ovr = oracle.quantize(vP.cpu().numpy(), bits)
+        osc = oracle.score([oc], [orn], [ovc], [ovr], [1.0], 512, bits)
+        np.testing.assert_array_equal(sc.cpu().numpy().view(np.uint32), osc.view(np.uint32))
+        np.testing.assert_array_equal(idx.cpu().numpy(), oracle.topk(osc, 50)[0])

@@ -1,0 +1,83 @@
+"""Host-side checks of the HIP library that need no GPU: it loads, exports every symbol the
+header declares, and refuses bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2502_01703_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, INVALID, UNSUPPORTED, WORKSPACE = 0, 1, 2, 3
+
+
+def test_header_symbols_are_all_exported():
+    text = open(os.path.join(ROOT, "include", "qless.h")).read()
+    declared = set(re.findall(r"\b(qless_[a-z_]+)\s*\(", text))
+    assert declared == set(binding.EXPORTS)
+    L = binding.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_status_strings():
+    L = binding.lib()
+    names = [L.qless_status_string(i).decode() for i in range(5)]
+    assert names[0] == "ok" and len(set(names)) == 5
+
+
+def test_project_argument_validation():
+    L = binding.lib()
+    one = ctypes.c_void_p(16)       # never dereferenced: every call below must fail validation first
+    f = L.qless_project
+    assert f(one, 1, -1, 64, 64, 0, 64, 0, 0, 0, one, 64, one, 1 << 30, None) == INVALID
+    assert f(one, 1, 4, 64, 32, 0, 64, 0, 0, 0, one, 64, one, 1 << 30, None) == INVALID      # ldG < d
+    assert f(one, 1, 4, 64, 64, 0, 64, 0, 0, 0, one, 32, one, 1 << 30, None) == INVALID      # ldP < k
+    assert f(None, 1, 4, 64, 64, 0, 64, 0, 0, 0, one, 64, one, 1 << 30, None) == INVALID
+    assert f(one, 1, 4, 64, 64, 0, 100, 0, 0, 0, one, 100, one, 1 << 30, None) == UNSUPPORTED  # k % 64
+    assert f(one, 1, 4, 64, 64, 8, 64, 0, 0, 0, one, 64, one, 1 << 30, None) == UNSUPPORTED    # offset % 32
+    assert f(one, 7, 4, 64, 64, 0, 64, 0, 0, 0, one, 64, one, 1 << 30, None) == UNSUPPORTED    # dtype
+    assert f(one, 1, 4, 64, 64, 0, 64, 5, 0, 0, one, 64, one, 1 << 30, None) == UNSUPPORTED    # kind
+    need = L.qless_project_workspace(4, 64, 64)
+    assert need == 4 * 64 * 4
+    assert f(one, 1, 4, 64, 64, 0, 64, 0, 0, 0, one, 64, one, need - 1, None) == WORKSPACE
+    assert f(one, 1, 4, 64, 64, 0, 64, 0, 0, 0, one, 64, None, 0, None) == WORKSPACE
+    assert f(one, 1, 0, 64, 64, 0, 64, 0, 0, 0, None, 64, None, 0, None) == OK                # n = 0
+
+
+def test_quantize_score_topk_argument_validation():
+    L = binding.lib()
+    one = ctypes.c_void_p(16)
+    q = L.qless_quantize
+    assert q(one, 64, 4, 64, 3, one, one, one, None) == UNSUPPORTED
+    assert q(one, 96, 4, 96, 8, one, one, one, None) == UNSUPPORTED
+    assert q(one, 32, 4, 64, 8, one, one, one, None) == INVALID
+    assert q(None, 64, 4, 64, 8, one, one, one, None) == INVALID
+    assert q(None, 64, 0, 64, 8, None, None, None, None) == OK
+    ptrs = (ctypes.c_void_p * 1)(16)
+    eta = (ctypes.c_float * 1)(1.0)
+    s = L.qless_score
+    args = lambda C=1, N=4, M=2, k=64, bits=8, score=one, full=None: (
+        ptrs, ptrs, ptrs, ptrs, ctypes.cast(eta, ctypes.c_void_p), C, N, M, k, bits, score, full, None, 0, None)
+    assert s(*args(C=0)) == INVALID
+    assert s(*args(C=17)) == UNSUPPORTED
+    assert s(*args(M=0)) == INVALID
+    assert s(*args(bits=3)) == UNSUPPORTED
+    assert s(*args(k=100)) == UNSUPPORTED
+    assert s(*args(score=None)) == INVALID
+    assert s(*args(N=0)) == OK
+    bad = (ctypes.c_void_p * 1)(8)           # codes must be 16-byte aligned
+    assert s(bad, ptrs, ptrs, ptrs, ctypes.cast(eta, ctypes.c_void_p), 1, 4, 2, 64, 8, one, None, None, 0, None) == INVALID
+    t = L.qless_topk
+    assert t(one, 10, 11, one, None, one, 1 << 20, None) == INVALID
+    assert t(one, 10, -1, one, None, one, 1 << 20, None) == INVALID
+    assert t(one, 10, 5, one, None, one, 8, None) == WORKSPACE
+    assert t(one, 10, 0, None, None, None, 0, None) == OK
+    assert L.qless_topk_workspace(270000, 13500) >= 270000 * 8 + 16384 * 8
+
+
+def test_gaussian_table_matches_the_oracle_table():
+    import oracle
+    np.testing.assert_array_equal(binding.gaussian_table().numpy().astype(np.float64), oracle.gauss_table())
