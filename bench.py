@@ -1,0 +1,249 @@
+#!/usr/bin/env python3
+"""Benchmark of the QLESS hot path on one MI355X.
+
+A step streams one batch of 64 training examples through the whole path at the 7B-class LoRA
+shape: for each of C = 4 checkpoints the [64, 2^27] bf16 gradient batch is projected to
+k = 8192 (Rademacher) and quantised to 1 bit into the datastore; the 64 new rows are scored
+against the resident validation datastore (M = 512, 4 checkpoints, max over validation) and
+the top 5 % of the N = 65536 running score vector is selected.  Inputs are synthetic and
+resident in HBM before the timed region.
+
+value = projected+quantised gradient vectors per second over the whole step.  The same run also
+times the scoring-only workload (N = 270000, M = 1024, k = 8192, C = 4, 1-bit) and the CPU oracle
+on a bounded sample; both are reported on the same JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "projected+quantised grads/sec (d=134M,k=8192) and train×val scores/sec, 1-bit"
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--bits", type=int, default=1, choices=[1, 2, 4, 8])
+    ap.add_argument("--d-log2", type=int, default=27, help="gradient dimension 2^x (27 = the metric's shape)")
+    ap.add_argument("--skip-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--skip-scoring", action="store_true", help="skip the scoring-only leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for profiler byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no collectives on the path); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2502_01703_amd import binding as Q
+    from paper_2502_01703_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    Q.lib()
+
+    n, d, k, C, M, N, bits = 64, 1 << args.d_log2, 8192, 4, 512, 65536, args.bits
+    k_sel = int(0.05 * N)
+    eta = [1.0, 0.75, 0.5, 0.25]
+
+    # ---------------------------------------------------------------- resident synthetic inputs
+    t0 = time.time()
+    G = []
+    for c in range(C):
+        g, _ = synth.student_t_gradients(n, d, seed=3000 + c, device=dev, dtype=torch.bfloat16)
+        G.append(g)
+    torch.cuda.synchronize()
+    log("gradients: %d x [%d, 2^%d] bf16 = %.1f GiB resident (%.1f s)" %
+        (C, n, args.d_log2, C * n * d * 2 / 2 ** 30, time.time() - t0))
+
+    def synthetic_store(rows, seed, sbits):
+        codes, rnorm = [], []
+        for c in range(C):
+            cc = torch.empty(rows, Q.code_bytes(k, sbits), dtype=torch.uint8, device=dev)
+            rr = torch.empty(rows, dtype=torch.float32, device=dev)
+            ss = torch.empty(rows, dtype=torch.float32, device=dev)
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(seed + c)
+            for r0 in range(0, rows, 16384):
+                r1 = min(rows, r0 + 16384)
+                P = torch.randn(r1 - r0, k, generator=gen, device=dev)
+                Q.quantize(P, sbits, codes=cc[r0:r1], S=ss[r0:r1], rnorm=rr[r0:r1])
+            codes.append(cc)
+            rnorm.append(rr)
+        return codes, rnorm
+
+    train_codes, train_rnorm = synthetic_store(N, 10, bits)
+    val_codes, val_rnorm = synthetic_store(M, 20, bits)
+    train_S = [torch.empty(N, dtype=torch.float32, device=dev) for _ in range(C)]
+    score = torch.zeros(N, dtype=torch.float32, device=dev)
+    Q.score(train_codes, train_rnorm, val_codes, val_rnorm, eta, k, bits, score_out=score)
+    P = torch.empty(n, k, dtype=torch.float32, device=dev)
+    ws_proj = torch.empty(max(Q.project_workspace(n, d, k), 16), dtype=torch.uint8, device=dev)
+    ws_topk = torch.empty(max(Q.topk_workspace(N, k_sel), 16), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)       # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    proj_events = []
+
+    def step(i, timed):
+        b = (i * n) % N
+        for c in range(C):
+            if timed:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+            Q.project(G[c], k, kind=Q.RADEMACHER, seed=0, out=P, ws=ws_proj)
+            if timed:
+                e1.record()
+                proj_events.append((e0, e1))
+            Q.quantize(P, bits, codes=train_codes[c][b:b + n], S=train_S[c][b:b + n],
+                       rnorm=train_rnorm[c][b:b + n])
+        Q.score([t[b:b + n] for t in train_codes], [t[b:b + n] for t in train_rnorm], val_codes,
+                val_rnorm, eta, k, bits, score_out=score[b:b + n])
+        return Q.topk(score, k_sel, ws=ws_topk)
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / max(args.steps, 1)
+    grads_per_s = n * C / (ms_per_step * 1e-3)
+    proj_ms = sum(a.elapsed_time(b) for a, b in proj_events) / max(len(proj_events), 1)
+    flops = 2.0 * n * d * k
+    achieved = flops / (proj_ms * 1e-3) / 1e12 if proj_ms > 0 else 0.0
+    log("step %.2f ms; projection launch %.3f ms = %.1f TFLOP/s" % (ms_per_step, proj_ms, achieved))
+
+    traffic = None
+    tp = os.path.join(ROOT, "profiles", "project_kernel_c3_traffic.json")
+    if os.path.exists(tp) and args.d_log2 == 27:
+        try:
+            traffic = json.load(open(tp)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+    roofline = {"kernel": "project_kernel", "bound": "mfma", "achieved": round(achieved, 2),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "traffic": traffic, "flops_per_launch": flops, "avg_launch_ms": round(proj_ms, 4)}
+
+    # ------------------------------------------------------------- scoring-only leg (1-bit, 270K x 1024)
+    extra = {}
+    if not args.skip_scoring:
+        del train_codes, train_rnorm
+        N4, M4 = 270000, 1024
+        for sb in (1, 8):
+            cbb = Q.code_bytes(k, sb)
+            tc4, tr4 = synthetic_store(N4, 40, sb)
+            vc4, vr4 = synthetic_store(M4, 50, sb)
+            sc4 = torch.empty(N4, dtype=torch.float32, device=dev)
+            ws4 = torch.empty(max(Q.topk_workspace(N4, 13500), 16), dtype=torch.uint8, device=dev)
+            Q.score(tc4, tr4, vc4, vr4, eta, k, sb, score_out=sc4)
+            torch.cuda.synchronize()
+            reps = 3
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            e[0].record()
+            for _ in range(reps):
+                Q.score(tc4, tr4, vc4, vr4, eta, k, sb, score_out=sc4)
+            e[1].record()
+            for _ in range(reps):
+                Q.topk(sc4, 13500, ws=ws4)
+            e[2].record()
+            torch.cuda.synchronize()
+            ts = e[0].elapsed_time(e[1]) / reps
+            tt = e[1].elapsed_time(e[2]) / reps
+            bytes_alg = C * (N4 + M4) * cbb + 4 * (N4 + M4) * C + 4 * N4
+            extra["score_%dbit" % sb] = {
+                "workload": "N=270000 M=1024 k=8192 C=4", "ms": round(ts, 3),
+                "pair_scores_per_s": round(N4 * M4 / (ts * 1e-3), 1),
+                "dots_per_s": round(N4 * M4 * C / (ts * 1e-3), 1),
+                "hbm_frac": round(bytes_alg / (ts * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                "topk_13500_ms": round(tt, 3)}
+            log("score %d-bit 270000x1024x4: %.2f ms (%.3g pair scores/s), topk %.3f ms" %
+                (sb, ts, N4 * M4 / (ts * 1e-3), tt))
+            del tc4, tr4, vc4, vr4
+        # quantise throughput at the datastore size (HBM-bound kernel)
+        Pq = torch.randn(32768, k, device=dev)
+        cq = torch.empty(32768, Q.code_bytes(k, 1), dtype=torch.uint8, device=dev)
+        sq = torch.empty(32768, dtype=torch.float32, device=dev)
+        rq = torch.empty(32768, dtype=torch.float32, device=dev)
+        Q.quantize(Pq, 1, codes=cq, S=sq, rnorm=rq)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            Q.quantize(Pq, 1, codes=cq, S=sq, rnorm=rq)
+        e1.record()
+        torch.cuda.synchronize()
+        tq = e0.elapsed_time(e1) / 5
+        qbytes = 32768 * (4 * k + k // 8 + 8)
+        extra["quantize_1bit"] = {"workload": "n=32768 k=8192", "ms": round(tq, 3),
+                                  "vectors_per_s": round(32768 / (tq * 1e-3), 1),
+                                  "GBps": round(qbytes / (tq * 1e-3) / 1e9, 1),
+                                  "hbm_frac": round(qbytes / (tq * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+        log("quantize 1-bit 32768x8192: %.3f ms = %.0f GB/s" % (tq, qbytes / (tq * 1e-3) / 1e9))
+
+    # ----------------------------------------------------------------- CPU oracle on a bounded sample
+    cpu = None
+    if not args.skip_cpu:
+        import numpy as np
+        import oracle
+        rows = list(range(0, k, 32))                       # 256 of the 8192 output coordinates
+        g0 = G[0][0:1].cpu()
+        t0 = time.perf_counter()
+        oracle.project_rows(g0, rows, seed=0)
+        t_proj = (time.perf_counter() - t0) * (k / len(rows))     # one gradient, all k coordinates
+        Ps = np.random.default_rng(0).standard_normal((n, k)).astype(np.float32)
+        t0 = time.perf_counter()
+        oc, _, orn = oracle.quantize(Ps, bits)
+        t_quant = time.perf_counter() - t0
+        vcs = [v.cpu().numpy() for v in val_codes]
+        vrs = [v.cpu().numpy() for v in val_rnorm]
+        t0 = time.perf_counter()
+        oracle.score([oc] * C, [orn] * C, vcs, vrs, eta, k, bits)
+        t_score = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oracle.topk(score.cpu().numpy(), k_sel)
+        t_topk = time.perf_counter() - t0
+        t_step_cpu = n * C * t_proj + C * t_quant + t_score + t_topk
+        cpu = {"value": round(n * C / t_step_cpu, 6), "unit": "grads/s", "cores": oracle.num_threads(),
+               "kind": "oracle",
+               "sample": "projection: 1 gradient (d=2^%d) x 256 of 8192 output coordinates, scaled x32; "
+                         "quantise 64x8192; score 64x512x4; top-k over 65536" % args.d_log2,
+               "seconds": {"project_per_gradient": round(t_proj, 3), "quantize_64": round(t_quant, 4),
+                           "score_64x512x4": round(t_score, 4), "topk": round(t_topk, 4)}}
+        log("oracle: %.1f s per projected gradient on %d threads" % (t_proj, cpu["cores"]))
+
+    out = {"metric": METRIC, "value": round(grads_per_s, 2), "unit": "grads/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+           "data": "synthetic",
+           "config": {"workload": "7B-class LoRA shape: d=2^%d bf16, batch n=64, k=8192 Rademacher, C=4 "
+                                  "checkpoints, %d-bit datastore, N=65536, M=512, top 5%%" % (args.d_log2, bits),
+                      "step": "4 x (project+quantize 64 gradients) + score 64x512x4 + top-3276 of 65536"},
+           "roofline": roofline, "cpu_baseline": cpu, "extra": extra}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
