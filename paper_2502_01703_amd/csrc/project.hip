@@ -23,7 +23,7 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kTileRows = 64;                  // batch rows per workgroup
-constexpr int kWaves = 4;
+constexpr int kWaves = 8;
 constexpr int kWaveCols = 128;                 // projected coordinates per wave
 constexpr int kTileCols = kWaves * kWaveCols;  // 512 per workgroup
 constexpr int kStageD = 128;                   // gradient columns per LDS stage
@@ -42,7 +42,7 @@ static ProjectPlan make_plan(int64_t n, int64_t d_len, int32_t k) {
     int64_t stages = (d_len + kStageD - 1) / kStageD;
     if (n <= 0 || d_len <= 0) { p.nsplit = 0; p.ws_bytes = 0; return p; }
     int64_t tiles = p.ntiles * p.ktiles;
-    int64_t want = (512 + tiles - 1) / tiles;          // about two workgroups per CU
+    int64_t want = (2048 / kWaves + tiles - 1) / tiles;   // about eight waves per CU
     if (want > stages) want = stages;
     if (want < 1) want = 1;
     p.stages_per_split = (stages + want - 1) / want;
@@ -110,7 +110,7 @@ __device__ inline uint4 load_chunk(const ProjectArgs &a, int64_t row, int64_t co
 union Frag { bf16x8 v; bf16x2 p[4]; uint4 u; uint32_t w[4]; };
 
 template <bool IN_F32, bool ALIGNED, bool GAUSS>
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(kWaves * 64, 2)
 project_kernel(ProjectArgs a, GaussTable gt) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // XCD-aware decode: consecutive workgroup ids land on different XCDs, so the ktiles
@@ -133,7 +133,7 @@ project_kernel(ProjectArgs a, GaussTable gt) {
     const int nstages = (int)((c_end - c_begin + kStageD - 1) / kStageD);
 
     uint16_t *gtab = (uint16_t *)(smem + 2 * kStageBytes);
-    if (GAUSS) { gtab[tid] = gt.v[tid]; }
+    if (GAUSS && tid < 256) { gtab[tid] = gt.v[tid]; }
 
     // row keys of this lane's four 32-row blocks
     const int mbase = kt * kTileCols + wave * kWaveCols;
@@ -155,21 +155,23 @@ project_kernel(ProjectArgs a, GaussTable gt) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[nb][kb][v] = 0.0f;
 
-    // staging: 64 rows x 16 chunks of 8 columns; thread handles chunks tid + 256*i
-    uint4 stage_regs[4];
+    // staging: 64 rows x 16 chunks of 8 columns; thread handles chunks tid + kThreads*i
+    constexpr int kThreads = kWaves * 64;
+    constexpr int kChunksPerThread = kTileRows * (kStageD / 8) / kThreads;
+    uint4 stage_regs[kChunksPerThread];
     auto fetch = [&](int s) {
         const int64_t cs = c_begin + (int64_t)s * kStageD;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int c = tid + 256 * i;
+        for (int i = 0; i < kChunksPerThread; ++i) {
+            int c = tid + kThreads * i;
             int r = c >> 4, cc = c & 15;
             stage_regs[i] = load_chunk<IN_F32, ALIGNED>(a, row0 + r, cs + cc * 8, c_end);
         }
     };
     auto commit = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int c = tid + 256 * i;
+        for (int i = 0; i < kChunksPerThread; ++i) {
+            int c = tid + kThreads * i;
             int r = c >> 4, cc = c & 15;
             *(uint4 *)(smem + buf * kStageBytes + r * kLdsStride + cc * 16) = stage_regs[i];
         }
@@ -198,7 +200,7 @@ project_kernel(ProjectArgs a, GaussTable gt) {
             const uint32_t wpair = wstage + 2u * bp;             // word index of lanes 0..31
 #pragma unroll
             for (int kb = 0; kb < 4; ++kb) {
-                if (!live[kb]) continue;
+                // row blocks past k (last k-tile only) are computed and dropped in the epilogue
                 if (!GAUSS) {
                     const uint32_t h = key_word(key[kb], wpair * kGold);
 #pragma unroll
@@ -314,7 +316,7 @@ extern "C" qless_status qless_project(const void *G, qless_dtype dt, int64_t n, 
         const size_t esz = dt == QLESS_F32 ? 4 : 2;
         const bool aligned = ((uintptr_t)G % 16 == 0) && ((ldG * esz) % 16 == 0);
         const size_t lds = 2 * kStageBytes + 512;
-        dim3 grid((unsigned)plan.grid), block(256);
+        dim3 grid((unsigned)plan.grid), block(kWaves * 64);
 #define QLESS_LAUNCH(F32, AL, GA) \
         hipLaunchKernelGGL((project_kernel<F32, AL, GA>), grid, block, lds, st, a, gt)
         if (dt == QLESS_F32) {
