@@ -137,13 +137,12 @@ def main():
     achieved = flops / (proj_ms * 1e-3) / 1e12 if proj_ms > 0 else 0.0
     log("step %.2f ms; projection launch %.3f ms = %.1f TFLOP/s" % (ms_per_step, proj_ms, achieved))
 
-    traffic = None
-    tp = os.path.join(ROOT, "profiles", "project_kernel_c3_traffic.json")
+    traffic = None      # HBM bytes per launch from the committed rocprofv3 --pmc summary
+    tp = os.path.join(ROOT, "profiles", "project_kernel_c3_hbm_traffic.txt")
     if os.path.exists(tp) and args.d_log2 == 27:
-        try:
-            traffic = json.load(open(tp)).get("hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
+        for line in open(tp):
+            if line.startswith("hbm_bytes_per_launch"):
+                traffic = int(line.split("=")[1])
     roofline = {"kernel": "project_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                 "traffic": traffic, "flops_per_launch": flops, "avg_launch_ms": round(proj_ms, 4)}
