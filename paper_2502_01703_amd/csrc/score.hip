@@ -202,168 +202,389 @@ score_popcount_kernel(ScoreArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// 8-bit / 4-bit: int8 MFMA kernel.  Workgroup tile 256 train rows x 64 val rows; each of the
-// four waves owns 64 x 64 as 2 x 2 accumulators of 32 x 32.
+// 8-bit / 4-bit / 1-bit at large M: int8 MFMA kernel.
+//
+// A small pre-pass expands the validation codes of every checkpoint to int8 rows (padded to the
+// tile size, in the K order in which the train operand is unpacked) together with
+// w'[c][z'] = eta_c * rnorm'_c(z') and, for 1-bit, vsum = sum of the +-1 codes of the row.
+// The main kernel runs one workgroup of 8 waves per (256 train rows) x (128 val rows) tile, each
+// wave 64 x 64 as 2 x 2 accumulators of v_mfma_i32_32x32x32_i8.  Train operands are unpacked in
+// registers on their way from LDS to the MFMA:
+//   8-bit  bytes as stored
+//   4-bit  (w<<4)&0xF0F0F0F0 and w&0xF0F0F0F0: bytes 16 q (even / odd elements); acc = 16 D
+//   1-bit  (w>>j)&0x01010101, j = 0..7: bytes a in {0,1} (1 = negative); D = vsum - 2 sum a v
+// Workgroups of the same train tile get ids 8 apart, so they run on one XCD and share the train
+// rows through its L2; the row maximum over val tiles is combined with an order-preserving
+// integer atomicMax (exact, order independent) and decoded by a last small kernel.
 // ------------------------------------------------------------------------------------------
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(16))) int i32x16;
 
+constexpr int kMT = 256, kMV = 128;            // train / val rows per workgroup tile
+
+__host__ __device__ constexpr int mfma_stage_elems(int) { return 128; }
+
+struct ScorePrep {                             // workspace views (device pointers)
+    int8_t *vexp;                              // [C][Mp][kp]
+    float *vw;                                 // [C][Mp]
+    int *vsum;                                 // [C][Mp]
+    unsigned int *smax;                        // [N] order-preserving keys of the row maxima
+    int32_t Mp, kp;
+};
+
+__device__ inline unsigned int f32_order_key(float f) {
+    const unsigned int u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ inline float f32_from_order_key(unsigned int k) {
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+
+// position p (0..kp) of an expanded val row -> element index of the code vector
+template <int BITS>
+__device__ inline int val_source_element(int p) {
+    if (BITS == 8) return p;
+    if (BITS == 4) {
+        // inside a half K-step of 16: [0,2,4,6,1,3,5,7,8,10,12,14,9,11,13,15]
+        const int i = p & 15, base = p & ~15;
+        const int d = i >> 2, b = i & 3;               // dword d, byte b
+        return base + 8 * (d >> 1) + 2 * b + (d & 1);
+    }
+    // 1-bit: K-step pair g (64 elements), step s, half h, dword jj, byte b
+    const int g = p >> 6, s = (p >> 5) & 1, h = (p >> 4) & 1, jj = (p >> 2) & 3, b = p & 3;
+    return 64 * g + 32 * h + 8 * b + 4 * s + jj;
+}
+
 template <int BITS>
 __global__ void __launch_bounds__(256)
-score_mfma_kernel(ScoreArgs a) {
-    constexpr int TN = 256, TM = 64, ROWS = TN + TM;
-    constexpr int KE = BITS == 8 ? 64 : 128;        // code elements per stage
-    constexpr int SB = KE * BITS / 8;               // stage bytes per row: 64
-    constexpr int STRIDE = SB + 16;
-    constexpr int CHUNKS = ROWS * (SB / 16);        // 16-byte chunks per stage
-    constexpr int CPT = (CHUNKS + 255) / 256;
+score_prepare_kernel(ScoreArgs a, ScorePrep w) {
+    const int row = blockIdx.x, ci = blockIdx.y;        // row < Mp
+    int8_t *dst = w.vexp + ((size_t)ci * w.Mp + row) * (size_t)w.kp;
+    const bool live = row < a.M;
+    const unsigned char *src = a.vc[ci] + (int64_t)(live ? row : 0) * ((int64_t)a.k * BITS / 8);
+    int part = 0;
+    for (int p = threadIdx.x; p < w.kp; p += 256) {
+        int q = 0;
+        if (live && p < a.k) {
+            const int m = val_source_element<BITS>(p);
+            if (BITS == 8) q = (int8_t)src[m];
+            else if (BITS == 4) { q = (src[m >> 1] >> (4 * (m & 1))) & 0xF; if (q & 8) q -= 16; }
+            else q = ((src[m >> 3] >> (m & 7)) & 1) ? -1 : 1;
+        }
+        dst[p] = (int8_t)q;
+        part += q;
+    }
+    __shared__ int s_part[4];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+    if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = part;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        w.vsum[ci * w.Mp + row] = s_part[0] + s_part[1] + s_part[2] + s_part[3];
+        w.vw[ci * w.Mp + row] = live ? __fmul_rn(a.eta[ci], a.vr[ci][row]) : 0.0f;
+    }
+    // the row-maximum keys start below every finite score
+    if (ci == 0) {
+        const int64_t per = (a.N + gridDim.x - 1) / gridDim.x;
+        const int64_t lo = (int64_t)row * per;
+        for (int64_t i = lo + threadIdx.x; i < lo + per && i < a.N; i += 256) w.smax[i] = 0u;
+    }
+}
+
+__global__ void score_finish_kernel(const unsigned int *smax, int64_t N, float *score) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N;
+         i += (int64_t)gridDim.x * blockDim.x)
+        score[i] = f32_from_order_key(smax[i]);
+}
+
+// Asynchronous 16-byte global -> LDS copy (no VGPR staging): lane L of the wavefront writes
+// LDS bytes [lds_addr + 16 L, +16) with the 16 bytes at its own global address.  lds_addr must be
+// wave-uniform.  Completion is tracked by vmcnt like any vector load.
+__device__ inline void global_to_lds16(const void *gptr, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(lds_addr), "v"(gptr) : "memory");
+}
+template <int N> __device__ inline void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+template <int BITS>
+__global__ void __launch_bounds__(512, 2)
+score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
+    constexpr int KE = 128;                         // code elements per stage
+    constexpr int TB = KE * BITS / 8;               // train bytes per row per stage: 128 / 64 / 16
+    constexpr int TCPR = TB / 16;                   // 16-byte chunks per train row
+    constexpr int TRAIN_BYTES = kMT * TB, VAL_BYTES = kMV * KE;
+    constexpr int TCH = kMT * TCPR, VCH = kMV * (KE / 16);
+    constexpr int NINST = (TCH + VCH) / 64;         // wavefront-wide copies per stage: 48 / 32 / 20
+    constexpr int LPW = (NINST + 7) / 8;            // per wave: 6 / 4 / 3
+    constexpr int BUF = TRAIN_BYTES + VAL_BYTES + 1024;   // + 1 KB landing zone for padding copies
+    constexpr int NBUF = BITS == 8 ? 3 : 4;         // LDS ring: 3 x 49 KB, 4 x 33 KB, 4 x 21 KB
+    static_assert((TCH + VCH) % 64 == 0, "whole wavefront copies");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    __shared__ unsigned int s_rowmax[kMT];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // XCD-aware decode: the vtiles workgroups of one train tile get ids 8 apart
+    const int64_t id = blockIdx.x;
+    const int xcd = (int)(id & 7);
+    const int64_t j = id >> 3;
+    const int vt = (int)(j % vtiles);
+    const int64_t tt = (j / vtiles) * 8 + xcd;
+    if (tt >= ttiles) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, l32 = lane & 31;
-    const int64_t row0 = (int64_t)blockIdx.x * TN;
+    const int wy = wave >> 1, wx = wave & 1;        // 4 x 2 waves
+    const int64_t row0 = tt * kMT;
+    const int v0 = vt * kMV;
     const int64_t cb = (int64_t)a.k * BITS / 8;
-    const int nstages = (a.k + KE - 1) / KE;
+    const int nstages = w.kp / KE;
+    if (tid < kMT) s_rowmax[tid] = 0u;
+    const unsigned lds0 = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)smem);
 
-    float rmax[2][16];
+    // ---- copy roles of this lane: LPW wavefront copies per stage -------------------------------
+    // Copy q covers LDS chunks 64 q .. 64 q + 63 of the stage buffer, laid out [train rows][val rows]
+    // without padding; inside a row the 16-byte chunks are XOR-swizzled so that the MFMA operand
+    // reads (16 consecutive rows, same chunk) hit distinct banks.
+    int64_t src_row[LPW];       // byte offset of the source row from the checkpoint's base (train) or tile base (val)
+    int src_col[LPW];           // byte offset inside the stage
+    bool is_train[LPW];
+    unsigned dst_off[LPW];      // wave-uniform LDS offset inside the buffer
+#pragma unroll
+    for (int u = 0; u < LPW; ++u) {
+        const int q = wave * LPW + u;
+        const int t = (q < NINST ? q : 0) * 64 + lane;
+        dst_off[u] = q < NINST ? (unsigned)q * 1024u : (unsigned)(TRAIN_BYTES + VAL_BYTES);
+        if (t < TCH) {
+            const int r = t / TCPR, pos = t % TCPR;
+            const int c = BITS == 8 ? (pos ^ ((r >> 1) & 7)) : (BITS == 4 ? (pos ^ ((r >> 2) & 3)) : 0);
+            int64_t grow = row0 + r;
+            if (grow > a.N - 1) grow = a.N - 1;
+            src_row[u] = grow * cb;
+            src_col[u] = c * 16;
+            is_train[u] = true;
+        } else {
+            const int tv = t - TCH;
+            const int r = tv >> 3, pos = tv & 7;
+            src_row[u] = (int64_t)r * w.kp;
+            src_col[u] = (pos ^ ((r >> 1) & 7)) * 16;
+            is_train[u] = false;
+        }
+    }
+
+    // ---- operand read addresses (swizzle folded into the lane's base, K-step applied by XOR) ---
+    unsigned a_base[2], b_base[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int R = wy * 64 + 32 * b + l32;
+        if (BITS == 8) a_base[b] = R * 128 + (((l32 >> 1) & 7) >> 1) * 32 + ((half ^ ((l32 >> 1) & 1)) * 16);
+        else if (BITS == 4) a_base[b] = R * 64 + ((l32 >> 2) & 3) * 16 + half * 8;
+        else a_base[b] = R * 16 + half * 4;
+        const int Rv = wx * 64 + 32 * b + l32;
+        b_base[b] = TRAIN_BYTES + Rv * 128 + (((l32 >> 1) & 7) >> 1) * 32 + ((half ^ ((l32 >> 1) & 1)) * 16);
+    }
+
+    float facc[2][2][16];
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) rmax[b][v] = neg_inf();
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) facc[b][c][v] = 0.0f;
 
-    for (int v0 = 0; v0 < a.M; v0 += TM) {
-        float facc[2][2][16];
+    const int total = a.C * nstages;                 // stages over all checkpoints, one pipeline
+    auto issue = [&](int g) {                        // start the copies of global stage g
+        const int ci = g / nstages, s = g - ci * nstages;
+        const unsigned char *tcp = a.tc[ci];
+        const int8_t *vcp = w.vexp + ((size_t)ci * w.Mp + v0) * (size_t)w.kp;
+        const unsigned buf = lds0 + (unsigned)(g % NBUF) * BUF;
+#pragma unroll
+        for (int u = 0; u < LPW; ++u) {
+            const unsigned char *p;
+            if (is_train[u]) {
+                int64_t byte = (int64_t)s * TB + src_col[u];
+                if (byte > cb - 16) byte = cb - 16;  // tail stage: the matching val bytes are zero
+                p = tcp + src_row[u] + byte;
+            } else {
+                p = (const unsigned char *)vcp + src_row[u] + (int64_t)s * KE + src_col[u];
+            }
+            global_to_lds16(p, buf + dst_off[u]);
+        }
+    };
+
+    // prologue: NBUF-1 stages in flight
+#pragma unroll
+    for (int g = 0; g < NBUF - 1; ++g)
+        if (g < total) issue(g);
+
+    int g = 0;
+    for (int ci = 0; ci < a.C; ++ci) {
+        i32x16 acc[2][2];
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int c = 0; c < 2; ++c)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) facc[b][c][v] = 0.0f;
+                for (int v = 0; v < 16; ++v) acc[b][c][v] = 0;
 
-        for (int ci = 0; ci < a.C; ++ci) {
-            const unsigned char *tcp = a.tc[ci], *vcp = a.vc[ci];
-            i32x16 acc[2][2];
+        for (int s = 0; s < nstages; ++s, ++g) {
+            // the copies of stage g are the oldest outstanding ones; NBUF-2 younger stages may stay in
+            // flight (near the end fewer are outstanding, so waiting for everything is exact there)
+            if (g + NBUF - 2 < total) wait_vmcnt<(NBUF - 2) * LPW>(); else wait_vmcnt<0>();
+            __syncthreads();                         // stage g visible to all; buffer of stage g-1 free
+            if (g + NBUF - 1 < total) issue(g + NBUF - 1);
+            const unsigned char *sb = smem + (g % NBUF) * BUF;
+            if (BITS == 1) {
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
+                for (int gp = 0; gp < KE / 64; ++gp) {          // K-step pairs
+                    i32x4 af[2][2];
 #pragma unroll
-                for (int c = 0; c < 2; ++c)
+                    for (int b = 0; b < 2; ++b) {
+                        const unsigned int wd = *(const unsigned int *)(sb + a_base[b] + 8 * gp);
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[b][c][v] = 0;
-
-            uint4 st[CPT];
-            auto fetch = [&](int s) {
-#pragma unroll
-                for (int u = 0; u < CPT; ++u) {
-                    const int c = tid + 256 * u;
-                    uint4 val = make_uint4(0, 0, 0, 0);
-                    if (c < CHUNKS) {
-                        const int r = c / (SB / 16), q = c % (SB / 16);
-                        const int64_t byte = (int64_t)s * SB + q * 16;
-                        if (byte < cb) {
-                            if (r < TN) { if (row0 + r < a.N) val = *(const uint4 *)(tcp + (row0 + r) * cb + byte); }
-                            else { if (v0 + (r - TN) < a.M) val = *(const uint4 *)(vcp + (int64_t)(v0 + r - TN) * cb + byte); }
-                        }
+                        for (int jd = 0; jd < 8; ++jd)
+                            af[b][jd >> 2][jd & 3] = (int)((wd >> jd) & 0x01010101u);
                     }
-                    st[u] = val;
-                }
-            };
-            auto commit = [&](int buf) {
 #pragma unroll
-                for (int u = 0; u < CPT; ++u) {
-                    const int c = tid + 256 * u;
-                    if (c < CHUNKS) {
-                        const int r = c / (SB / 16), q = c % (SB / 16);
-                        *(uint4 *)(smem + buf * ROWS * STRIDE + r * STRIDE + q * 16) = st[u];
+                    for (int s2 = 0; s2 < 2; ++s2) {
+                        i32x4 bf[2];
+#pragma unroll
+                        for (int c = 0; c < 2; ++c)
+                            bf[c] = *(const i32x4 *)(sb + (b_base[c] ^ ((2 * gp + s2) << 5)));
+#pragma unroll
+                        for (int b = 0; b < 2; ++b)
+#pragma unroll
+                            for (int c = 0; c < 2; ++c)
+                                acc[b][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[b][s2], bf[c], acc[b][c], 0, 0, 0);
                     }
                 }
-            };
-            __syncthreads();
-            fetch(0);
-            commit(0);
-            __syncthreads();
-            for (int s = 0; s < nstages; ++s) {
-                const int buf = s & 1;
-                if (s + 1 < nstages) fetch(s + 1);
-                const unsigned char *ta = smem + buf * ROWS * STRIDE + (wave * 64) * STRIDE;
-                const unsigned char *va = smem + buf * ROWS * STRIDE + TN * STRIDE;
+            } else {
 #pragma unroll
                 for (int ks = 0; ks < KE / 32; ++ks) {
                     i32x4 af[2], bf[2];
 #pragma unroll
                     for (int b = 0; b < 2; ++b) {
                         if (BITS == 8) {
-                            af[b] = *(const i32x4 *)(ta + (32 * b + l32) * STRIDE + 32 * ks + 16 * half);
-                            bf[b] = *(const i32x4 *)(va + (32 * b + l32) * STRIDE + 32 * ks + 16 * half);
+                            af[b] = *(const i32x4 *)(sb + (a_base[b] ^ (ks << 5)));
                         } else {
-                            const uint2 pa = *(const uint2 *)(ta + (32 * b + l32) * STRIDE + 16 * ks + 8 * half);
-                            const uint2 pb = *(const uint2 *)(va + (32 * b + l32) * STRIDE + 16 * ks + 8 * half);
+                            const uint2 pa = *(const uint2 *)(sb + (a_base[b] ^ (ks << 4)));
                             af[b][0] = (int)((pa.x << 4) & 0xF0F0F0F0u); af[b][1] = (int)(pa.x & 0xF0F0F0F0u);
                             af[b][2] = (int)((pa.y << 4) & 0xF0F0F0F0u); af[b][3] = (int)(pa.y & 0xF0F0F0F0u);
-                            bf[b][0] = (int)((pb.x << 4) & 0xF0F0F0F0u); bf[b][1] = (int)(pb.x & 0xF0F0F0F0u);
-                            bf[b][2] = (int)((pb.y << 4) & 0xF0F0F0F0u); bf[b][3] = (int)(pb.y & 0xF0F0F0F0u);
                         }
                     }
+#pragma unroll
+                    for (int c = 0; c < 2; ++c) bf[c] = *(const i32x4 *)(sb + (b_base[c] ^ (ks << 5)));
 #pragma unroll
                     for (int b = 0; b < 2; ++b)
 #pragma unroll
                         for (int c = 0; c < 2; ++c)
                             acc[b][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[b], bf[c], acc[b][c], 0, 0, 0);
                 }
-                if (s + 1 < nstages) commit(buf ^ 1);
-                __syncthreads();
             }
-            // checkpoint epilogue.  acc[b][c][v]: train row 32b + 8(v/4) + 4 half + v%4, val col 32c + l32
-            // lane L of the wave holds rnorm of train row (wave*64 + L); rows are fetched by shuffle
-            int64_t myrow = row0 + wave * 64 + lane;
-            if (myrow > a.N - 1) myrow = a.N - 1;
-            const float rt_lane = a.tr[ci][myrow];
-            float wv[2];
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                int col = v0 + 32 * c + l32;
-                if (col > a.M - 1) col = a.M - 1;
-                wv[c] = __fmul_rn(a.eta[ci], a.vr[ci][col]);
-            }
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const float rt = __shfl(rt_lane, 32 * b + 8 * (v >> 2) + 4 * half + (v & 3), 64);
-#pragma unroll
-                    for (int c = 0; c < 2; ++c) {
-                        const int D = BITS == 8 ? acc[b][c][v] : (acc[b][c][v] >> 8);
-                        const float t = __fmul_rn(__fmul_rn((float)D, rt), wv[c]);
-                        facc[b][c][v] = __fadd_rn(facc[b][c][v], t);
-                    }
-                }
         }
+        // checkpoint epilogue.  acc[b][c][v]: train row 32b + 8(v/4) + 4 half + v%4, val col 32c + l32.
+        // Lane L of the wave holds rnorm of train row (wy*64 + L); rows are fetched by shuffle.
+        int64_t myrow = row0 + wy * 64 + lane;
+        if (myrow > a.N - 1) myrow = a.N - 1;
+        const float rt_lane = a.tr[ci][myrow];
+        float wv[2];
+        int vs[2];
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
-            const int col = v0 + 32 * c + l32;
-            if (col < a.M) {
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        rmax[b][v] = fmaxf(rmax[b][v], facc[b][c][v]);
-                        const int64_t r = row0 + wave * 64 + 32 * b + 8 * (v >> 2) + 4 * half + (v & 3);
-                        if (a.full && r < a.N) a.full[r * a.M + col] = facc[b][c][v];
-                    }
-            }
+            const int col = v0 + wx * 64 + 32 * c + l32;            // < Mp (padded)
+            wv[c] = w.vw[ci * w.Mp + col];
+            vs[c] = BITS == 1 ? w.vsum[ci * w.Mp + col] : 0;
         }
-    }
-    if (a.score) {
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                float m = rmax[b][v];
+                const float rt = __shfl(rt_lane, 32 * b + 8 * (v >> 2) + 4 * half + (v & 3), 64);
 #pragma unroll
-                for (int o = 16; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-                const int64_t r = row0 + wave * 64 + 32 * b + 8 * (v >> 2) + 4 * half + (v & 3);
-                if (l32 == 0 && r < a.N) a.score[r] = m;
+                for (int c = 0; c < 2; ++c) {
+                    const int D = BITS == 8 ? acc[b][c][v] : (BITS == 4 ? (acc[b][c][v] >> 4) : vs[c] - 2 * acc[b][c][v]);
+                    const float t = __fmul_rn(__fmul_rn((float)D, rt), wv[c]);
+                    facc[b][c][v] = __fadd_rn(facc[b][c][v], t);
+                }
             }
     }
+    // tile epilogue: optional full matrix, row maxima over this val tile
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rloc = wy * 64 + 32 * b + 8 * (v >> 2) + 4 * half + (v & 3);
+            const int64_t r = row0 + rloc;
+            float m = neg_inf();
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const int col = v0 + wx * 64 + 32 * c + l32;
+                if (col < a.M) {
+                    m = fmaxf(m, facc[b][c][v]);
+                    if (a.full && r < a.N) a.full[r * a.M + col] = facc[b][c][v];
+                }
+            }
+            if (a.score) {
+#pragma unroll
+                for (int o = 16; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+                if (l32 == 0 && m > neg_inf()) atomicMax(&s_rowmax[rloc], f32_order_key(m));
+            }
+        }
+    if (a.score) {
+        __syncthreads();
+        if (tid < kMT && row0 + tid < a.N && s_rowmax[tid] != 0u) atomicMax(&w.smax[row0 + tid], s_rowmax[tid]);
+    }
+}
+
+struct MfmaPlan { int32_t Mp, kp; size_t off_vw, off_vsum, off_smax, total; };
+static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int bits, int C) {
+    MfmaPlan p{};
+    const int ke = mfma_stage_elems(bits);
+    p.Mp = (M + kMV - 1) / kMV * kMV;
+    p.kp = (k + ke - 1) / ke * ke;
+    size_t o = (size_t)C * p.Mp * (size_t)p.kp;
+    o = (o + 255) & ~(size_t)255;
+    p.off_vw = o;   o += (size_t)C * p.Mp * 4;
+    p.off_vsum = o; o += (size_t)C * p.Mp * 4;
+    o = (o + 255) & ~(size_t)255;
+    p.off_smax = o; o += (size_t)(N > 0 ? N : 1) * 4;
+    p.total = o;
+    return p;
+}
+static bool use_mfma_path(int bits, int32_t M, int32_t k) {
+    return bits == 8 || bits == 4 || (bits == 1 && M > 64 && k % 128 == 0);   // 1-bit rows must be 16-byte multiples
+}
+
+template <int BITS>
+static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st) {
+    const MfmaPlan p = mfma_plan(a.N, a.M, a.k, BITS, a.C);
+    ScorePrep w{};
+    unsigned char *base = (unsigned char *)ws;
+    w.vexp = (int8_t *)base; w.vw = (float *)(base + p.off_vw); w.vsum = (int *)(base + p.off_vsum);
+    w.smax = (unsigned int *)(base + p.off_smax); w.Mp = p.Mp; w.kp = p.kp;
+    hipLaunchKernelGGL((score_prepare_kernel<BITS>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
+    constexpr int KE = mfma_stage_elems(BITS);
+    constexpr int TB = KE * BITS / 8;
+    const size_t lds = (size_t)(BITS == 8 ? 3 : 4) * (size_t)(kMT * TB + kMV * KE + 1024);
+    static bool once = false;
+    if (!once) {
+        if (hipFuncSetAttribute((const void *)score_mfma_kernel<BITS>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess) return QLESS_ERR_DEVICE;
+        once = true;
+    }
+    const int64_t ttiles = (a.N + kMT - 1) / kMT;
+    const int vtiles = p.Mp / kMV;
+    const int64_t grid = 8 * (int64_t)vtiles * ((ttiles + 7) / 8);
+    if (grid > 0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((score_mfma_kernel<BITS>), dim3((unsigned)grid), dim3(512), lds, st, a, w, (int)ttiles, vtiles);
+    if (a.score) {
+        int64_t blocks = (a.N + 255) / 256;
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(score_finish_kernel, dim3((unsigned)blocks), dim3(256), 0, st, w.smax, a.N, a.score);
+    }
+    return launch_status();
 }
 
 template <int BITS, int RT, int CT, int TY, int TX>
@@ -380,15 +601,15 @@ static void launch_popcount(const ScoreArgs &a, hipStream_t st) {
 using namespace qless;
 
 extern "C" size_t qless_score_workspace(int64_t N, int32_t M, int32_t k, int bits, int C) {
-    (void)N; (void)M; (void)k; (void)bits; (void)C;
-    return 0;
+    if (N < 0 || M < 1 || k <= 0 || C < 1 || !valid_bits(bits)) return 0;
+    if (!use_mfma_path(bits, M, k)) return 0;
+    return mfma_plan(N, M, k, bits, C).total;
 }
 
 extern "C" qless_status qless_score(const void *const *train_codes, const float *const *train_rnorm,
                                     const void *const *val_codes, const float *const *val_rnorm,
                                     const float *eta, int C, int64_t N, int32_t M, int32_t k, int bits,
                                     float *score, float *full, void *ws, size_t ws_bytes, void *stream) {
-    (void)ws; (void)ws_bytes;
     if (!train_codes || !train_rnorm || !val_codes || !val_rnorm || !eta) return QLESS_ERR_INVALID_ARG;
     if (C < 1 || N < 0 || M < 1 || k <= 0) return QLESS_ERR_INVALID_ARG;
     if (!score && !full) return QLESS_ERR_INVALID_ARG;
@@ -404,6 +625,15 @@ extern "C" qless_status qless_score(const void *const *train_codes, const float 
     a.C = C; a.N = N; a.M = M; a.k = k; a.score = score; a.full = full;
     if (N == 0) return QLESS_OK;
     hipStream_t st = (hipStream_t)stream;
+    if (use_mfma_path(bits, M, k)) {
+        const size_t need = mfma_plan(N, M, k, bits, C).total;
+        if (!ws || ws_bytes < need) return QLESS_ERR_WORKSPACE;
+        if ((uintptr_t)ws % 16) return QLESS_ERR_INVALID_ARG;
+        if (N > (int64_t)0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
+        if (bits == 8) return launch_mfma<8>(a, ws, st);
+        if (bits == 4) return launch_mfma<4>(a, ws, st);
+        return launch_mfma<1>(a, ws, st);
+    }
     if (bits == 1) {
         if (M > 32) launch_popcount<1, 8, 4, 16, 16>(a, st);
         else if (M > 8) launch_popcount<1, 8, 4, 32, 8>(a, st);
@@ -412,11 +642,6 @@ extern "C" qless_status qless_score(const void *const *train_codes, const float 
         if (M > 32) launch_popcount<2, 4, 4, 16, 16>(a, st);
         else if (M > 8) launch_popcount<2, 4, 4, 32, 8>(a, st);
         else launch_popcount<2, 8, 1, 32, 8>(a, st);
-    } else {
-        const size_t lds = 2 * (size_t)(256 + 64) * (64 + 16);
-        const unsigned grid = (unsigned)((N + 255) / 256);
-        if (bits == 8) hipLaunchKernelGGL((score_mfma_kernel<8>), dim3(grid), dim3(256), lds, st, a);
-        else hipLaunchKernelGGL((score_mfma_kernel<4>), dim3(grid), dim3(256), lds, st, a);
     }
     return launch_status();
 }
