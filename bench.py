@@ -91,7 +91,8 @@ def main():
     val_codes, val_rnorm = synthetic_store(M, 20, bits)
     train_S = [torch.empty(N, dtype=torch.float32, device=dev) for _ in range(C)]
     score = torch.zeros(N, dtype=torch.float32, device=dev)
-    Q.score(train_codes, train_rnorm, val_codes, val_rnorm, eta, k, bits, score_out=score)
+    ws_score = torch.empty(max(Q.score_workspace(N, M, k, bits, C), 16), dtype=torch.uint8, device=dev)
+    Q.score(train_codes, train_rnorm, val_codes, val_rnorm, eta, k, bits, score_out=score, ws=ws_score)
     P = torch.empty(n, k, dtype=torch.float32, device=dev)
     ws_proj = torch.empty(max(Q.project_workspace(n, d, k), 16), dtype=torch.uint8, device=dev)
     ws_topk = torch.empty(max(Q.topk_workspace(N, k_sel), 16), dtype=torch.uint8, device=dev)
@@ -119,7 +120,7 @@ def main():
             Q.quantize(P, bits, codes=train_codes[c][b:b + n], S=train_S[c][b:b + n],
                        rnorm=train_rnorm[c][b:b + n])
         Q.score([t[b:b + n] for t in train_codes], [t[b:b + n] for t in train_rnorm], val_codes,
-                val_rnorm, eta, k, bits, score_out=score[b:b + n])
+                val_rnorm, eta, k, bits, score_out=score[b:b + n], ws=ws_score)
         return Q.topk(score, k_sel, ws=ws_topk)
 
     for i in range(args.warmup):
@@ -158,13 +159,14 @@ def main():
             vc4, vr4 = synthetic_store(M4, 50, sb)
             sc4 = torch.empty(N4, dtype=torch.float32, device=dev)
             ws4 = torch.empty(max(Q.topk_workspace(N4, 13500), 16), dtype=torch.uint8, device=dev)
-            Q.score(tc4, tr4, vc4, vr4, eta, k, sb, score_out=sc4)
+            wss = torch.empty(max(Q.score_workspace(N4, M4, k, sb, C), 16), dtype=torch.uint8, device=dev)
+            Q.score(tc4, tr4, vc4, vr4, eta, k, sb, score_out=sc4, ws=wss)
             torch.cuda.synchronize()
             reps = 3
             e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
             e[0].record()
             for _ in range(reps):
-                Q.score(tc4, tr4, vc4, vr4, eta, k, sb, score_out=sc4)
+                Q.score(tc4, tr4, vc4, vr4, eta, k, sb, score_out=sc4, ws=wss)
             e[1].record()
             for _ in range(reps):
                 Q.topk(sc4, 13500, ws=ws4)

@@ -300,9 +300,10 @@ __global__ void score_finish_kernel(const unsigned int *smax, int64_t N, float *
 // Asynchronous 16-byte global -> LDS copy (no VGPR staging): lane L of the wavefront writes
 // LDS bytes [lds_addr + 16 L, +16) with the 16 bytes at its own global address.  lds_addr must be
 // wave-uniform.  Completion is tracked by vmcnt like any vector load.
-__device__ inline void global_to_lds16(const void *gptr, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :: "s"(lds_addr), "v"(gptr) : "memory");
+// The global address is a wave-uniform base (SGPR pair) plus an unsigned 32-bit lane offset.
+__device__ inline void global_to_lds16(const void *base, unsigned lane_off, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
 }
 template <int N> __device__ inline void wait_vmcnt() {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
@@ -348,31 +349,32 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     // Copy q covers LDS chunks 64 q .. 64 q + 63 of the stage buffer, laid out [train rows][val rows]
     // without padding; inside a row the 16-byte chunks are XOR-swizzled so that the MFMA operand
     // reads (16 consecutive rows, same chunk) hit distinct banks.
-    int64_t src_row[LPW];       // byte offset of the source row from the checkpoint's base (train) or tile base (val)
-    int src_col[LPW];           // byte offset inside the stage
-    bool is_train[LPW];
+    unsigned voff[LPW];         // lane offset from the stage's (uniform) train or val base
+    unsigned vcol[LPW];         // byte offset of the lane's chunk inside the stage (train copies)
+    bool is_train[LPW];         // wave-uniform: a copy is all train chunks or all val chunks
     unsigned dst_off[LPW];      // wave-uniform LDS offset inside the buffer
 #pragma unroll
     for (int u = 0; u < LPW; ++u) {
         const int q = wave * LPW + u;
-        const int t = (q < NINST ? q : 0) * 64 + lane;
+        const int qq = q < NINST ? q : 0;
+        const int t = qq * 64 + lane;
         dst_off[u] = q < NINST ? (unsigned)q * 1024u : (unsigned)(TRAIN_BYTES + VAL_BYTES);
+        is_train[u] = qq * 64 < TCH;
         if (t < TCH) {
             const int r = t / TCPR, pos = t % TCPR;
             const int c = BITS == 8 ? (pos ^ ((r >> 1) & 7)) : (BITS == 4 ? (pos ^ ((r >> 2) & 3)) : 0);
             int64_t grow = row0 + r;
-            if (grow > a.N - 1) grow = a.N - 1;
-            src_row[u] = grow * cb;
-            src_col[u] = c * 16;
-            is_train[u] = true;
+            if (grow > a.N - 1) grow = a.N - 1;          // rows past N re-read the last row (masked later)
+            voff[u] = (unsigned)((grow - row0) * cb) + c * 16;
+            vcol[u] = c * 16;
         } else {
             const int tv = t - TCH;
             const int r = tv >> 3, pos = tv & 7;
-            src_row[u] = (int64_t)r * w.kp;
-            src_col[u] = (pos ^ ((r >> 1) & 7)) * 16;
-            is_train[u] = false;
+            voff[u] = (unsigned)r * (unsigned)w.kp + (pos ^ ((r >> 1) & 7)) * 16;
+            vcol[u] = 0;
         }
     }
+    const bool ragged = (a.k % KE) != 0;             // last stage reaches past the end of the train rows
 
     // ---- operand read addresses (swizzle folded into the lane's base, K-step applied by XOR) ---
     unsigned a_base[2], b_base[2];
@@ -397,20 +399,19 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     const int total = a.C * nstages;                 // stages over all checkpoints, one pipeline
     auto issue = [&](int g) {                        // start the copies of global stage g
         const int ci = g / nstages, s = g - ci * nstages;
-        const unsigned char *tcp = a.tc[ci];
-        const int8_t *vcp = w.vexp + ((size_t)ci * w.Mp + v0) * (size_t)w.kp;
+        const unsigned char *tbase = a.tc[ci] + row0 * cb + (int64_t)s * TB;
+        const unsigned char *vbase = (const unsigned char *)w.vexp + ((size_t)ci * w.Mp + v0) * (size_t)w.kp + (size_t)s * KE;
         const unsigned buf = lds0 + (unsigned)(g % NBUF) * BUF;
+        const bool tail = ragged && s == nstages - 1;
 #pragma unroll
         for (int u = 0; u < LPW; ++u) {
-            const unsigned char *p;
-            if (is_train[u]) {
-                int64_t byte = (int64_t)s * TB + src_col[u];
-                if (byte > cb - 16) byte = cb - 16;  // tail stage: the matching val bytes are zero
-                p = tcp + src_row[u] + byte;
-            } else {
-                p = (const unsigned char *)vcp + src_row[u] + (int64_t)s * KE + src_col[u];
+            unsigned off = voff[u];
+            if (tail && is_train[u]) {
+                // chunks past the row end re-read its last 16 bytes (the matching val bytes are zero)
+                const int64_t over = (int64_t)s * TB + vcol[u] - (cb - 16);
+                if (over > 0) off -= (unsigned)over;
             }
-            global_to_lds16(p, buf + dst_off[u]);
+            global_to_lds16(is_train[u] ? tbase : vbase, off, buf + dst_off[u]);
         }
     };
 
