@@ -1,26 +1,46 @@
 // qless_quantize: absmax b-bit quantisation and packing of projected gradients
 // (paper Eq.(4),(5), Sec. 2.3 / 3.1; the 1-bit sign code of Table 3 / Sec. 5).
 //
-// One workgroup of 256 threads per row.  The row is read once into registers (k <= 16384) or
-// twice (longer rows; the second read is served by L2), reduced to its absolute maximum with
-// wavefront shuffles, quantised with the canonical fp32 sequence
+// Rows up to 8192 elements: one wavefront per row (four rows per workgroup), the whole row held
+// in registers (128 floats per lane at k = 8192), absolute maximum and sum of squares reduced
+// with DPP row shifts and broadcasts -- no LDS, no barrier, so every wavefront keeps its loads
+// in flight independently.  Longer rows: one workgroup per row, cached in registers up to
+// k = 16384, re-read (from L2) above that.  Canonical fp32 sequence on both paths:
 //     scale = alpha / S (IEEE division),  q = clamp(rne(P * scale))
-// and written as packed codes with coalesced stores.  HBM-bound: 4k bytes in, k*bits/8 + 8 out.
+// Codes leave as packed words with coalesced stores.  HBM-bound: 4k bytes in, k*bits/8 + 8 out.
 #include "common.h"
 
 namespace qless {
 
 constexpr int kQThreads = 256;
-constexpr int kQMaxRegs = 64;   // floats cached per thread: rows up to 256*64 = 16384 elements
 
-__device__ inline float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
+// Wavefront reductions on DPP: row_shr 1/2/4/8 build the totals of the four 16-lane rows in
+// their last lanes, row_bcast15 / row_bcast31 carry them into lane 63.  Lanes without a source
+// read 0, the identity of both uses (max of absolute values, unsigned sum).
+template <int CTRL, int ROWMASK>
+__device__ inline uint32_t dpp0(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROWMASK, 0xF, false);
 }
-__device__ inline unsigned long long wave_sum_u64(unsigned long long v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+__device__ inline float wave_max(float v) {          // v >= 0; result uniform
+    uint32_t x = __float_as_uint(v);                 // non-negative floats order like their bits
+    x = max(x, dpp0<0x111, 0xF>(x)); x = max(x, dpp0<0x112, 0xF>(x));
+    x = max(x, dpp0<0x114, 0xF>(x)); x = max(x, dpp0<0x118, 0xF>(x));
+    x = max(x, dpp0<0x142, 0xA>(x)); x = max(x, dpp0<0x143, 0xC>(x));
+    return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)x, 63));
+}
+__device__ inline uint32_t wave_sum_u32(uint32_t x) {   // result uniform
+    x += dpp0<0x111, 0xF>(x); x += dpp0<0x112, 0xF>(x);
+    x += dpp0<0x114, 0xF>(x); x += dpp0<0x118, 0xF>(x);
+    x += dpp0<0x142, 0xA>(x); x += dpp0<0x143, 0xC>(x);
+    return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+
+// OR of a value over each aligned group of 8 lanes, valid in the group's first lane
+// (three v_or_b32 with DPP row_shl:1/2/4; lanes shifted in from outside a row read 0).
+__device__ inline uint32_t or_reduce8(uint32_t v) {
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x101, 0xF, 0xF, true);
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x102, 0xF, 0xF, true);
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x104, 0xF, 0xF, true);
     return v;
 }
 
@@ -32,31 +52,32 @@ __device__ inline int quant1(float p, float scale, float alpha) {
 }
 
 // Element ownership: thread t owns, for each group g, the E consecutive elements starting at
-// g * 256 * E + t * E, where E = 4 (8-bit: one dword of codes), 8 (4-bit: one dword) or
-// 1 (2-/1-bit: a wavefront ballot yields 64 plane bits).  k is a multiple of 64, so a thread's
-// E elements are all inside the row or all outside, and so is a whole wavefront for E = 1.
+// g * 256 * E + t * E with E = 4: one dword of codes (8-bit), one 16-bit word (4-bit) or one
+// nibble of plane bits OR-combined over 8 neighbouring lanes into a 32-bit plane word (2-/1-bit).
+// k is a multiple of 64, so a thread's E elements are all inside the row or all outside, and so
+// is every aligned group of 8 lanes for the bit planes.
+// Branch-free load of a thread's E elements: the address is clamped into the row, elements past
+// the row end become 0 by a select (so all of a thread's loads can be issued back to back).
 template <int E>
 __device__ inline void load_elems(const float *p, int base, int32_t k, bool vec, float (&v)[E]) {
-    if (base >= k) {
-#pragma unroll
-        for (int e = 0; e < E; ++e) v[e] = 0.0f;
-        return;
-    }
+    const bool in = base < k;
+    const int b = in ? base : k - E;
     if (E >= 4 && vec) {
 #pragma unroll
         for (int e = 0; e < E; e += 4) {
-            const float4 f = *(const float4 *)(p + base + e);
-            v[e] = f.x; v[e + 1] = f.y; v[e + 2] = f.z; v[e + 3] = f.w;
+            const float4 f = *(const float4 *)(p + b + e);
+            v[e] = in ? f.x : 0.0f; v[e + 1] = in ? f.y : 0.0f;
+            v[e + 2] = in ? f.z : 0.0f; v[e + 3] = in ? f.w : 0.0f;
         }
     } else {
 #pragma unroll
-        for (int e = 0; e < E; ++e) v[e] = p[base + e];
+        for (int e = 0; e < E; ++e) { const float f = p[b + e]; v[e] = in ? f : 0.0f; }
     }
 }
 
 template <int BITS, int E>
 __device__ inline void emit_elems(const float (&v)[E], int base, int32_t k, float scale, float alpha,
-                                  unsigned char *crow, int lane, unsigned long long &n2) {
+                                  unsigned char *crow, int lane, uint32_t &n2) {
     const bool in = base < k;
     if (BITS == 8) {
         uint32_t w = 0;
@@ -75,31 +96,49 @@ __device__ inline void emit_elems(const float (&v)[E], int base, int32_t k, floa
             n2 += (unsigned)(q * q);
             w |= ((uint32_t)q & 0xFu) << (4 * e);
         }
-        if (in) *(uint32_t *)(crow + base / 2) = w;
-    } else if (BITS == 2) {
-        const int q = quant1(v[0], scale, alpha);
-        const unsigned long long nz = __ballot(in && q != 0);
-        const unsigned long long sg = __ballot(in && q < 0);
-        if (lane == 0 && in) {
-            *(unsigned long long *)(crow + base / 8) = nz;
-            *(unsigned long long *)(crow + k / 8 + base / 8) = sg;
-            n2 += (unsigned)__popcll(nz);
-        }
+        if (in) *(uint16_t *)(crow + base / 2) = (uint16_t)w;
     } else {
-        const unsigned long long sg = __ballot(in && v[0] < 0.0f);
-        if (lane == 0 && in) *(unsigned long long *)(crow + base / 8) = sg;
+        // plane bits of this thread's 4 elements, placed at bit 4*(lane%8) .. +3 of a 32-bit word
+        uint32_t sg = 0, nz = 0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            if (BITS == 2) {
+                const int q = quant1(v[e], scale, alpha);
+                nz |= (uint32_t)(q != 0) << e;
+                sg |= (uint32_t)(q < 0) << e;
+            } else {
+                sg |= (uint32_t)(v[e] < 0.0f) << e;
+            }
+        }
+        const int sh = 4 * (lane & 7);
+        sg <<= sh;
+        sg = or_reduce8(sg);
+        if (BITS == 2) {
+            n2 += (unsigned)__popc(nz);
+            nz <<= sh;
+            nz = or_reduce8(nz);
+        }
+        if (in && (lane & 7) == 0) {
+            if (BITS == 2) {
+                *(uint32_t *)(crow + base / 8) = nz;
+                *(uint32_t *)(crow + k / 8 + base / 8) = sg;
+            } else {
+                *(uint32_t *)(crow + base / 8) = sg;
+            }
+        }
     }
 }
 
-template <int BITS, bool CACHED>
+template <int BITS, int NG>   // NG > 0: the row fits NG register groups per thread; NG == 0: re-read it
 __global__ void __launch_bounds__(kQThreads)
 quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned char *__restrict__ codes,
                 float *__restrict__ S_out, float *__restrict__ rnorm_out, int vec) {
-    constexpr int E = BITS == 8 ? 4 : (BITS == 4 ? 8 : 1);
+    constexpr int E = 4;
     constexpr int GROUP = kQThreads * E;
-    constexpr int MAXG = CACHED ? kQMaxRegs / E : 1;
+    constexpr bool CACHED = NG > 0;
+    constexpr int MAXG = CACHED ? NG : 1;
     __shared__ float s_max[4];
-    __shared__ unsigned long long s_sum[4];
+    __shared__ uint32_t s_sum[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t row = blockIdx.x;
     const float *p = P + row * ldP;
@@ -131,7 +170,7 @@ quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned ch
     const float alpha = (float)((1 << (BITS - 1)) - 1);
     const float scale = (BITS > 1 && S > 0.0f) ? __fdiv_rn(alpha, S) : 0.0f;
 
-    unsigned long long n2 = 0;
+    uint32_t n2 = 0;        // per-thread partial: < 2^32 for rows up to 2^26 elements
     if (CACHED) {
 #pragma unroll
         for (int g = 0; g < MAXG; ++g)
@@ -149,11 +188,45 @@ quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned ch
         }
         return;
     }
-    n2 = wave_sum_u64(n2);
+    n2 = wave_sum_u32(n2);   // a wavefront's share: < 2^32 for rows up to 2^20 elements
     if (lane == 0) s_sum[wave] = n2;
     __syncthreads();
     if (tid == 0) {
-        const unsigned long long tot = s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3];
+        const unsigned long long tot = (unsigned long long)s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3];
+        S_out[row] = S;
+        rnorm_out[row] = tot ? (float)(1.0 / sqrt((double)tot)) : 0.0f;
+    }
+}
+
+// One wavefront per row, k <= 256 * NG * ... : lane L owns, for each group g < NG, the four
+// elements starting at 256 g + 4 L.
+template <int BITS, int NG, bool VEC>
+__global__ void __launch_bounds__(kQThreads)
+quantize_wave_kernel(const float *__restrict__ P, int64_t ldP, int64_t n, int32_t k,
+                     unsigned char *__restrict__ codes, float *__restrict__ S_out,
+                     float *__restrict__ rnorm_out) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= n) return;                       // whole wavefront; nothing below synchronises
+    const float *p = P + row * ldP;
+    unsigned char *crow = codes + row * ((int64_t)k * BITS / 8);
+    float reg[NG][4];
+    float amax = 0.0f;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        load_elems<4>(p, g * 256 + lane * 4, k, VEC, reg[g]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) amax = fmaxf(amax, fabsf(reg[g][e]));
+    }
+    const float S = wave_max(amax);
+    const float alpha = (float)((1 << (BITS - 1)) - 1);
+    const float scale = (BITS > 1 && S > 0.0f) ? __fdiv_rn(alpha, S) : 0.0f;
+    uint32_t n2 = 0;
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+        emit_elems<BITS, 4>(reg[g], g * 256 + lane * 4, k, scale, alpha, crow, lane, n2);
+    const uint32_t tot = BITS == 1 ? (uint32_t)k : wave_sum_u32(n2);
+    if (lane == 0) {
         S_out[row] = S;
         rnorm_out[row] = tot ? (float)(1.0 / sqrt((double)tot)) : 0.0f;
     }
@@ -162,19 +235,42 @@ quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned ch
 template <int BITS>
 static void launch_quantize(const float *P, int64_t ldP, int64_t n, int32_t k, void *codes, float *S,
                             float *rnorm, hipStream_t st) {
-    constexpr int E = BITS == 8 ? 4 : (BITS == 4 ? 8 : 1);
-    const bool cached = ((k + kQThreads * E - 1) / (kQThreads * E)) * E <= kQMaxRegs;
+    constexpr int E = 4;
+    const int groups = (k + kQThreads * E - 1) / (kQThreads * E);
     const int vec = ((uintptr_t)P % 16 == 0 && ldP % 4 == 0) ? 1 : 0;
+    if (k <= 8192) {
+        // wavefront per row; 4 rows per workgroup
+        for (int64_t r0 = 0; r0 < n; r0 += 0x40000000) {
+            const int64_t rows = n - r0 < 0x40000000 ? n - r0 : 0x40000000;
+            const float *p = P + r0 * ldP;
+            unsigned char *c = (unsigned char *)codes + r0 * ((int64_t)k * BITS / 8);
+            const dim3 grid((unsigned)((rows + 3) / 4)), block(kQThreads);
+#define QLESS_QW(NG) do { \
+                if (vec) hipLaunchKernelGGL((quantize_wave_kernel<BITS, NG, true>), grid, block, 0, st, p, ldP, rows, k, c, S + r0, rnorm + r0); \
+                else hipLaunchKernelGGL((quantize_wave_kernel<BITS, NG, false>), grid, block, 0, st, p, ldP, rows, k, c, S + r0, rnorm + r0); } while (0)
+            if (k <= 2048) QLESS_QW(8);
+            else if (k <= 4096) QLESS_QW(16);
+            else QLESS_QW(32);
+#undef QLESS_QW
+        }
+        return;
+    }
     // grid.x is limited to 2^31-1 rows per launch
     for (int64_t r0 = 0; r0 < n; r0 += 0x40000000) {
         const int64_t rows = n - r0 < 0x40000000 ? n - r0 : 0x40000000;
         const float *p = P + r0 * ldP;
         unsigned char *c = (unsigned char *)codes + r0 * ((int64_t)k * BITS / 8);
-        if (cached)
-            hipLaunchKernelGGL((quantize_kernel<BITS, true>), dim3((unsigned)rows), dim3(kQThreads), 0, st,
+        if (groups <= 4)
+            hipLaunchKernelGGL((quantize_kernel<BITS, 4>), dim3((unsigned)rows), dim3(kQThreads), 0, st,
+                               p, ldP, k, c, S + r0, rnorm + r0, vec);
+        else if (groups <= 8)
+            hipLaunchKernelGGL((quantize_kernel<BITS, 8>), dim3((unsigned)rows), dim3(kQThreads), 0, st,
+                               p, ldP, k, c, S + r0, rnorm + r0, vec);
+        else if (groups <= 16)
+            hipLaunchKernelGGL((quantize_kernel<BITS, 16>), dim3((unsigned)rows), dim3(kQThreads), 0, st,
                                p, ldP, k, c, S + r0, rnorm + r0, vec);
         else
-            hipLaunchKernelGGL((quantize_kernel<BITS, false>), dim3((unsigned)rows), dim3(kQThreads), 0, st,
+            hipLaunchKernelGGL((quantize_kernel<BITS, 0>), dim3((unsigned)rows), dim3(kQThreads), 0, st,
                                p, ldP, k, c, S + r0, rnorm + r0, vec);
     }
 }
