@@ -42,6 +42,24 @@ __host__ __device__ inline uint32_t key_word(RowKey key, uint32_t counter) {
     return x;
 }
 
+// Asynchronous 16-byte global -> LDS copy (no VGPR staging): lane L of the wavefront writes LDS
+// bytes [lds_addr + 16 L, +16) with the 16 bytes at its own global address.  lds_addr must be
+// wave-uniform.  Completion is tracked by vmcnt like any vector load; wait_vmcnt<N> blocks until
+// at most N of the wavefront's vector memory operations are outstanding (they retire in order).
+__device__ inline void global_to_lds16(const void *gptr, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(lds_addr), "v"(gptr) : "memory");
+}
+// Same with a wave-uniform base address (SGPR pair) plus an unsigned 32-bit lane offset.
+__device__ inline void global_to_lds16(const void *base, unsigned lane_off, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
+}
+template <int N> __device__ inline void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
 inline qless_status launch_status() {
     return hipGetLastError() == hipSuccess ? QLESS_OK : QLESS_ERR_DEVICE;
 }

@@ -109,9 +109,17 @@ __device__ inline uint4 load_chunk(const ProjectArgs &a, int64_t row, int64_t co
 
 union Frag { bf16x8 v; bf16x2 p[4]; uint4 u; uint32_t w[4]; };
 
-template <bool IN_F32, bool ALIGNED, bool GAUSS>
+// DIRECT: gradient tiles go global -> LDS asynchronously (no VGPR staging) into a ring of kRing
+// unpadded, XOR-swizzled stage buffers, three stages ahead of the MFMAs.  It needs bf16 input,
+// 16-byte aligned rows and a gradient length that is a multiple of the stage width; every other
+// case stages through registers into two padded buffers.
+constexpr int kRing = 4;
+constexpr int kDirectStageBytes = kTileRows * kStageD * 2;
+
+template <bool IN_F32, bool ALIGNED, bool GAUSS, bool DIRECT>
 __global__ void __launch_bounds__(kWaves * 64, 2)
 project_kernel(ProjectArgs a, GaussTable gt) {
+    static_assert(!DIRECT || (!IN_F32 && ALIGNED), "direct LDS copies move bf16 rows as they are");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // XCD-aware decode: consecutive workgroup ids land on different XCDs, so the ktiles
     // workgroups that share one gradient slice are given ids 8 apart (same XCD, same L2).
@@ -132,7 +140,7 @@ project_kernel(ProjectArgs a, GaussTable gt) {
     if (c_end > a.d_len) c_end = a.d_len;
     const int nstages = (int)((c_end - c_begin + kStageD - 1) / kStageD);
 
-    uint16_t *gtab = (uint16_t *)(smem + 2 * kStageBytes);
+    uint16_t *gtab = (uint16_t *)(smem + (DIRECT ? kRing * kDirectStageBytes : 2 * kStageBytes));
     if (GAUSS && tid < 256) { gtab[tid] = gt.v[tid]; }
 
     // row keys of this lane's four 32-row blocks
@@ -155,17 +163,17 @@ project_kernel(ProjectArgs a, GaussTable gt) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[nb][kb][v] = 0.0f;
 
-    // staging: 64 rows x 16 chunks of 8 columns; thread handles chunks tid + kThreads*i
+    // staging (register path): 64 rows x 16 chunks of 8 columns; thread handles chunks tid + kThreads*i
     constexpr int kThreads = kWaves * 64;
     constexpr int kChunksPerThread = kTileRows * (kStageD / 8) / kThreads;
-    uint4 stage_regs[kChunksPerThread];
+    uint4 stage_regs[DIRECT ? 1 : kChunksPerThread];
     auto fetch = [&](int s) {
         const int64_t cs = c_begin + (int64_t)s * kStageD;
 #pragma unroll
         for (int i = 0; i < kChunksPerThread; ++i) {
             int c = tid + kThreads * i;
             int r = c >> 4, cc = c & 15;
-            stage_regs[i] = load_chunk<IN_F32, ALIGNED>(a, row0 + r, cs + cc * 8, c_end);
+            stage_regs[DIRECT ? 0 : i] = load_chunk<IN_F32, ALIGNED>(a, row0 + r, cs + cc * 8, c_end);
         }
     };
     auto commit = [&](int buf) {
@@ -173,18 +181,68 @@ project_kernel(ProjectArgs a, GaussTable gt) {
         for (int i = 0; i < kChunksPerThread; ++i) {
             int c = tid + kThreads * i;
             int r = c >> 4, cc = c & 15;
-            *(uint4 *)(smem + buf * kStageBytes + r * kLdsStride + cc * 16) = stage_regs[i];
+            *(uint4 *)(smem + buf * kStageBytes + r * kLdsStride + cc * 16) = stage_regs[DIRECT ? 0 : i];
         }
     };
 
-    fetch(0);
-    commit(0);
-    __syncthreads();
+    // staging (direct path): a stage is 64 rows x 256 bytes = 16 wavefront copies of 1 KB, two per
+    // wave.  Copy q fills LDS chunks 64 q .. 64 q + 63 (rows 4 q .. 4 q + 3); chunk `pos` of row r
+    // holds gradient chunk pos ^ (r & 15), so 16 consecutive rows read the same gradient chunk
+    // from 16 different bank groups.  Rows past n re-read row n-1 (never stored).
+    constexpr int kCopies = kDirectStageBytes / 1024 / kWaves;
+    const unsigned char *cptr[kCopies];
+    unsigned cdst[kCopies];
+    const unsigned lds0 = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)smem);
+    const int uwave = __builtin_amdgcn_readfirstlane(wave);
+    if (DIRECT) {
+#pragma unroll
+        for (int u = 0; u < kCopies; ++u) {
+            const int q = uwave * kCopies + u;
+            const int r = 4 * q + (lane >> 4), pos = lane & 15;
+            int64_t grow = row0 + r;
+            if (grow > a.n - 1) grow = a.n - 1;
+            cptr[u] = (const unsigned char *)a.G + (grow * a.ldG + c_begin) * 2 + ((pos ^ (r & 15)) << 4);
+            cdst[u] = (unsigned)q * 1024u;
+        }
+    }
+    auto issue = [&](int s) {                      // start the copies of stage s (ring slot s % kRing)
+        const unsigned buf = lds0 + (unsigned)(s % kRing) * kDirectStageBytes;
+#pragma unroll
+        for (int u = 0; u < kCopies; ++u) {
+            global_to_lds16(cptr[u], buf + cdst[u]);
+            cptr[u] += kStageD * 2;
+        }
+    };
+    // A fragment (rows 32 nb + l32, columns 64 bp + 32 half + 8 ks .. +7) of the stage in `slot`
+    const unsigned a_sw = (unsigned)(((4 * half) ^ (l32 & 15)) << 4);
+    auto read_a = [&](int slot, int nb, int bp, int ks) -> uint4 {
+        if (DIRECT)
+            return *(const uint4 *)(smem + slot * kDirectStageBytes + (32 * nb + l32) * (kStageD * 2) +
+                                    (a_sw ^ (unsigned)((8 * bp + ks) << 4)));
+        return *(const uint4 *)(smem + slot * kStageBytes + (32 * nb + l32) * kLdsStride +
+                                (64 * bp + 32 * half + 8 * ks) * 2);
+    };
+
+    if (DIRECT) {
+#pragma unroll
+        for (int s = 0; s < kRing - 1; ++s)
+            if (s < nstages) issue(s);
+    } else {
+        fetch(0);
+        commit(0);
+        __syncthreads();
+    }
 
     for (int s = 0; s < nstages; ++s) {
-        const int buf = s & 1;
-        if (s + 1 < nstages) fetch(s + 1);
-        const unsigned char *sa = smem + buf * kStageBytes;
+        const int buf = DIRECT ? s % kRing : (s & 1);
+        if (DIRECT) {
+            // stage s is the oldest copy group in flight; two younger ones may stay outstanding
+            if (s + kRing - 2 < nstages) wait_vmcnt<(kRing - 2) * kCopies>(); else wait_vmcnt<0>();
+            __syncthreads();                       // stage s visible to all waves; slot of stage s-1 free
+            if (s + kRing - 1 < nstages) issue(s + kRing - 1);
+        } else {
+            if (s + 1 < nstages) fetch(s + 1);
+        }
         const int64_t cs = c_begin + (int64_t)s * kStageD;       // multiple of 128
         const uint32_t wstage = a.wbase + (uint32_t)(cs >> 5);
 #pragma unroll
@@ -195,8 +253,7 @@ project_kernel(ProjectArgs a, GaussTable gt) {
             for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
-                    af[nb][ks].u = *(const uint4 *)(sa + (32 * nb + l32) * kLdsStride +
-                                                    (64 * bp + 32 * half + 8 * ks) * 2);
+                    af[nb][ks].u = read_a(buf, nb, bp, ks);
             const uint32_t wpair = wstage + 2u * bp;             // word index of lanes 0..31
 #pragma unroll
             for (int kb = 0; kb < 4; ++kb) {
@@ -232,8 +289,10 @@ project_kernel(ProjectArgs a, GaussTable gt) {
                 }
             }
         }
-        if (s + 1 < nstages) commit(buf ^ 1);
-        __syncthreads();
+        if (!DIRECT) {
+            if (s + 1 < nstages) commit(buf ^ 1);
+            __syncthreads();
+        }
     }
 
     // partial tile -> workspace [split][n][k];  D[i][j]: j = lane%32, i = 8*(v/4) + 4*(lane/32) + v%4
@@ -315,16 +374,27 @@ extern "C" qless_status qless_project(const void *G, qless_dtype dt, int64_t n, 
         if (gauss) { const uint16_t *t = gaussian_table_bf16(); for (int i = 0; i < 256; ++i) gt.v[i] = t[i]; }
         const size_t esz = dt == QLESS_F32 ? 4 : 2;
         const bool aligned = ((uintptr_t)G % 16 == 0) && ((ldG * esz) % 16 == 0);
-        const size_t lds = 2 * kStageBytes + 512;
+        const bool direct = dt == QLESS_BF16 && aligned && d_len % kStageD == 0;
+        const size_t lds = (direct ? (size_t)kRing * kDirectStageBytes : (size_t)2 * kStageBytes) + 512;
         dim3 grid((unsigned)plan.grid), block(kWaves * 64);
-#define QLESS_LAUNCH(F32, AL, GA) \
-        hipLaunchKernelGGL((project_kernel<F32, AL, GA>), grid, block, lds, st, a, gt)
+        // more than 64 KB of dynamic LDS has to be allowed per kernel (host-side attribute, no device work)
+#define QLESS_LAUNCH(F32, AL, GA, DI) do { \
+            static bool once = false; \
+            if (!once) { \
+                if (hipFuncSetAttribute((const void *)project_kernel<F32, AL, GA, DI>, \
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
+                    return QLESS_ERR_DEVICE; \
+                once = true; \
+            } \
+            hipLaunchKernelGGL((project_kernel<F32, AL, GA, DI>), grid, block, lds, st, a, gt); } while (0)
         if (dt == QLESS_F32) {
-            if (aligned) { if (gauss) QLESS_LAUNCH(true, true, true); else QLESS_LAUNCH(true, true, false); }
-            else         { if (gauss) QLESS_LAUNCH(true, false, true); else QLESS_LAUNCH(true, false, false); }
+            if (aligned) { if (gauss) QLESS_LAUNCH(true, true, true, false); else QLESS_LAUNCH(true, true, false, false); }
+            else         { if (gauss) QLESS_LAUNCH(true, false, true, false); else QLESS_LAUNCH(true, false, false, false); }
+        } else if (direct) {
+            if (gauss) QLESS_LAUNCH(false, true, true, true); else QLESS_LAUNCH(false, true, false, true);
         } else {
-            if (aligned) { if (gauss) QLESS_LAUNCH(false, true, true); else QLESS_LAUNCH(false, true, false); }
-            else         { if (gauss) QLESS_LAUNCH(false, false, true); else QLESS_LAUNCH(false, false, false); }
+            if (aligned) { if (gauss) QLESS_LAUNCH(false, true, true, false); else QLESS_LAUNCH(false, true, false, false); }
+            else         { if (gauss) QLESS_LAUNCH(false, false, true, false); else QLESS_LAUNCH(false, false, false, false); }
         }
 #undef QLESS_LAUNCH
         if (launch_status() != QLESS_OK) return QLESS_ERR_DEVICE;

@@ -297,19 +297,6 @@ __global__ void score_finish_kernel(const unsigned int *smax, int64_t N, float *
         score[i] = f32_from_order_key(smax[i]);
 }
 
-// Asynchronous 16-byte global -> LDS copy (no VGPR staging): lane L of the wavefront writes
-// LDS bytes [lds_addr + 16 L, +16) with the 16 bytes at its own global address.  lds_addr must be
-// wave-uniform.  Completion is tracked by vmcnt like any vector load.
-// The global address is a wave-uniform base (SGPR pair) plus an unsigned 32-bit lane offset.
-__device__ inline void global_to_lds16(const void *base, unsigned lane_off, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
-}
-template <int N> __device__ inline void wait_vmcnt() {
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
-}
-
 template <int BITS>
 __global__ void __launch_bounds__(512, 2)
 score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {

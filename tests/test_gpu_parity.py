@@ -49,7 +49,8 @@ def test_generator_words_match_oracle_and_golden_file():
 # --------------------------------------------------------------------------------- projection
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("kind", [Q.RADEMACHER, Q.GAUSSIAN])
-@pytest.mark.parametrize("n,d,k", [(70, 5000, 576), (3, 333, 64), (130, 4099, 1088)])
+@pytest.mark.parametrize("n,d,k", [(70, 5000, 576), (3, 333, 64), (130, 4099, 1088), (66, 5120, 576),
+                                   (5, 128, 64), (64, 16384, 2048)])
 def test_projection_parity_ragged(dtype, kind, n, d, k):
     _say("project n=%d d=%d k=%d kind=%d %s" % (n, d, k, kind, dtype))
     g = torch.Generator().manual_seed(n * 1000 + d)
