@@ -102,12 +102,16 @@ qless_status qless_quantize(const float *P, int64_t ldP, int64_t n, int32_t k, i
  *   ((float)D * rnorm_i(z)) * (eta[i] * rnorm'_i(z')),  added over i = 0..C-1 starting from +0,
  * each operation rounded once (no fused multiply-add).
  *
- *   train_codes, val_codes   host arrays of C device pointers to N (resp. M) packed rows
+ *   train_codes, val_codes   host arrays of C device pointers to N (resp. M) packed rows, each
+ *                            pointer 16-byte aligned
  *   train_rnorm, val_rnorm   host arrays of C device pointers to N (resp. M) fp32
  *   eta        host, C learning-rate weights;  1 <= C <= QLESS_MAX_CHECKPOINTS
+ *   k          a multiple of 64, at most 65536 (integer dot products stay inside int32)
  *   score      device, N fp32, or NULL
  *   full       device, N x M fp32 row-major receiving acc, or NULL (at least one of the two)
- *   ws         device workspace of at least qless_score_workspace(N, M, k, bits, C) bytes
+ *   ws         device workspace, 16-byte aligned, of at least qless_score_workspace(N, M, k, bits, C)
+ *              bytes (0 for the configurations that need none).  It holds the validation codes
+ *              expanded to int8 for the matrix-core path and the running row maxima.
  * N == 0 is valid; M >= 1.
  * ------------------------------------------------------------------------------------------- */
 size_t qless_score_workspace(int64_t N, int32_t M, int32_t k, int bits, int C);

@@ -1,6 +1,15 @@
-// Shared host/device helpers of the HIP library (status handling, the R generator).
-// The generator is specified in prose in the design notes; this is the library's own
-// implementation of that specification (the CPU oracle has a separate one).
+// Shared host/device helpers of the HIP library: status handling, asynchronous LDS copies and
+// the generator of the projection matrix R (paper Eq.(1): a random Rademacher or Gaussian map,
+// Sec. 2.4; the paper fixes no generator).  R is never stored; entry (m, j) is a pure function
+// of (seed, m, j):
+//   mix(x):  x ^= x>>16; x *= 0x85EBCA6B; x ^= x>>13; x *= 0xC2B2AE35; x ^= x>>16      (mod 2^32)
+//   s0 = mix(seed_lo + 0x9E3779B9),  s1 = mix(seed_hi ^ s0 ^ 0x7F4A7C15)
+//   keyA(m) = mix(s1 + m*0x9E3779B1),  keyB(m) = mix(keyA(m) ^ s0 ^ 0x5BD1E995)
+//   word(m, w, salt): x = keyA(m) + w*0x9E3779B1 + salt*0x68E31DA4;
+//                     x ^= x>>16; x *= 0x85EBCA6B; x ^= keyB(m); x ^= x>>13; x *= 0xC2B2AE35; x ^= x>>16
+//   Rademacher: R[m][j] = -1 iff bit beta(j%32) of word(m, j/32, 0) is set, beta(c) = 4*(c%8) + 3 - c/8
+//   Gaussian:   R[m][j] = T[byte (j%4) of word(m, j/4, 1)], T[i] = bf16(Phi^-1((i + 1/2)/256))
+// This file is the library's own implementation of that specification.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
