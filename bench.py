@@ -152,8 +152,8 @@ def main():
     extra = {}
     if not args.skip_scoring:
         del train_codes, train_rnorm
-        N4, M4 = 270000, 1024
-        for sb in (1, 8):
+        N4 = 270000
+        for sb, M4 in ((1, 1024), (8, 1024), (8, 8)):
             cbb = Q.code_bytes(k, sb)
             tc4, tr4 = synthetic_store(N4, 40, sb)
             vc4, vr4 = synthetic_store(M4, 50, sb)
@@ -175,14 +175,17 @@ def main():
             ts = e[0].elapsed_time(e[1]) / reps
             tt = e[1].elapsed_time(e[2]) / reps
             bytes_alg = C * (N4 + M4) * cbb + 4 * (N4 + M4) * C + 4 * N4
-            extra["score_%dbit" % sb] = {
-                "workload": "N=270000 M=1024 k=8192 C=4", "ms": round(ts, 3),
+            macs = float(N4) * M4 * C * k
+            extra["score_%dbit_M%d" % (sb, M4)] = {
+                "workload": "N=270000 M=%d k=8192 C=4" % M4, "ms": round(ts, 3),
                 "pair_scores_per_s": round(N4 * M4 / (ts * 1e-3), 1),
                 "dots_per_s": round(N4 * M4 * C / (ts * 1e-3), 1),
+                "int8_mfma_frac": round(macs / (ts * 1e-3) / 2.5e15, 4),
                 "hbm_frac": round(bytes_alg / (ts * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                 "topk_13500_ms": round(tt, 3)}
-            log("score %d-bit 270000x1024x4: %.2f ms (%.3g pair scores/s), topk %.3f ms" %
-                (sb, ts, N4 * M4 / (ts * 1e-3), tt))
+            log("score %d-bit 270000x%dx4: %.2f ms (%.3g pair scores/s, %.0f%% of int8 MFMA peak, %.0f%% of HBM peak), topk %.3f ms" %
+                (sb, M4, ts, N4 * M4 / (ts * 1e-3), 100 * macs / (ts * 1e-3) / 2.5e15,
+                 100 * bytes_alg / (ts * 1e-3) / 1e9 / PEAK_HBM_GBS, tt))
             del tc4, tr4, vc4, vr4
         # quantise throughput at the datastore size (HBM-bound kernel)
         Pq = torch.randn(32768, k, device=dev)

@@ -190,6 +190,8 @@ def score(train_codes, train_rnorm, val_codes, val_rnorm, eta, k, bits, want_ful
     tr = [np.ascontiguousarray(a, dtype=np.float32) for a in train_rnorm]
     vr = [np.ascontiguousarray(a, dtype=np.float32) for a in val_rnorm]
     eta = np.ascontiguousarray(eta, dtype=np.float32)
+    if not (len(tr) == len(vc) == len(vr) == eta.size == C):
+        raise ValueError("oracle score: one entry per checkpoint is needed in every list")
     N, M = tc[0].shape[0], vc[0].shape[0]
     sc = np.zeros(N, dtype=np.float32)
     full = np.zeros((N, M), dtype=np.float32) if want_full else None

@@ -150,6 +150,7 @@ def score(train_codes, train_rnorm, val_codes, val_rnorm, eta, k, bits, want_sco
           score_out=None, full_out=None, ws=None):
     """qless_score: per-checkpoint lists of device tensors -> score [N] (and/or full [N, M])."""
     C = len(train_codes)
+    assert len(train_rnorm) == C and len(val_codes) == C and len(val_rnorm) == C and len(eta) == C
     N, M = train_codes[0].shape[0], val_codes[0].shape[0]
     dev = val_codes[0].device
     for t in list(train_codes) + list(val_codes):

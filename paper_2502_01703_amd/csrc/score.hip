@@ -3,17 +3,16 @@
 // reduced by max over validation examples.
 //
 // Integer dot products are exact; how they are formed depends on the code width:
-//   1-bit   D = k - 2 popcount(a ^ b)                                   (XOR + V_BCNT)
-//   2-bit   D = popcount(nz_a & nz_b) - 2 popcount(nz_a & nz_b & (sg_a ^ sg_b))   (bit planes)
-//   8-bit   int8 x int8 -> int32 MFMA (v_mfma_i32_32x32x32_i8)
-//   4-bit   nibbles moved to the high half of a byte ((w<<4)&0xF0F0F0F0, w&0xF0F0F0F0) give int8
-//           operands 16 q; the MFMA accumulates 256 D, shifted back exactly.
+//   all widths, more than 16 val vectors: int8 x int8 -> int32 MFMA (v_mfma_i32_32x32x32_i8) on
+//           codes unpacked to int8 in registers (see score_mfma_kernel)
+//   1-bit, few val vectors   D = k - 2 popcount(a ^ b)                  (XOR + V_BCNT)
+//   2-bit, few val vectors   D = popcount(nz_a & nz_b) - 2 popcount(nz_a & nz_b & (sg_a ^ sg_b))
 // The fp32 epilogue is a fixed sequence of single operations (compiled without contraction):
 //   acc += ((float)D * rnorm_train) * (eta * rnorm_val), checkpoints in order, starting from +0.
 //
-// A workgroup owns a block of train rows and walks over all validation tiles, keeping the
-// running row maximum in registers, so every train code is read from HBM once per val tile
-// (and from L2 after the first) and `score` is written exactly once.
+// The popcount kernels give a workgroup a block of train rows and walk it over all validation
+// tiles with the running row maximum in registers; the MFMA kernel gives every (train tile, val
+// tile) pair its own workgroup and combines the row maxima with an exact integer atomicMax.
 #include "common.h"
 
 namespace qless {
@@ -202,17 +201,19 @@ score_popcount_kernel(ScoreArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// 8-bit / 4-bit / 1-bit at large M: int8 MFMA kernel.
+// int8 MFMA kernel for all four code widths.
 //
 // A small pre-pass expands the validation codes of every checkpoint to int8 rows (padded to the
 // tile size, in the K order in which the train operand is unpacked) together with
 // w'[c][z'] = eta_c * rnorm'_c(z') and, for 1-bit, vsum = sum of the +-1 codes of the row.
-// The main kernel runs one workgroup of 8 waves per (256 train rows) x (128 val rows) tile, each
-// wave 64 x 64 as 2 x 2 accumulators of v_mfma_i32_32x32x32_i8.  Train operands are unpacked in
-// registers on their way from LDS to the MFMA:
+// The main kernel runs one workgroup of 8 waves per (256 train rows) x (32 / 64 / 128 val rows)
+// tile with accumulators of v_mfma_i32_32x32x32_i8.  Train operands are unpacked in registers on
+// their way from LDS to the MFMA:
 //   8-bit  bytes as stored
 //   4-bit  (w<<4)&0xF0F0F0F0 and w&0xF0F0F0F0: bytes 16 q (even / odd elements); acc = 16 D
+//   2-bit  nz = (w_nz>>j)&0x01010101, sg likewise: bytes nz | sg*0xFE in {0, 1, 0xFF}
 //   1-bit  (w>>j)&0x01010101, j = 0..7: bytes a in {0,1} (1 = negative); D = vsum - 2 sum a v
+// Operand stages travel global -> LDS asynchronously through a ring of 3-4 swizzled buffers.
 // Workgroups of the same train tile get ids 8 apart, so they run on one XCD and share the train
 // rows through its L2; the row maximum over val tiles is combined with an order-preserving
 // integer atomicMax (exact, order independent) and decoded by a last small kernel.
@@ -220,9 +221,8 @@ score_popcount_kernel(ScoreArgs a) {
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(16))) int i32x16;
 
-constexpr int kMT = 256, kMV = 128;            // train / val rows per workgroup tile
-
-__host__ __device__ constexpr int mfma_stage_elems(int) { return 128; }
+constexpr int kMT = 256;                       // train rows per workgroup tile
+constexpr int kKE = 128;                       // code elements per pipeline stage
 
 struct ScorePrep {                             // workspace views (device pointers)
     int8_t *vexp;                              // [C][Mp][kp]
@@ -250,7 +250,7 @@ __device__ inline int val_source_element(int p) {
         const int d = i >> 2, b = i & 3;               // dword d, byte b
         return base + 8 * (d >> 1) + 2 * b + (d & 1);
     }
-    // 1-bit: K-step pair g (64 elements), step s, half h, dword jj, byte b
+    // bit planes: K-step pair g (64 elements), step s, half h, dword jj, byte b
     const int g = p >> 6, s = (p >> 5) & 1, h = (p >> 4) & 1, jj = (p >> 2) & 3, b = p & 3;
     return 64 * g + 32 * h + 8 * b + 4 * s + jj;
 }
@@ -269,7 +269,10 @@ score_prepare_kernel(ScoreArgs a, ScorePrep w) {
             const int m = val_source_element<BITS>(p);
             if (BITS == 8) q = (int8_t)src[m];
             else if (BITS == 4) { q = (src[m >> 1] >> (4 * (m & 1))) & 0xF; if (q & 8) q -= 16; }
-            else q = ((src[m >> 3] >> (m & 7)) & 1) ? -1 : 1;
+            else if (BITS == 2) {
+                const int nz = (src[m >> 3] >> (m & 7)) & 1, sg = (src[a.k / 8 + (m >> 3)] >> (m & 7)) & 1;
+                q = nz ? (sg ? -1 : 1) : 0;
+            } else q = ((src[m >> 3] >> (m & 7)) & 1) ? -1 : 1;
         }
         dst[p] = (int8_t)q;
         part += q;
@@ -297,19 +300,34 @@ __global__ void score_finish_kernel(const unsigned int *smax, int64_t N, float *
         score[i] = f32_from_order_key(smax[i]);
 }
 
-template <int BITS>
+// Shape of the 8 waves of a workgroup: WX waves across the val tile, 8 / WX down the 256 train
+// rows; each wave owns WR x WC accumulators of 32 x 32.  Val tile width VT = 32 WC WX:
+//   M > 64: <2, 2, 2> (64 x 64 per wave, VT = 128);  M <= 64: <1, 2, 1> (VT = 64);  M <= 32: <1, 1, 1>.
+template <int BITS, int WR, int WC, int WX>
+struct MfmaShape {
+    static constexpr int WY = 8 / WX;
+    static constexpr int VT = 32 * WC * WX;
+    static constexpr int TB = kKE * BITS / 8;            // train bytes per row per stage: 128 / 64 / 32 / 16
+    static constexpr int TCPR = TB / 16;                 // 16-byte chunks per train row
+    static constexpr int TRAIN_BYTES = kMT * TB, VAL_BYTES = VT * kKE;
+    static constexpr int TCH = kMT * TCPR, VCH = VT * (kKE / 16);
+    static constexpr int NINST = (TCH + VCH) / 64;       // wavefront-wide copies per stage
+    static constexpr int LPW = (NINST + 7) / 8;          // per wave
+    static constexpr int BUF = TRAIN_BYTES + VAL_BYTES + 1024;   // + 1 KB landing zone for padding copies
+    static constexpr int NBUF = (158 * 1024) / BUF >= 4 ? 4 : 3; // LDS ring depth
+    static_assert(32 * WR * WY == kMT, "8 waves cover the 256 train rows");
+    static_assert((TCH + VCH) % 64 == 0, "whole wavefront copies");
+    static_assert((158 * 1024) / BUF >= 3, "at least three stages fit");
+};
+
+template <int BITS, int WR, int WC, int WX>
 __global__ void __launch_bounds__(512, 2)
 score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
-    constexpr int KE = 128;                         // code elements per stage
-    constexpr int TB = KE * BITS / 8;               // train bytes per row per stage: 128 / 64 / 16
-    constexpr int TCPR = TB / 16;                   // 16-byte chunks per train row
-    constexpr int TRAIN_BYTES = kMT * TB, VAL_BYTES = kMV * KE;
-    constexpr int TCH = kMT * TCPR, VCH = kMV * (KE / 16);
-    constexpr int NINST = (TCH + VCH) / 64;         // wavefront-wide copies per stage: 48 / 32 / 20
-    constexpr int LPW = (NINST + 7) / 8;            // per wave: 6 / 4 / 3
-    constexpr int BUF = TRAIN_BYTES + VAL_BYTES + 1024;   // + 1 KB landing zone for padding copies
-    constexpr int NBUF = BITS == 8 ? 3 : 4;         // LDS ring: 3 x 49 KB, 4 x 33 KB, 4 x 21 KB
-    static_assert((TCH + VCH) % 64 == 0, "whole wavefront copies");
+    using Sh = MfmaShape<BITS, WR, WC, WX>;
+    constexpr int KE = kKE, TB = Sh::TB, TCPR = Sh::TCPR, VT = Sh::VT;
+    constexpr int TRAIN_BYTES = Sh::TRAIN_BYTES, VAL_BYTES = Sh::VAL_BYTES, TCH = Sh::TCH;
+    constexpr int NINST = Sh::NINST, LPW = Sh::LPW, BUF = Sh::BUF, NBUF = Sh::NBUF;
+    constexpr int TSTEP = BITS == 2 ? 16 : TB;      // bytes a train chunk's source advances per stage
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ unsigned int s_rowmax[kMT];
 
@@ -324,9 +342,10 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, l32 = lane & 31;
-    const int wy = wave >> 1, wx = wave & 1;        // 4 x 2 waves
+    const int wy = wave / WX, wx = wave % WX;
+    const int trow = wy * 32 * WR, vcol = wx * 32 * WC;   // this wave's corner inside the tile
     const int64_t row0 = tt * kMT;
-    const int v0 = vt * kMV;
+    const int v0 = vt * VT;
     const int64_t cb = (int64_t)a.k * BITS / 8;
     const int nstages = w.kp / KE;
     if (tid < kMT) s_rowmax[tid] = 0u;
@@ -335,9 +354,10 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     // ---- copy roles of this lane: LPW wavefront copies per stage -------------------------------
     // Copy q covers LDS chunks 64 q .. 64 q + 63 of the stage buffer, laid out [train rows][val rows]
     // without padding; inside a row the 16-byte chunks are XOR-swizzled so that the MFMA operand
-    // reads (16 consecutive rows, same chunk) hit distinct banks.
+    // reads (16 consecutive rows, same chunk) hit distinct banks.  2-bit train rows hold the
+    // "non-zero" chunk then the "negative" chunk of the stage (the planes are k/8 bytes apart).
     unsigned voff[LPW];         // lane offset from the stage's (uniform) train or val base
-    unsigned vcol[LPW];         // byte offset of the lane's chunk inside the stage (train copies)
+    unsigned vcolb[LPW];        // byte offset of the lane's chunk inside the stage (8/4-bit train copies)
     bool is_train[LPW];         // wave-uniform: a copy is all train chunks or all val chunks
     unsigned dst_off[LPW];      // wave-uniform LDS offset inside the buffer
 #pragma unroll
@@ -349,44 +369,47 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
         is_train[u] = qq * 64 < TCH;
         if (t < TCH) {
             const int r = t / TCPR, pos = t % TCPR;
-            const int c = BITS == 8 ? (pos ^ ((r >> 1) & 7)) : (BITS == 4 ? (pos ^ ((r >> 2) & 3)) : 0);
+            const int c = BITS == 8 ? (pos ^ ((r >> 1) & 7)) : (BITS == 4 ? (pos ^ ((r >> 2) & 3)) : pos);
             int64_t grow = row0 + r;
             if (grow > a.N - 1) grow = a.N - 1;          // rows past N re-read the last row (masked later)
-            voff[u] = (unsigned)((grow - row0) * cb) + c * 16;
-            vcol[u] = c * 16;
+            voff[u] = (unsigned)((grow - row0) * cb) + (BITS == 2 ? c * (a.k / 8) : c * 16);
+            vcolb[u] = c * 16;
         } else {
             const int tv = t - TCH;
             const int r = tv >> 3, pos = tv & 7;
             voff[u] = (unsigned)r * (unsigned)w.kp + (pos ^ ((r >> 1) & 7)) * 16;
-            vcol[u] = 0;
+            vcolb[u] = 0;
         }
     }
-    const bool ragged = (a.k % KE) != 0;             // last stage reaches past the end of the train rows
+    const bool ragged = BITS >= 4 && (a.k % KE) != 0;  // last stage reaches past the end of the train rows
 
     // ---- operand read addresses (swizzle folded into the lane's base, K-step applied by XOR) ---
-    unsigned a_base[2], b_base[2];
+    unsigned a_base[WR], b_base[WC];
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-        const int R = wy * 64 + 32 * b + l32;
+    for (int b = 0; b < WR; ++b) {
+        const int R = trow + 32 * b + l32;
         if (BITS == 8) a_base[b] = R * 128 + (((l32 >> 1) & 7) >> 1) * 32 + ((half ^ ((l32 >> 1) & 1)) * 16);
         else if (BITS == 4) a_base[b] = R * 64 + ((l32 >> 2) & 3) * 16 + half * 8;
-        else a_base[b] = R * 16 + half * 4;
-        const int Rv = wx * 64 + 32 * b + l32;
-        b_base[b] = TRAIN_BYTES + Rv * 128 + (((l32 >> 1) & 7) >> 1) * 32 + ((half ^ ((l32 >> 1) & 1)) * 16);
+        else a_base[b] = R * TB + half * 4;
+    }
+#pragma unroll
+    for (int c = 0; c < WC; ++c) {
+        const int Rv = vcol + 32 * c + l32;
+        b_base[c] = TRAIN_BYTES + Rv * 128 + (((l32 >> 1) & 7) >> 1) * 32 + ((half ^ ((l32 >> 1) & 1)) * 16);
     }
 
-    float facc[2][2][16];
+    float facc[WR][WC][16];
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < WR; ++b)
 #pragma unroll
-        for (int c = 0; c < 2; ++c)
+        for (int c = 0; c < WC; ++c)
 #pragma unroll
             for (int v = 0; v < 16; ++v) facc[b][c][v] = 0.0f;
 
     const int total = a.C * nstages;                 // stages over all checkpoints, one pipeline
     auto issue = [&](int g) {                        // start the copies of global stage g
         const int ci = g / nstages, s = g - ci * nstages;
-        const unsigned char *tbase = a.tc[ci] + row0 * cb + (int64_t)s * TB;
+        const unsigned char *tbase = a.tc[ci] + row0 * cb + (int64_t)s * TSTEP;
         const unsigned char *vbase = (const unsigned char *)w.vexp + ((size_t)ci * w.Mp + v0) * (size_t)w.kp + (size_t)s * KE;
         const unsigned buf = lds0 + (unsigned)(g % NBUF) * BUF;
         const bool tail = ragged && s == nstages - 1;
@@ -395,7 +418,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
             unsigned off = voff[u];
             if (tail && is_train[u]) {
                 // chunks past the row end re-read its last 16 bytes (the matching val bytes are zero)
-                const int64_t over = (int64_t)s * TB + vcol[u] - (cb - 16);
+                const int64_t over = (int64_t)s * TB + vcolb[u] - (cb - 16);
                 if (over > 0) off -= (unsigned)over;
             }
             global_to_lds16(is_train[u] ? tbase : vbase, off, buf + dst_off[u]);
@@ -409,11 +432,11 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
 
     int g = 0;
     for (int ci = 0; ci < a.C; ++ci) {
-        i32x16 acc[2][2];
+        i32x16 acc[WR][WC];
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < WR; ++b)
 #pragma unroll
-            for (int c = 0; c < 2; ++c)
+            for (int c = 0; c < WC; ++c)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[b][c][v] = 0;
 
@@ -424,36 +447,46 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
             __syncthreads();                         // stage g visible to all; buffer of stage g-1 free
             if (g + NBUF - 1 < total) issue(g + NBUF - 1);
             const unsigned char *sb = smem + (g % NBUF) * BUF;
-            if (BITS == 1) {
+            if (BITS <= 2) {
 #pragma unroll
                 for (int gp = 0; gp < KE / 64; ++gp) {          // K-step pairs
-                    i32x4 af[2][2];
+                    i32x4 af[WR][2];
 #pragma unroll
-                    for (int b = 0; b < 2; ++b) {
-                        const unsigned int wd = *(const unsigned int *)(sb + a_base[b] + 8 * gp);
+                    for (int b = 0; b < WR; ++b) {
+                        if (BITS == 1) {
+                            const unsigned int wd = *(const unsigned int *)(sb + a_base[b] + 8 * gp);
 #pragma unroll
-                        for (int jd = 0; jd < 8; ++jd)
-                            af[b][jd >> 2][jd & 3] = (int)((wd >> jd) & 0x01010101u);
+                            for (int jd = 0; jd < 8; ++jd)
+                                af[b][jd >> 2][jd & 3] = (int)((wd >> jd) & 0x01010101u);
+                        } else {
+                            const unsigned int wn = *(const unsigned int *)(sb + a_base[b] + 8 * gp);
+                            const unsigned int wg = *(const unsigned int *)(sb + a_base[b] + 16 + 8 * gp);
+#pragma unroll
+                            for (int jd = 0; jd < 8; ++jd) {
+                                const unsigned int tn = (wn >> jd) & 0x01010101u, tg = (wg >> jd) & 0x01010101u;
+                                af[b][jd >> 2][jd & 3] = (int)(tn | (tg * 0xFEu));   // bytes 0, 1 or 0xFF (-1)
+                            }
+                        }
                     }
 #pragma unroll
                     for (int s2 = 0; s2 < 2; ++s2) {
-                        i32x4 bf[2];
+                        i32x4 bf[WC];
 #pragma unroll
-                        for (int c = 0; c < 2; ++c)
+                        for (int c = 0; c < WC; ++c)
                             bf[c] = *(const i32x4 *)(sb + (b_base[c] ^ ((2 * gp + s2) << 5)));
 #pragma unroll
-                        for (int b = 0; b < 2; ++b)
+                        for (int b = 0; b < WR; ++b)
 #pragma unroll
-                            for (int c = 0; c < 2; ++c)
+                            for (int c = 0; c < WC; ++c)
                                 acc[b][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[b][s2], bf[c], acc[b][c], 0, 0, 0);
                     }
                 }
             } else {
 #pragma unroll
                 for (int ks = 0; ks < KE / 32; ++ks) {
-                    i32x4 af[2], bf[2];
+                    i32x4 af[WR], bf[WC];
 #pragma unroll
-                    for (int b = 0; b < 2; ++b) {
+                    for (int b = 0; b < WR; ++b) {
                         if (BITS == 8) {
                             af[b] = *(const i32x4 *)(sb + (a_base[b] ^ (ks << 5)));
                         } else {
@@ -463,36 +496,36 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
                         }
                     }
 #pragma unroll
-                    for (int c = 0; c < 2; ++c) bf[c] = *(const i32x4 *)(sb + (b_base[c] ^ (ks << 5)));
+                    for (int c = 0; c < WC; ++c) bf[c] = *(const i32x4 *)(sb + (b_base[c] ^ (ks << 5)));
 #pragma unroll
-                    for (int b = 0; b < 2; ++b)
+                    for (int b = 0; b < WR; ++b)
 #pragma unroll
-                        for (int c = 0; c < 2; ++c)
+                        for (int c = 0; c < WC; ++c)
                             acc[b][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[b], bf[c], acc[b][c], 0, 0, 0);
                 }
             }
         }
         // checkpoint epilogue.  acc[b][c][v]: train row 32b + 8(v/4) + 4 half + v%4, val col 32c + l32.
-        // Lane L of the wave holds rnorm of train row (wy*64 + L); rows are fetched by shuffle.
-        int64_t myrow = row0 + wy * 64 + lane;
+        // Lane L < 32 WR of the wave holds rnorm of train row (trow + L); rows are fetched by shuffle.
+        int64_t myrow = row0 + trow + (lane & (32 * WR - 1));
         if (myrow > a.N - 1) myrow = a.N - 1;
         const float rt_lane = a.tr[ci][myrow];
-        float wv[2];
-        int vs[2];
+        float wv[WC];
+        int vs[WC];
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const int col = v0 + wx * 64 + 32 * c + l32;            // < Mp (padded)
+        for (int c = 0; c < WC; ++c) {
+            const int col = v0 + vcol + 32 * c + l32;               // < Mp (padded)
             wv[c] = w.vw[ci * w.Mp + col];
             vs[c] = BITS == 1 ? w.vsum[ci * w.Mp + col] : 0;
         }
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < WR; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const float rt = __shfl(rt_lane, 32 * b + 8 * (v >> 2) + 4 * half + (v & 3), 64);
 #pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    const int D = BITS == 8 ? acc[b][c][v] : (BITS == 4 ? (acc[b][c][v] >> 4) : vs[c] - 2 * acc[b][c][v]);
+                for (int c = 0; c < WC; ++c) {
+                    const int D = BITS == 4 ? (acc[b][c][v] >> 4) : (BITS == 1 ? vs[c] - 2 * acc[b][c][v] : acc[b][c][v]);
                     const float t = __fmul_rn(__fmul_rn((float)D, rt), wv[c]);
                     facc[b][c][v] = __fadd_rn(facc[b][c][v], t);
                 }
@@ -500,15 +533,15 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     }
     // tile epilogue: optional full matrix, row maxima over this val tile
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < WR; ++b)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int rloc = wy * 64 + 32 * b + 8 * (v >> 2) + 4 * half + (v & 3);
+            const int rloc = trow + 32 * b + 8 * (v >> 2) + 4 * half + (v & 3);
             const int64_t r = row0 + rloc;
             float m = neg_inf();
 #pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const int col = v0 + wx * 64 + 32 * c + l32;
+            for (int c = 0; c < WC; ++c) {
+                const int col = v0 + vcol + 32 * c + l32;
                 if (col < a.M) {
                     m = fmaxf(m, facc[b][c][v]);
                     if (a.full && r < a.N) a.full[r * a.M + col] = facc[b][c][v];
@@ -526,12 +559,12 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     }
 }
 
-struct MfmaPlan { int32_t Mp, kp; size_t off_vw, off_vsum, off_smax, total; };
-static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int bits, int C) {
+struct MfmaPlan { int32_t vt, Mp, kp; size_t off_vw, off_vsum, off_smax, total; };
+static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int C) {
     MfmaPlan p{};
-    const int ke = mfma_stage_elems(bits);
-    p.Mp = (M + kMV - 1) / kMV * kMV;
-    p.kp = (k + ke - 1) / ke * ke;
+    p.vt = M > 64 ? 128 : (M > 32 ? 64 : 32);
+    p.Mp = (M + p.vt - 1) / p.vt * p.vt;
+    p.kp = (k + kKE - 1) / kKE * kKE;
     size_t o = (size_t)C * p.Mp * (size_t)p.kp;
     o = (o + 255) & ~(size_t)255;
     p.off_vw = o;   o += (size_t)C * p.Mp * 4;
@@ -541,32 +574,44 @@ static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int bits, int C) {
     p.total = o;
     return p;
 }
-static bool use_mfma_path(int bits, int32_t M, int32_t k) {
-    return bits == 8 || bits == 4 || (bits == 1 && M > 64 && k % 128 == 0);   // 1-bit rows must be 16-byte multiples
+// The bit planes are copied in 16-byte chunks: k must be a multiple of 128 for the 1-/2-bit codes.
+// With at most 16 validation vectors those codes are bandwidth-bound and their 16-byte stages are
+// too fine for the copy pipeline; the popcount kernels stream them faster.
+static bool use_mfma_path(int bits, int32_t M, int32_t k) { return bits >= 4 || (k % 128 == 0 && M > 16); }
+
+template <int BITS, int WR, int WC, int WX>
+static qless_status launch_mfma_shape(const ScoreArgs &a, const ScorePrep &w, hipStream_t st) {
+    using Sh = MfmaShape<BITS, WR, WC, WX>;
+    const size_t lds = (size_t)Sh::NBUF * Sh::BUF;
+    static bool once = false;
+    if (!once) {
+        if (hipFuncSetAttribute((const void *)score_mfma_kernel<BITS, WR, WC, WX>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return QLESS_ERR_DEVICE;
+        once = true;
+    }
+    const int64_t ttiles = (a.N + kMT - 1) / kMT;
+    const int vtiles = w.Mp / Sh::VT;
+    const int64_t grid = 8 * (int64_t)vtiles * ((ttiles + 7) / 8);
+    if (grid > 0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((score_mfma_kernel<BITS, WR, WC, WX>), dim3((unsigned)grid), dim3(512), lds, st, a, w,
+                       (int)ttiles, vtiles);
+    return QLESS_OK;
 }
 
 template <int BITS>
 static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st) {
-    const MfmaPlan p = mfma_plan(a.N, a.M, a.k, BITS, a.C);
+    const MfmaPlan p = mfma_plan(a.N, a.M, a.k, a.C);
     ScorePrep w{};
     unsigned char *base = (unsigned char *)ws;
     w.vexp = (int8_t *)base; w.vw = (float *)(base + p.off_vw); w.vsum = (int *)(base + p.off_vsum);
     w.smax = (unsigned int *)(base + p.off_smax); w.Mp = p.Mp; w.kp = p.kp;
     hipLaunchKernelGGL((score_prepare_kernel<BITS>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
-    constexpr int KE = mfma_stage_elems(BITS);
-    constexpr int TB = KE * BITS / 8;
-    const size_t lds = (size_t)(BITS == 8 ? 3 : 4) * (size_t)(kMT * TB + kMV * KE + 1024);
-    static bool once = false;
-    if (!once) {
-        if (hipFuncSetAttribute((const void *)score_mfma_kernel<BITS>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds) != hipSuccess) return QLESS_ERR_DEVICE;
-        once = true;
-    }
-    const int64_t ttiles = (a.N + kMT - 1) / kMT;
-    const int vtiles = p.Mp / kMV;
-    const int64_t grid = 8 * (int64_t)vtiles * ((ttiles + 7) / 8);
-    if (grid > 0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((score_mfma_kernel<BITS>), dim3((unsigned)grid), dim3(512), lds, st, a, w, (int)ttiles, vtiles);
+    qless_status rc;
+    if (p.vt == 128) rc = launch_mfma_shape<BITS, 2, 2, 2>(a, w, st);
+    else if (p.vt == 64) rc = launch_mfma_shape<BITS, 1, 2, 1>(a, w, st);
+    else rc = launch_mfma_shape<BITS, 1, 1, 1>(a, w, st);
+    if (rc != QLESS_OK) return rc;
     if (a.score) {
         int64_t blocks = (a.N + 255) / 256;
         if (blocks > 4096) blocks = 4096;
@@ -591,7 +636,7 @@ using namespace qless;
 extern "C" size_t qless_score_workspace(int64_t N, int32_t M, int32_t k, int bits, int C) {
     if (N < 0 || M < 1 || k <= 0 || C < 1 || !valid_bits(bits)) return 0;
     if (!use_mfma_path(bits, M, k)) return 0;
-    return mfma_plan(N, M, k, bits, C).total;
+    return mfma_plan(N, M, k, C).total;
 }
 
 extern "C" qless_status qless_score(const void *const *train_codes, const float *const *train_rnorm,
@@ -614,14 +659,16 @@ extern "C" qless_status qless_score(const void *const *train_codes, const float 
     if (N == 0) return QLESS_OK;
     hipStream_t st = (hipStream_t)stream;
     if (use_mfma_path(bits, M, k)) {
-        const size_t need = mfma_plan(N, M, k, bits, C).total;
+        const size_t need = mfma_plan(N, M, k, C).total;
         if (!ws || ws_bytes < need) return QLESS_ERR_WORKSPACE;
         if ((uintptr_t)ws % 16) return QLESS_ERR_INVALID_ARG;
         if (N > (int64_t)0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
         if (bits == 8) return launch_mfma<8>(a, ws, st);
         if (bits == 4) return launch_mfma<4>(a, ws, st);
+        if (bits == 2) return launch_mfma<2>(a, ws, st);
         return launch_mfma<1>(a, ws, st);
     }
+    // bit-plane codes with rows that are not multiples of 16 bytes, or very few val vectors: popcount kernels
     if (bits == 1) {
         if (M > 32) launch_popcount<1, 8, 4, 16, 16>(a, st);
         else if (M > 8) launch_popcount<1, 8, 4, 32, 8>(a, st);

@@ -151,7 +151,8 @@ def _datastore(n, k, bits, C, seed):
 
 @pytest.mark.parametrize("bits", [8, 4, 2, 1])
 @pytest.mark.parametrize("N,M,k,C", [(300, 70, 576, 3), (257, 1, 64, 1), (129, 8, 1024, 2),
-                                     (64, 33, 8192, 4), (1000, 130, 2048, 2)])
+                                     (64, 33, 8192, 4), (1000, 130, 2048, 2), (515, 17, 256, 3),
+                                     (260, 16, 128, 1), (40, 300, 384, 5)])
 def test_score_bit_exact(bits, N, M, k, C):
     _say("score bits=%d N=%d M=%d k=%d C=%d" % (bits, N, M, k, C))
     tc, tr = _datastore(N, k, bits, C, 1000 + bits)
@@ -159,7 +160,7 @@ def test_score_bit_exact(bits, N, M, k, C):
     if bits > 1:
         tc[0][5] = 0
         tr[0][5] = 0.0                                 # an all-zero code vector scores 0
-    eta = [1.0, 0.75, 0.5, 0.25][:C]
+    eta = [1.0, 0.75, 0.5, 0.25, 0.125][:C]
     ref_s, ref_f = oracle.score(tc, tr, vc, vr, eta, k, bits, want_full=True)
     dev = lambda arrs: [torch.from_numpy(a).to(DEV) for a in arrs]
     s, f = Q.score(dev(tc), dev(tr), dev(vc), dev(vr), eta, k, bits, want_full=True)
