@@ -1,9 +1,10 @@
 /*
  * qless.h -- C ABI of the MI355X (gfx950) QLESS gradient-datastore and influence engine.
  *
- * The four calls follow the pipeline of the QLESS paper (arXiv 2502.01703):
+ * The calls follow the pipeline of the QLESS paper (arXiv 2502.01703):
  *   qless_project   Eq.(1)        random projection of per-example gradients, d -> k
  *   qless_quantize  Eq.(4),(5)    absmax b-bit quantisation into the packed gradient datastore
+   qless_project_quantize        both of the above in one call
  *   qless_score     Eq.(6),(7)    normalised quantised cosine, learning-rate weighted over
  *                                 checkpoints, reduced by max over validation examples
  *   qless_topk      Sec. 4.1      selection of the highest-scoring training examples
@@ -93,6 +94,20 @@ qless_status qless_gaussian_table(float *host_out256);
  * ------------------------------------------------------------------------------------------- */
 qless_status qless_quantize(const float *P, int64_t ldP, int64_t n, int32_t k, int bits,
                             void *codes, float *S, float *rnorm, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Datastore build in one call (Sec. 3.1: project, then quantise and store): Eq.(1) followed by
+ * Eq.(4),(5) on the same rows without a round trip of P through memory.  Arguments as in
+ * qless_project (no accumulate: the call covers a whole gradient or one stand-alone slice; d_len >= 1)
+ * and qless_quantize.  codes, S, rnorm are bit-identical to qless_project followed by
+ * qless_quantize with the same arguments.
+ *   P     device, n x k fp32 with leading dimension ldP >= k receiving the projection, or NULL
+ *   ws    device workspace, 16-byte aligned, of at least qless_project_workspace(n, d_len, k) bytes
+ * ------------------------------------------------------------------------------------------- */
+qless_status qless_project_quantize(const void *G, qless_dtype dt, int64_t n, int64_t d_len, int64_t ldG,
+                                    int64_t d_offset, int32_t k, qless_proj kind, uint64_t seed,
+                                    int bits, void *codes, float *S, float *rnorm,
+                                    float *P, int64_t ldP, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Influence scores, Eq.(6),(7) (Sec. 3.2) and the max over validation examples:

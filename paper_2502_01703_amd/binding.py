@@ -29,6 +29,8 @@ EXPORTS = {
     "qless_generator_words": (_c.c_int, [_u64, _u32, _i32, _u32, _i32, _u32, _vp, _vp]),
     "qless_gaussian_table": (_c.c_int, [_vp]),
     "qless_quantize": (_c.c_int, [_vp, _i64, _i64, _i32, _c.c_int, _vp, _vp, _vp, _vp]),
+    "qless_project_quantize": (_c.c_int, [_vp, _c.c_int, _i64, _i64, _i64, _i64, _i32, _c.c_int, _u64, _c.c_int,
+                                          _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
     "qless_score_workspace": (_sz, [_i64, _i32, _i32, _c.c_int, _c.c_int]),
     "qless_score": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _c.c_int, _i64, _i32, _i32, _c.c_int, _vp, _vp,
                                _vp, _sz, _vp]),
@@ -136,6 +138,24 @@ def quantize(P, bits, codes=None, S=None, rnorm=None):
                                 _vp(codes.data_ptr()), _vp(S.data_ptr()), _vp(rnorm.data_ptr()), _stream()),
            "qless_quantize")
     return codes, S, rnorm
+
+
+def project_quantize(G, k, bits, kind=RADEMACHER, seed=0, d_offset=0, want_P=False, ws=None):
+    """qless_project_quantize: G [n, d] -> (codes, S, rnorm[, P]) in one call."""
+    assert G.is_cuda and G.dim() == 2 and G.stride(1) == 1
+    n, d = G.shape
+    dev = G.device
+    codes = torch.empty(n, code_bytes(k, bits) if bits in (1, 2, 4, 8) else k, dtype=torch.uint8, device=dev)
+    S = torch.empty(n, dtype=torch.float32, device=dev)
+    rnorm = torch.empty(n, dtype=torch.float32, device=dev)
+    P = torch.empty(n, k, dtype=torch.float32, device=dev) if want_P else None
+    ldG = G.stride(0) if n > 1 else max(d, G.stride(0))
+    w = _ws(project_workspace(n, d, k), dev, ws)
+    _check(lib().qless_project_quantize(_vp(G.data_ptr()), _dtype_code(G), n, d, ldG, d_offset, k, kind, seed,
+                                        bits, _vp(codes.data_ptr()), _vp(S.data_ptr()), _vp(rnorm.data_ptr()),
+                                        _vp(P.data_ptr()) if want_P else None, k,
+                                        _vp(w.data_ptr()), w.numel(), _stream()), "qless_project_quantize")
+    return (codes, S, rnorm, P) if want_P else (codes, S, rnorm)
 
 
 def score_workspace(N, M, k, bits, C):

@@ -74,6 +74,12 @@ inline qless_status launch_status() {
 }
 inline bool valid_bits(int bits) { return bits == 1 || bits == 2 || bits == 4 || bits == 8; }
 
+// quantize.hip: Eq.(4),(5) over n rows whose value at (row, m) is the sum, in ascending s, of
+// src[s * plane + row * ld + m] for s < nsplit; `keep` (or null) receives the summed rows in fp32.
+qless_status quantize_rows(const float *src, int64_t ld, int nsplit, size_t plane, float *keep, int64_t ldK,
+                           int64_t n, int32_t k, int bits, void *codes, float *S, float *rnorm,
+                           hipStream_t st);
+
 // Gaussian table (bf16 bit patterns), built once on the host
 const uint16_t *gaussian_table_bf16();
 

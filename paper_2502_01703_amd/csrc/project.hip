@@ -346,12 +346,14 @@ extern "C" size_t qless_project_workspace(int64_t n, int64_t d_len, int32_t k) {
     return make_plan(n, d_len, k).ws_bytes;
 }
 
-extern "C" qless_status qless_project(const void *G, qless_dtype dt, int64_t n, int64_t d_len,
-                                      int64_t ldG, int64_t d_offset, int32_t k, qless_proj kind,
-                                      uint64_t seed, int accumulate, float *P, int64_t ldP,
-                                      void *ws, size_t ws_bytes, void *stream) {
-    if (n < 0 || d_len < 0 || d_offset < 0 || k <= 0 || ldG < d_len || ldP < k) return QLESS_ERR_INVALID_ARG;
-    if ((n > 0 && !P) || (n > 0 && d_len > 0 && !G)) return QLESS_ERR_INVALID_ARG;
+// Validates the projection arguments shared by both entry points and launches the split-d
+// partial sums into ws ([nsplit][n][k]).  *nsplit_out = 0 when there is nothing to launch.
+static qless_status project_partials(const void *G, qless_dtype dt, int64_t n, int64_t d_len, int64_t ldG,
+                                     int64_t d_offset, int32_t k, qless_proj kind, uint64_t seed,
+                                     void *ws, size_t ws_bytes, hipStream_t st, int *nsplit_out) {
+    *nsplit_out = 0;
+    if (n < 0 || d_len < 0 || d_offset < 0 || k <= 0 || ldG < d_len) return QLESS_ERR_INVALID_ARG;
+    if (n > 0 && d_len > 0 && !G) return QLESS_ERR_INVALID_ARG;
     if (dt != QLESS_F32 && dt != QLESS_BF16) return QLESS_ERR_UNSUPPORTED;
     if (kind != QLESS_RADEMACHER && kind != QLESS_GAUSSIAN) return QLESS_ERR_UNSUPPORTED;
     if (k % 64 != 0 || d_offset % 32 != 0) return QLESS_ERR_UNSUPPORTED;
@@ -361,52 +363,81 @@ extern "C" qless_status qless_project(const void *G, qless_dtype dt, int64_t n, 
     ProjectPlan plan = make_plan(n, d_len, k);
     if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return QLESS_ERR_WORKSPACE;
     if (plan.grid > 0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
-    hipStream_t st = (hipStream_t)stream;
+    if (plan.nsplit == 0) return QLESS_OK;
 
-    if (plan.nsplit > 0) {
-        ProjectArgs a{};
-        a.G = G; a.ws = (float *)ws; a.n = n; a.d_len = d_len; a.ldG = ldG;
-        a.wbase = (uint32_t)(d_offset >> 5); a.k = k; a.sk = seed_keys(seed);
-        a.ktiles = (int32_t)plan.ktiles; a.nsplit = (int32_t)plan.nsplit;
-        a.slices = plan.slices; a.stages_per_split = plan.stages_per_split;
-        GaussTable gt{};
-        const bool gauss = kind == QLESS_GAUSSIAN;
-        if (gauss) { const uint16_t *t = gaussian_table_bf16(); for (int i = 0; i < 256; ++i) gt.v[i] = t[i]; }
-        const size_t esz = dt == QLESS_F32 ? 4 : 2;
-        const bool aligned = ((uintptr_t)G % 16 == 0) && ((ldG * esz) % 16 == 0);
-        const bool direct = dt == QLESS_BF16 && aligned && d_len % kStageD == 0;
-        const size_t lds = (direct ? (size_t)kRing * kDirectStageBytes : (size_t)2 * kStageBytes) + 512;
-        dim3 grid((unsigned)plan.grid), block(kWaves * 64);
-        // more than 64 KB of dynamic LDS has to be allowed per kernel (host-side attribute, no device work)
+    ProjectArgs a{};
+    a.G = G; a.ws = (float *)ws; a.n = n; a.d_len = d_len; a.ldG = ldG;
+    a.wbase = (uint32_t)(d_offset >> 5); a.k = k; a.sk = seed_keys(seed);
+    a.ktiles = (int32_t)plan.ktiles; a.nsplit = (int32_t)plan.nsplit;
+    a.slices = plan.slices; a.stages_per_split = plan.stages_per_split;
+    GaussTable gt{};
+    const bool gauss = kind == QLESS_GAUSSIAN;
+    if (gauss) { const uint16_t *t = gaussian_table_bf16(); for (int i = 0; i < 256; ++i) gt.v[i] = t[i]; }
+    const size_t esz = dt == QLESS_F32 ? 4 : 2;
+    const bool aligned = ((uintptr_t)G % 16 == 0) && ((ldG * esz) % 16 == 0);
+    const bool direct = dt == QLESS_BF16 && aligned && d_len % kStageD == 0;
+    const size_t lds = (direct ? (size_t)kRing * kDirectStageBytes : (size_t)2 * kStageBytes) + 512;
+    dim3 grid((unsigned)plan.grid), block(kWaves * 64);
+    // more than 64 KB of dynamic LDS has to be allowed per kernel (host-side attribute, no device work)
 #define QLESS_LAUNCH(F32, AL, GA, DI) do { \
-            static bool once = false; \
-            if (!once) { \
-                if (hipFuncSetAttribute((const void *)project_kernel<F32, AL, GA, DI>, \
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
-                    return QLESS_ERR_DEVICE; \
-                once = true; \
-            } \
-            hipLaunchKernelGGL((project_kernel<F32, AL, GA, DI>), grid, block, lds, st, a, gt); } while (0)
-        if (dt == QLESS_F32) {
-            if (aligned) { if (gauss) QLESS_LAUNCH(true, true, true, false); else QLESS_LAUNCH(true, true, false, false); }
-            else         { if (gauss) QLESS_LAUNCH(true, false, true, false); else QLESS_LAUNCH(true, false, false, false); }
-        } else if (direct) {
-            if (gauss) QLESS_LAUNCH(false, true, true, true); else QLESS_LAUNCH(false, true, false, true);
-        } else {
-            if (aligned) { if (gauss) QLESS_LAUNCH(false, true, true, false); else QLESS_LAUNCH(false, true, false, false); }
-            else         { if (gauss) QLESS_LAUNCH(false, false, true, false); else QLESS_LAUNCH(false, false, false, false); }
-        }
-#undef QLESS_LAUNCH
-        if (launch_status() != QLESS_OK) return QLESS_ERR_DEVICE;
-    } else if (accumulate) {
-        return QLESS_OK;                      // nothing to add
+        static bool once = false; \
+        if (!once) { \
+            if (hipFuncSetAttribute((const void *)project_kernel<F32, AL, GA, DI>, \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
+                return QLESS_ERR_DEVICE; \
+            once = true; \
+        } \
+        hipLaunchKernelGGL((project_kernel<F32, AL, GA, DI>), grid, block, lds, st, a, gt); } while (0)
+    if (dt == QLESS_F32) {
+        if (aligned) { if (gauss) QLESS_LAUNCH(true, true, true, false); else QLESS_LAUNCH(true, true, false, false); }
+        else         { if (gauss) QLESS_LAUNCH(true, false, true, false); else QLESS_LAUNCH(true, false, false, false); }
+    } else if (direct) {
+        if (gauss) QLESS_LAUNCH(false, true, true, true); else QLESS_LAUNCH(false, true, false, true);
+    } else {
+        if (aligned) { if (gauss) QLESS_LAUNCH(false, true, true, false); else QLESS_LAUNCH(false, true, false, false); }
+        else         { if (gauss) QLESS_LAUNCH(false, false, true, false); else QLESS_LAUNCH(false, false, false, false); }
     }
+#undef QLESS_LAUNCH
+    if (launch_status() != QLESS_OK) return QLESS_ERR_DEVICE;
+    *nsplit_out = (int)plan.nsplit;
+    return QLESS_OK;
+}
+
+extern "C" qless_status qless_project(const void *G, qless_dtype dt, int64_t n, int64_t d_len,
+                                      int64_t ldG, int64_t d_offset, int32_t k, qless_proj kind,
+                                      uint64_t seed, int accumulate, float *P, int64_t ldP,
+                                      void *ws, size_t ws_bytes, void *stream) {
+    if (ldP < k || (n > 0 && !P)) return QLESS_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    int nsplit = 0;
+    const qless_status rc = project_partials(G, dt, n, d_len, ldG, d_offset, k, kind, seed, ws, ws_bytes,
+                                             st, &nsplit);
+    if (rc != QLESS_OK || n == 0) return rc;
+    if (nsplit == 0 && accumulate) return QLESS_OK;       // nothing to add
     const int64_t total = n * (int64_t)k;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(project_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
-                       (const float *)ws, (int)plan.nsplit, n, k, accumulate, P, ldP);
+                       (const float *)ws, nsplit, n, k, accumulate, P, ldP);
     return launch_status();
+}
+
+extern "C" qless_status qless_project_quantize(const void *G, qless_dtype dt, int64_t n, int64_t d_len,
+                                               int64_t ldG, int64_t d_offset, int32_t k, qless_proj kind,
+                                               uint64_t seed, int bits, void *codes, float *S, float *rnorm,
+                                               float *P, int64_t ldP, void *ws, size_t ws_bytes,
+                                               void *stream) {
+    if (d_len <= 0 || (P && ldP < k)) return QLESS_ERR_INVALID_ARG;
+    if (n > 0 && (!codes || !S || !rnorm)) return QLESS_ERR_INVALID_ARG;
+    if (!valid_bits(bits)) return QLESS_ERR_UNSUPPORTED;
+    if (ws && (uintptr_t)ws % 16 != 0) return QLESS_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    int nsplit = 0;
+    const qless_status rc = project_partials(G, dt, n, d_len, ldG, d_offset, k, kind, seed, ws, ws_bytes,
+                                             st, &nsplit);
+    if (rc != QLESS_OK || n == 0) return rc;
+    return quantize_rows((const float *)ws, k, nsplit, (size_t)n * (size_t)k, P, ldP, n, k, bits, codes, S,
+                         rnorm, st);
 }
 
 extern "C" qless_status qless_generator_words(uint64_t seed, uint32_t m0, int32_t nrows,

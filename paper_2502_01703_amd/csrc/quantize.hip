@@ -58,20 +58,56 @@ __device__ inline int quant1(float p, float scale, float alpha) {
 // is every aligned group of 8 lanes for the bit planes.
 // Branch-free load of a thread's E elements: the address is clamped into the row, elements past
 // the row end become 0 by a select (so all of a thread's loads can be issued back to back).
+// The row's value at element m is p[m] + p[plane + m] + ... over nsplit planes, added in that
+// order (nsplit = 1 for an ordinary matrix; the fused projection passes its split-d partial sums).
 template <int E>
-__device__ inline void load_elems(const float *p, int base, int32_t k, bool vec, float (&v)[E]) {
+__device__ inline void load_elems(const float *p, int base, int32_t k, bool vec, int nsplit, size_t plane,
+                                  float (&v)[E]) {
     const bool in = base < k;
     const int b = in ? base : k - E;
     if (E >= 4 && vec) {
 #pragma unroll
         for (int e = 0; e < E; e += 4) {
-            const float4 f = *(const float4 *)(p + b + e);
+            float4 f = *(const float4 *)(p + b + e);
+            int s = 1;
+            for (; s + 4 <= nsplit; s += 4) {          // four planes in flight, added in plane order
+                float4 t[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) t[u] = *(const float4 *)(p + (size_t)(s + u) * plane + b + e);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    f.x = __fadd_rn(f.x, t[u].x); f.y = __fadd_rn(f.y, t[u].y);
+                    f.z = __fadd_rn(f.z, t[u].z); f.w = __fadd_rn(f.w, t[u].w);
+                }
+            }
+            for (; s < nsplit; ++s) {
+                const float4 t = *(const float4 *)(p + (size_t)s * plane + b + e);
+                f.x = __fadd_rn(f.x, t.x); f.y = __fadd_rn(f.y, t.y);
+                f.z = __fadd_rn(f.z, t.z); f.w = __fadd_rn(f.w, t.w);
+            }
             v[e] = in ? f.x : 0.0f; v[e + 1] = in ? f.y : 0.0f;
             v[e + 2] = in ? f.z : 0.0f; v[e + 3] = in ? f.w : 0.0f;
         }
     } else {
 #pragma unroll
-        for (int e = 0; e < E; ++e) { const float f = p[b + e]; v[e] = in ? f : 0.0f; }
+        for (int e = 0; e < E; ++e) {
+            float f = p[b + e];
+            for (int s = 1; s < nsplit; ++s) f = __fadd_rn(f, p[(size_t)s * plane + b + e]);
+            v[e] = in ? f : 0.0f;
+        }
+    }
+}
+
+// Optional fp32 copy of the (summed) row, written while it is in registers.
+template <int E>
+__device__ inline void keep_elems(float *dst, int base, int32_t k, bool vec, const float (&v)[E]) {
+    if (!dst || base >= k) return;
+    if (E >= 4 && vec) {
+#pragma unroll
+        for (int e = 0; e < E; e += 4) *(float4 *)(dst + base + e) = make_float4(v[e], v[e + 1], v[e + 2], v[e + 3]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < E; ++e) dst[base + e] = v[e];
     }
 }
 
@@ -132,7 +168,8 @@ __device__ inline void emit_elems(const float (&v)[E], int base, int32_t k, floa
 template <int BITS, int NG>   // NG > 0: the row fits NG register groups per thread; NG == 0: re-read it
 __global__ void __launch_bounds__(kQThreads)
 quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned char *__restrict__ codes,
-                float *__restrict__ S_out, float *__restrict__ rnorm_out, int vec) {
+                float *__restrict__ S_out, float *__restrict__ rnorm_out, int vec, int nsplit, size_t plane,
+                float *__restrict__ keep, int64_t ldK) {
     constexpr int E = 4;
     constexpr int GROUP = kQThreads * E;
     constexpr bool CACHED = NG > 0;
@@ -143,6 +180,7 @@ quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned ch
     const int64_t row = blockIdx.x;
     const float *p = P + row * ldP;
     unsigned char *crow = codes + row * ((int64_t)k * BITS / 8);
+    float *krow = keep ? keep + row * ldK : nullptr;
     const int ngroups = (k + GROUP - 1) / GROUP;
 
     float reg[MAXG][E];
@@ -151,14 +189,16 @@ quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned ch
 #pragma unroll
         for (int g = 0; g < MAXG; ++g) {
             if (g < ngroups) {
-                load_elems<E>(p, g * GROUP + tid * E, k, vec != 0, reg[g]);
+                load_elems<E>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[g]);
+                keep_elems<E>(krow, g * GROUP + tid * E, k, vec != 0, reg[g]);
 #pragma unroll
                 for (int e = 0; e < E; ++e) amax = fmaxf(amax, fabsf(reg[g][e]));
             }
         }
     } else {
         for (int g = 0; g < ngroups; ++g) {
-            load_elems<E>(p, g * GROUP + tid * E, k, vec != 0, reg[0]);
+            load_elems<E>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[0]);
+            keep_elems<E>(krow, g * GROUP + tid * E, k, vec != 0, reg[0]);
 #pragma unroll
             for (int e = 0; e < E; ++e) amax = fmaxf(amax, fabsf(reg[0][e]));
         }
@@ -177,7 +217,7 @@ quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned ch
             if (g < ngroups) emit_elems<BITS, E>(reg[g], g * GROUP + tid * E, k, scale, alpha, crow, lane, n2);
     } else {
         for (int g = 0; g < ngroups; ++g) {
-            load_elems<E>(p, g * GROUP + tid * E, k, vec != 0, reg[0]);
+            load_elems<E>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[0]);
             emit_elems<BITS, E>(reg[0], g * GROUP + tid * E, k, scale, alpha, crow, lane, n2);
         }
     }
@@ -204,7 +244,8 @@ template <int BITS, int NG, bool VEC>
 __global__ void __launch_bounds__(kQThreads)
 quantize_wave_kernel(const float *__restrict__ P, int64_t ldP, int64_t n, int32_t k,
                      unsigned char *__restrict__ codes, float *__restrict__ S_out,
-                     float *__restrict__ rnorm_out) {
+                     float *__restrict__ rnorm_out, int nsplit, size_t plane,
+                     float *__restrict__ keep, int64_t ldK) {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= n) return;                       // whole wavefront; nothing below synchronises
@@ -214,7 +255,8 @@ quantize_wave_kernel(const float *__restrict__ P, int64_t ldP, int64_t n, int32_
     float amax = 0.0f;
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-        load_elems<4>(p, g * 256 + lane * 4, k, VEC, reg[g]);
+        load_elems<4>(p, g * 256 + lane * 4, k, VEC, nsplit, plane, reg[g]);
+        keep_elems<4>(keep ? keep + row * ldK : nullptr, g * 256 + lane * 4, k, VEC, reg[g]);
 #pragma unroll
         for (int e = 0; e < 4; ++e) amax = fmaxf(amax, fabsf(reg[g][e]));
     }
@@ -232,22 +274,27 @@ quantize_wave_kernel(const float *__restrict__ P, int64_t ldP, int64_t n, int32_
     }
 }
 
+// Source rows: value(row, m) = sum over s < nsplit of P[s * plane + row * ldP + m].  A wavefront per
+// row when there are many short rows; a workgroup per row when rows are long, or when few rows
+// each sum many planes (more loads in flight per row).
 template <int BITS>
-static void launch_quantize(const float *P, int64_t ldP, int64_t n, int32_t k, void *codes, float *S,
-                            float *rnorm, hipStream_t st) {
+static void launch_quantize(const float *P, int64_t ldP, int nsplit, size_t plane, float *keep, int64_t ldK,
+                            int64_t n, int32_t k, void *codes, float *S, float *rnorm, hipStream_t st) {
     constexpr int E = 4;
     const int groups = (k + kQThreads * E - 1) / (kQThreads * E);
-    const int vec = ((uintptr_t)P % 16 == 0 && ldP % 4 == 0) ? 1 : 0;
-    if (k <= 8192) {
+    const int vec = ((uintptr_t)P % 16 == 0 && ldP % 4 == 0 && plane % 4 == 0 &&
+                     (!keep || ((uintptr_t)keep % 16 == 0 && ldK % 4 == 0))) ? 1 : 0;
+    if (k <= 8192 && (nsplit <= 1 || n >= 2048)) {
         // wavefront per row; 4 rows per workgroup
         for (int64_t r0 = 0; r0 < n; r0 += 0x40000000) {
             const int64_t rows = n - r0 < 0x40000000 ? n - r0 : 0x40000000;
             const float *p = P + r0 * ldP;
+            float *kp = keep ? keep + r0 * ldK : nullptr;
             unsigned char *c = (unsigned char *)codes + r0 * ((int64_t)k * BITS / 8);
             const dim3 grid((unsigned)((rows + 3) / 4)), block(kQThreads);
 #define QLESS_QW(NG) do { \
-                if (vec) hipLaunchKernelGGL((quantize_wave_kernel<BITS, NG, true>), grid, block, 0, st, p, ldP, rows, k, c, S + r0, rnorm + r0); \
-                else hipLaunchKernelGGL((quantize_wave_kernel<BITS, NG, false>), grid, block, 0, st, p, ldP, rows, k, c, S + r0, rnorm + r0); } while (0)
+                if (vec) hipLaunchKernelGGL((quantize_wave_kernel<BITS, NG, true>), grid, block, 0, st, p, ldP, rows, k, c, S + r0, rnorm + r0, nsplit, plane, kp, ldK); \
+                else hipLaunchKernelGGL((quantize_wave_kernel<BITS, NG, false>), grid, block, 0, st, p, ldP, rows, k, c, S + r0, rnorm + r0, nsplit, plane, kp, ldK); } while (0)
             if (k <= 2048) QLESS_QW(8);
             else if (k <= 4096) QLESS_QW(16);
             else QLESS_QW(32);
@@ -259,20 +306,28 @@ static void launch_quantize(const float *P, int64_t ldP, int64_t n, int32_t k, v
     for (int64_t r0 = 0; r0 < n; r0 += 0x40000000) {
         const int64_t rows = n - r0 < 0x40000000 ? n - r0 : 0x40000000;
         const float *p = P + r0 * ldP;
+        float *kp = keep ? keep + r0 * ldK : nullptr;
         unsigned char *c = (unsigned char *)codes + r0 * ((int64_t)k * BITS / 8);
-        if (groups <= 4)
-            hipLaunchKernelGGL((quantize_kernel<BITS, 4>), dim3((unsigned)rows), dim3(kQThreads), 0, st,
-                               p, ldP, k, c, S + r0, rnorm + r0, vec);
-        else if (groups <= 8)
-            hipLaunchKernelGGL((quantize_kernel<BITS, 8>), dim3((unsigned)rows), dim3(kQThreads), 0, st,
-                               p, ldP, k, c, S + r0, rnorm + r0, vec);
-        else if (groups <= 16)
-            hipLaunchKernelGGL((quantize_kernel<BITS, 16>), dim3((unsigned)rows), dim3(kQThreads), 0, st,
-                               p, ldP, k, c, S + r0, rnorm + r0, vec);
-        else
-            hipLaunchKernelGGL((quantize_kernel<BITS, 0>), dim3((unsigned)rows), dim3(kQThreads), 0, st,
-                               p, ldP, k, c, S + r0, rnorm + r0, vec);
+#define QLESS_QB(NG) hipLaunchKernelGGL((quantize_kernel<BITS, NG>), dim3((unsigned)rows), dim3(kQThreads), 0, st, \
+                                        p, ldP, k, c, S + r0, rnorm + r0, vec, nsplit, plane, kp, ldK)
+        if (groups <= 4) QLESS_QB(4);
+        else if (groups <= 8) QLESS_QB(8);
+        else if (groups <= 16) QLESS_QB(16);
+        else QLESS_QB(0);
+#undef QLESS_QB
     }
+}
+
+qless_status quantize_rows(const float *src, int64_t ld, int nsplit, size_t plane, float *keep, int64_t ldK,
+                           int64_t n, int32_t k, int bits, void *codes, float *S, float *rnorm,
+                           hipStream_t st) {
+    switch (bits) {
+        case 8: launch_quantize<8>(src, ld, nsplit, plane, keep, ldK, n, k, codes, S, rnorm, st); break;
+        case 4: launch_quantize<4>(src, ld, nsplit, plane, keep, ldK, n, k, codes, S, rnorm, st); break;
+        case 2: launch_quantize<2>(src, ld, nsplit, plane, keep, ldK, n, k, codes, S, rnorm, st); break;
+        default: launch_quantize<1>(src, ld, nsplit, plane, keep, ldK, n, k, codes, S, rnorm, st); break;
+    }
+    return launch_status();
 }
 
 }  // namespace qless
@@ -285,12 +340,5 @@ extern "C" qless_status qless_quantize(const float *P, int64_t ldP, int64_t n, i
     if (n > 0 && (!P || !codes || !S || !rnorm)) return QLESS_ERR_INVALID_ARG;
     if (!valid_bits(bits) || k % 64 != 0) return QLESS_ERR_UNSUPPORTED;
     if (n == 0) return QLESS_OK;
-    hipStream_t st = (hipStream_t)stream;
-    switch (bits) {
-        case 8: launch_quantize<8>(P, ldP, n, k, codes, S, rnorm, st); break;
-        case 4: launch_quantize<4>(P, ldP, n, k, codes, S, rnorm, st); break;
-        case 2: launch_quantize<2>(P, ldP, n, k, codes, S, rnorm, st); break;
-        default: launch_quantize<1>(P, ldP, n, k, codes, S, rnorm, st); break;
-    }
-    return launch_status();
+    return quantize_rows(P, ldP, 1, 0, nullptr, 0, n, k, bits, codes, S, rnorm, (hipStream_t)stream);
 }

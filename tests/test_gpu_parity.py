@@ -140,6 +140,30 @@ def test_quantize_strided_rows_and_literal_formula_boundary_rate():
             assert np.abs(gq.astype(int) - lit.astype(int)).max() == 1
 
 
+@pytest.mark.parametrize("bits", [8, 4, 2, 1])
+@pytest.mark.parametrize("n,d,k,dtype,kind", [(70, 5000, 576, torch.float32, 0), (64, 16384, 2048, torch.bfloat16, 0),
+                                              (3, 333, 64, torch.bfloat16, 1), (9, 40000, 16384, torch.bfloat16, 0),
+                                              (2100, 1024, 128, torch.bfloat16, 0)])
+def test_fused_project_quantize_matches_the_two_calls_and_the_oracle(bits, n, d, k, dtype, kind):
+    """One call for Eq.(1) then Eq.(4),(5): same bits as the two separate calls, and the codes are
+    the oracle's codes of the projection the call reports."""
+    _say("project_quantize n=%d d=%d k=%d bits=%d kind=%d %s" % (n, d, k, bits, kind, dtype))
+    g = torch.Generator().manual_seed(n + d + k)
+    G = (torch.randn(n, d, generator=g) * torch.exp(torch.randn(n, 1, generator=g))).to(dtype).to(DEV)
+    P = Q.project(G, k, kind=kind, seed=5)
+    codes, S, rn = Q.quantize(P, bits)
+    fc, fS, frn, fP = Q.project_quantize(G, k, bits, kind=kind, seed=5, want_P=True)
+    assert torch.equal(fP, P) and torch.equal(fc, codes) and torch.equal(fS, S) and torch.equal(frn, rn)
+    gc, gS, grn = Q.project_quantize(G, k, bits, kind=kind, seed=5)         # without the fp32 copy
+    assert torch.equal(gc, codes) and torch.equal(gS, S) and torch.equal(grn, rn)
+    oc, oS, orn = oracle.quantize(fP.cpu().numpy(), bits)
+    np.testing.assert_array_equal(fc.cpu().numpy(), oc)
+    np.testing.assert_array_equal(fS.cpu().numpy(), oS)
+    np.testing.assert_array_equal(frn.cpu().numpy(), orn)
+    ref = oracle.project(G.cpu(), k, kind=kind, seed=5)
+    assert _rel_l2(fP.cpu().numpy(), ref).max() <= 1e-2
+
+
 # ------------------------------------------------------------------------------------ scoring
 def _datastore(n, k, bits, C, seed):
     rng = np.random.default_rng(seed)

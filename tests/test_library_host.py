@@ -47,6 +47,25 @@ def test_project_argument_validation():
     assert f(one, 1, 0, 64, 64, 0, 64, 0, 0, 0, None, 64, None, 0, None) == OK                # n = 0
 
 
+def test_project_quantize_argument_validation():
+    L = binding.lib()
+    one = ctypes.c_void_p(16)
+    f = L.qless_project_quantize
+    a = lambda G=one, n=4, d=64, ldG=64, off=0, k=64, bits=8, codes=one, P=None, ldP=0, ws=one, wsb=1 << 30: (
+        G, 1, n, d, ldG, off, k, 0, 0, bits, codes, one, one, P, ldP, ws, wsb, None)
+    assert f(*a(d=0)) == INVALID
+    assert f(*a(codes=None)) == INVALID
+    assert f(*a(G=None)) == INVALID
+    assert f(*a(P=one, ldP=32)) == INVALID
+    assert f(*a(bits=3)) == UNSUPPORTED
+    assert f(*a(k=96)) == UNSUPPORTED
+    assert f(*a(off=16)) == UNSUPPORTED
+    assert f(*a(ws=None, wsb=0)) == WORKSPACE
+    assert f(*a(ws=ctypes.c_void_p(8))) == WORKSPACE
+    assert f(*a(wsb=64)) == WORKSPACE
+    assert f(*a(n=0, codes=None)) == OK
+
+
 def test_quantize_score_topk_argument_validation():
     L = binding.lib()
     one = ctypes.c_void_p(16)
