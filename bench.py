@@ -153,45 +153,52 @@ def main():
     if not args.skip_scoring:
         del train_codes, train_rnorm
         N4 = 270000
-        for sb, M4 in ((1, 1024), (8, 1024), (8, 8)):
+        oracle_sample = None
+        for sb in (1, 8):
             cbb = Q.code_bytes(k, sb)
             tc4, tr4 = synthetic_store(N4, 40, sb)
-            vc4, vr4 = synthetic_store(M4, 50, sb)
+            vc4f, vr4f = synthetic_store(1024, 50, sb)
             sc4 = torch.empty(N4, dtype=torch.float32, device=dev)
             ws4 = torch.empty(max(Q.topk_workspace(N4, 13500), 16), dtype=torch.uint8, device=dev)
-            wss = torch.empty(max(Q.score_workspace(N4, M4, k, sb, C), 16), dtype=torch.uint8, device=dev)
-            Q.score(tc4, tr4, vc4, vr4, eta, k, sb, score_out=sc4, ws=wss)
-            torch.cuda.synchronize()
-            reps = 3
-            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-            e[0].record()
-            for _ in range(reps):
+            for M4 in (1024, 64, 8):          # M = 1024: matrix-core bound; M = 8: HBM bound
+                vc4, vr4 = [v[:M4] for v in vc4f], [v[:M4] for v in vr4f]
+                wss = torch.empty(max(Q.score_workspace(N4, M4, k, sb, C), 16), dtype=torch.uint8, device=dev)
                 Q.score(tc4, tr4, vc4, vr4, eta, k, sb, score_out=sc4, ws=wss)
-            e[1].record()
-            for _ in range(reps):
-                Q.topk(sc4, 13500, ws=ws4)
-            e[2].record()
-            torch.cuda.synchronize()
-            ts = e[0].elapsed_time(e[1]) / reps
-            tt = e[1].elapsed_time(e[2]) / reps
-            bytes_alg = C * (N4 + M4) * cbb + 4 * (N4 + M4) * C + 4 * N4
-            macs = float(N4) * M4 * C * k
-            extra["score_%dbit_M%d" % (sb, M4)] = {
-                "workload": "N=270000 M=%d k=8192 C=4" % M4, "ms": round(ts, 3),
-                "pair_scores_per_s": round(N4 * M4 / (ts * 1e-3), 1),
-                "dots_per_s": round(N4 * M4 * C / (ts * 1e-3), 1),
-                "int8_mfma_frac": round(macs / (ts * 1e-3) / 2.5e15, 4),
-                "hbm_frac": round(bytes_alg / (ts * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-                "topk_13500_ms": round(tt, 3)}
-            log("score %d-bit 270000x%dx4: %.2f ms (%.3g pair scores/s, %.0f%% of int8 MFMA peak, %.0f%% of HBM peak), topk %.3f ms" %
-                (sb, M4, ts, N4 * M4 / (ts * 1e-3), 100 * macs / (ts * 1e-3) / 2.5e15,
-                 100 * bytes_alg / (ts * 1e-3) / 1e9 / PEAK_HBM_GBS, tt))
-            del tc4, tr4, vc4, vr4
+                torch.cuda.synchronize()
+                reps = 3
+                e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+                e[0].record()
+                for _ in range(reps):
+                    Q.score(tc4, tr4, vc4, vr4, eta, k, sb, score_out=sc4, ws=wss)
+                e[1].record()
+                for _ in range(reps):
+                    Q.topk(sc4, 13500, ws=ws4)
+                e[2].record()
+                torch.cuda.synchronize()
+                ts = e[0].elapsed_time(e[1]) / reps
+                tt = e[1].elapsed_time(e[2]) / reps
+                bytes_alg = C * (N4 + M4) * cbb + 4 * (N4 + M4) * C + 4 * N4
+                macs = float(N4) * M4 * C * k
+                mfma_frac = macs / (ts * 1e-3) / 2.5e15
+                hbm_frac = bytes_alg / (ts * 1e-3) / 1e9 / PEAK_HBM_GBS
+                extra["score_%dbit_M%d" % (sb, M4)] = {
+                    "workload": "N=270000 M=%d k=8192 C=4" % M4, "ms": round(ts, 3),
+                    "pair_scores_per_s": round(N4 * M4 / (ts * 1e-3), 1),
+                    "dots_per_s": round(N4 * M4 * C / (ts * 1e-3), 1),
+                    "int8_mfma_frac": round(mfma_frac, 4), "hbm_frac": round(hbm_frac, 4),
+                    "binding": "int8 mfma" if mfma_frac > hbm_frac else "hbm",
+                    "topk_13500_ms": round(tt, 3)}
+                log("score %d-bit 270000x%dx4: %.2f ms (%.3g pair scores/s, %.0f%% of int8 MFMA peak, %.0f%% of HBM peak), topk %.3f ms" %
+                    (sb, M4, ts, N4 * M4 / (ts * 1e-3), 100 * mfma_frac, 100 * hbm_frac, tt))
+            if sb == 1 and not args.skip_cpu:      # rows for the oracle's scoring sample
+                oracle_sample = ([t[:2048].cpu().numpy() for t in tc4], [t[:2048].cpu().numpy() for t in tr4],
+                                 [v.cpu().numpy() for v in vc4f], [v.cpu().numpy() for v in vr4f])
+            del tc4, tr4, vc4f, vr4f, vc4, vr4
         # quantise throughput at the datastore size (HBM-bound kernel)
-        Pq = torch.randn(32768, k, device=dev)
-        cq = torch.empty(32768, Q.code_bytes(k, 1), dtype=torch.uint8, device=dev)
-        sq = torch.empty(32768, dtype=torch.float32, device=dev)
-        rq = torch.empty(32768, dtype=torch.float32, device=dev)
+        Pq = torch.randn(N4, k, device=dev)
+        cq = torch.empty(N4, Q.code_bytes(k, 1), dtype=torch.uint8, device=dev)
+        sq = torch.empty(N4, dtype=torch.float32, device=dev)
+        rq = torch.empty(N4, dtype=torch.float32, device=dev)
         Q.quantize(Pq, 1, codes=cq, S=sq, rnorm=rq)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
@@ -200,12 +207,13 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         tq = e0.elapsed_time(e1) / 5
-        qbytes = 32768 * (4 * k + k // 8 + 8)
-        extra["quantize_1bit"] = {"workload": "n=32768 k=8192", "ms": round(tq, 3),
-                                  "vectors_per_s": round(32768 / (tq * 1e-3), 1),
+        qbytes = N4 * (4 * k + k // 8 + 8)
+        extra["quantize_1bit"] = {"workload": "n=270000 k=8192", "ms": round(tq, 3),
+                                  "vectors_per_s": round(N4 / (tq * 1e-3), 1),
                                   "GBps": round(qbytes / (tq * 1e-3) / 1e9, 1),
                                   "hbm_frac": round(qbytes / (tq * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
-        log("quantize 1-bit 32768x8192: %.3f ms = %.0f GB/s" % (tq, qbytes / (tq * 1e-3) / 1e9))
+        log("quantize 1-bit 270000x8192: %.3f ms = %.0f GB/s" % (tq, qbytes / (tq * 1e-3) / 1e9))
+        del Pq, cq
 
     # ----------------------------------------------------------------- CPU oracle on a bounded sample
     cpu = None
@@ -237,6 +245,14 @@ def main():
                "seconds": {"project_per_gradient": round(t_proj, 3), "quantize_64": round(t_quant, 4),
                            "score_64x512x4": round(t_score, 4), "topk": round(t_topk, 4)}}
         log("oracle: %.1f s per projected gradient on %d threads" % (t_proj, cpu["cores"]))
+        if not args.skip_scoring and oracle_sample is not None:
+            t0 = time.perf_counter()
+            oracle.score(*oracle_sample, eta, k, 1)
+            t_sc = time.perf_counter() - t0
+            cpu["scores"] = {"value": round(2048 * 1024 / t_sc, 1), "unit": "pair scores/s",
+                             "sample": "2048 of the 270000 train rows x 1024 val x 4 checkpoints, 1-bit, k=8192",
+                             "seconds": round(t_sc, 3)}
+            log("oracle: %.3g pair scores/s (1-bit, 2048x1024x4 sample, %.2f s)" % (2048 * 1024 / t_sc, t_sc))
 
     out = {"metric": METRIC, "value": round(grads_per_s, 2), "unit": "grads/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),

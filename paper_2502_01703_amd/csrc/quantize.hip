@@ -60,11 +60,13 @@ __device__ inline int quant1(float p, float scale, float alpha) {
 // the row end become 0 by a select (so all of a thread's loads can be issued back to back).
 // The row's value at element m is p[m] + p[plane + m] + ... over nsplit planes, added in that
 // order (nsplit = 1 for an ordinary matrix; the fused projection passes its split-d partial sums).
-template <int E>
+// SUM = false is the plain matrix (one plane): no loop, so a thread's loads go out back to back.
+template <int E, bool SUM>
 __device__ inline void load_elems(const float *p, int base, int32_t k, bool vec, int nsplit, size_t plane,
                                   float (&v)[E]) {
     const bool in = base < k;
     const int b = in ? base : k - E;
+    if (!SUM) nsplit = 1;
     if (E >= 4 && vec) {
 #pragma unroll
         for (int e = 0; e < E; e += 4) {
@@ -165,7 +167,7 @@ __device__ inline void emit_elems(const float (&v)[E], int base, int32_t k, floa
     }
 }
 
-template <int BITS, int NG>   // NG > 0: the row fits NG register groups per thread; NG == 0: re-read it
+template <int BITS, int NG, bool SUM>   // NG > 0: the row fits NG register groups per thread; NG == 0: re-read it
 __global__ void __launch_bounds__(kQThreads)
 quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned char *__restrict__ codes,
                 float *__restrict__ S_out, float *__restrict__ rnorm_out, int vec, int nsplit, size_t plane,
@@ -189,16 +191,16 @@ quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned ch
 #pragma unroll
         for (int g = 0; g < MAXG; ++g) {
             if (g < ngroups) {
-                load_elems<E>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[g]);
-                keep_elems<E>(krow, g * GROUP + tid * E, k, vec != 0, reg[g]);
+                load_elems<E, SUM>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[g]);
+                if (SUM) keep_elems<E>(krow, g * GROUP + tid * E, k, vec != 0, reg[g]);
 #pragma unroll
                 for (int e = 0; e < E; ++e) amax = fmaxf(amax, fabsf(reg[g][e]));
             }
         }
     } else {
         for (int g = 0; g < ngroups; ++g) {
-            load_elems<E>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[0]);
-            keep_elems<E>(krow, g * GROUP + tid * E, k, vec != 0, reg[0]);
+            load_elems<E, SUM>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[0]);
+            if (SUM) keep_elems<E>(krow, g * GROUP + tid * E, k, vec != 0, reg[0]);
 #pragma unroll
             for (int e = 0; e < E; ++e) amax = fmaxf(amax, fabsf(reg[0][e]));
         }
@@ -217,7 +219,7 @@ quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned ch
             if (g < ngroups) emit_elems<BITS, E>(reg[g], g * GROUP + tid * E, k, scale, alpha, crow, lane, n2);
     } else {
         for (int g = 0; g < ngroups; ++g) {
-            load_elems<E>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[0]);
+            load_elems<E, SUM>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[0]);
             emit_elems<BITS, E>(reg[0], g * GROUP + tid * E, k, scale, alpha, crow, lane, n2);
         }
     }
@@ -240,7 +242,7 @@ quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned ch
 
 // One wavefront per row, k <= 256 * NG * ... : lane L owns, for each group g < NG, the four
 // elements starting at 256 g + 4 L.
-template <int BITS, int NG, bool VEC>
+template <int BITS, int NG, bool VEC, bool SUM>
 __global__ void __launch_bounds__(kQThreads)
 quantize_wave_kernel(const float *__restrict__ P, int64_t ldP, int64_t n, int32_t k,
                      unsigned char *__restrict__ codes, float *__restrict__ S_out,
@@ -255,8 +257,8 @@ quantize_wave_kernel(const float *__restrict__ P, int64_t ldP, int64_t n, int32_
     float amax = 0.0f;
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-        load_elems<4>(p, g * 256 + lane * 4, k, VEC, nsplit, plane, reg[g]);
-        keep_elems<4>(keep ? keep + row * ldK : nullptr, g * 256 + lane * 4, k, VEC, reg[g]);
+        load_elems<4, SUM>(p, g * 256 + lane * 4, k, VEC, nsplit, plane, reg[g]);
+        if (SUM) keep_elems<4>(keep ? keep + row * ldK : nullptr, g * 256 + lane * 4, k, VEC, reg[g]);
 #pragma unroll
         for (int e = 0; e < 4; ++e) amax = fmaxf(amax, fabsf(reg[g][e]));
     }
@@ -284,7 +286,9 @@ static void launch_quantize(const float *P, int64_t ldP, int nsplit, size_t plan
     const int groups = (k + kQThreads * E - 1) / (kQThreads * E);
     const int vec = ((uintptr_t)P % 16 == 0 && ldP % 4 == 0 && plane % 4 == 0 &&
                      (!keep || ((uintptr_t)keep % 16 == 0 && ldK % 4 == 0))) ? 1 : 0;
-    if (k <= 8192 && (nsplit <= 1 || n >= 2048)) {
+    // summing kernels exist for 16-byte aligned planes only (the projection workspace always is)
+    const bool sum = nsplit > 1 || keep != nullptr;
+    if (k <= 8192 && (!sum || (n >= 2048 && vec))) {
         // wavefront per row; 4 rows per workgroup
         for (int64_t r0 = 0; r0 < n; r0 += 0x40000000) {
             const int64_t rows = n - r0 < 0x40000000 ? n - r0 : 0x40000000;
@@ -293,8 +297,9 @@ static void launch_quantize(const float *P, int64_t ldP, int nsplit, size_t plan
             unsigned char *c = (unsigned char *)codes + r0 * ((int64_t)k * BITS / 8);
             const dim3 grid((unsigned)((rows + 3) / 4)), block(kQThreads);
 #define QLESS_QW(NG) do { \
-                if (vec) hipLaunchKernelGGL((quantize_wave_kernel<BITS, NG, true>), grid, block, 0, st, p, ldP, rows, k, c, S + r0, rnorm + r0, nsplit, plane, kp, ldK); \
-                else hipLaunchKernelGGL((quantize_wave_kernel<BITS, NG, false>), grid, block, 0, st, p, ldP, rows, k, c, S + r0, rnorm + r0, nsplit, plane, kp, ldK); } while (0)
+                if (sum) hipLaunchKernelGGL((quantize_wave_kernel<BITS, NG, true, true>), grid, block, 0, st, p, ldP, rows, k, c, S + r0, rnorm + r0, nsplit, plane, kp, ldK); \
+                else if (vec) hipLaunchKernelGGL((quantize_wave_kernel<BITS, NG, true, false>), grid, block, 0, st, p, ldP, rows, k, c, S + r0, rnorm + r0, nsplit, plane, kp, ldK); \
+                else hipLaunchKernelGGL((quantize_wave_kernel<BITS, NG, false, false>), grid, block, 0, st, p, ldP, rows, k, c, S + r0, rnorm + r0, nsplit, plane, kp, ldK); } while (0)
             if (k <= 2048) QLESS_QW(8);
             else if (k <= 4096) QLESS_QW(16);
             else QLESS_QW(32);
@@ -308,8 +313,11 @@ static void launch_quantize(const float *P, int64_t ldP, int nsplit, size_t plan
         const float *p = P + r0 * ldP;
         float *kp = keep ? keep + r0 * ldK : nullptr;
         unsigned char *c = (unsigned char *)codes + r0 * ((int64_t)k * BITS / 8);
-#define QLESS_QB(NG) hipLaunchKernelGGL((quantize_kernel<BITS, NG>), dim3((unsigned)rows), dim3(kQThreads), 0, st, \
-                                        p, ldP, k, c, S + r0, rnorm + r0, vec, nsplit, plane, kp, ldK)
+#define QLESS_QB(NG) do { \
+            if (sum) hipLaunchKernelGGL((quantize_kernel<BITS, NG, true>), dim3((unsigned)rows), dim3(kQThreads), 0, st, \
+                                        p, ldP, k, c, S + r0, rnorm + r0, vec, nsplit, plane, kp, ldK); \
+            else hipLaunchKernelGGL((quantize_kernel<BITS, NG, false>), dim3((unsigned)rows), dim3(kQThreads), 0, st, \
+                                    p, ldP, k, c, S + r0, rnorm + r0, vec, nsplit, plane, kp, ldK); } while (0)
         if (groups <= 4) QLESS_QB(4);
         else if (groups <= 8) QLESS_QB(8);
         else if (groups <= 16) QLESS_QB(16);
