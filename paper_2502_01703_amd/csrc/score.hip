@@ -201,6 +201,189 @@ score_popcount_kernel(ScoreArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
+// 1-bit / 2-bit codes against at most 8 validation vectors: streaming kernel, bound by HBM.
+//
+// No barrier after the start: every wavefront owns a contiguous range of 8-row blocks and streams
+// them through a private LDS ring with asynchronous 16-byte copies (one copy instruction = 8 rows x
+// 128 bytes, whole cache lines; lane = row rr = lane / 8, 16-byte chunk g = lane % 8 of the
+// 128-byte slice), nb - 1 slices ahead of their use.  Every lane reads back exactly the 16 bytes it
+// requested.  The validation codes and weights of all checkpoints sit in LDS for the whole kernel.
+// Popcounts accumulate per lane over the whole row; the 8 lanes of a row are summed once per
+// checkpoint with three DPP steps.  Ranges are split in units of 8 rows, so all wavefronts finish
+// within one row block of each other (no tail of half-empty rounds).
+// Lanes whose chunk lies past the end of a plane copy its last 16 bytes and skip the arithmetic.
+// ------------------------------------------------------------------------------------------
+constexpr int kStreamVal = 8;                  // validation vectors the streaming kernel handles
+
+__device__ inline int sum_over_8_lanes(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
+    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
+    v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true);   // row_half_mirror: the other quad
+    return v;
+}
+struct StreamCtx {                              // per-wavefront constants of the streaming kernel
+    const unsigned char *vlds;                  // [C][MV][cb] validation codes
+    const float *wlds;                          // [C][MV] eta * rnorm'
+    unsigned char *ring;                        // this wavefront's ring (generic pointer) ...
+    unsigned ring_lds;                          // ... and its LDS address
+    int nb, cb, plane, nsl, T, lane, g, rr;
+};
+
+// One panel of PB row blocks starting at block rbp: all checkpoints, all slices, outputs.
+template <int BITS, int MV, int PB>
+__device__ inline void stream_panel(const ScoreArgs &a, const StreamCtx &c, int64_t rbp) {
+    constexpr int NPL = BITS;                   // bit planes per row
+    constexpr int L = PB * NPL;                 // 1 KB copies per slice
+    const int64_t prow0 = rbp * 8;              // first row of the panel (wave-uniform)
+    int64_t row[PB];
+    unsigned rel[PB];                           // byte offset of the lane's row from the panel's first
+#pragma unroll
+    for (int p = 0; p < PB; ++p) {
+        const int64_t r = (rbp + p) * 8 + c.rr;
+        row[p] = r < a.N ? r : a.N - 1;         // clamped; masked at the output
+        rel[p] = (unsigned)(row[p] - prow0) * (unsigned)c.cb;
+    }
+    float facc[PB][MV];
+    int accP[PB][MV], accN[BITS == 2 ? PB : 1][MV];
+#pragma unroll
+    for (int p = 0; p < PB; ++p)
+#pragma unroll
+        for (int j = 0; j < MV; ++j) { facc[p][j] = 0.0f; accP[p][j] = 0; if (BITS == 2) accN[p][j] = 0; }
+
+    // slice `it` of the panel: checkpoint it / nsl, slice it % nsl, ring slot it % nb
+    auto fetch = [&](int it) {
+        const int ci = it / c.nsl, sl = it - ci * c.nsl;
+        int off = sl * 128 + c.g * 16;
+        if (off >= c.plane) off = c.plane - 16;                  // such lanes skip the arithmetic
+        const unsigned char *base = a.tc[ci] + prow0 * c.cb;     // wave-uniform
+        const unsigned slot = c.ring_lds + (unsigned)(it % c.nb) * (4 * 1024);
+#pragma unroll
+        for (int p = 0; p < PB; ++p)
+#pragma unroll
+            for (int q = 0; q < NPL; ++q)
+                global_to_lds16(base, rel[p] + (unsigned)(q * c.plane + off), slot + (unsigned)(p * NPL + q) * 1024u);
+    };
+    for (int it = 0; it < c.nb - 1 && it < c.T; ++it) fetch(it);
+    for (int it = 0; it < c.T; ++it) {
+        // copies issued after this slice's: nb - 2 more slices, fewer at the end of the panel
+        const int younger = c.T - 1 - it < c.nb - 2 ? c.T - 1 - it : c.nb - 2;
+        if (younger >= 1) wait_vmcnt<L>(); else wait_vmcnt<0>();
+        // the slot of slice it - 1 is free: this wave's reads of it were consumed in the last step
+        if (it + c.nb - 1 < c.T) fetch(it + c.nb - 1);
+        const int ci = it / c.nsl, sl = it - ci * c.nsl;
+        const int off = sl * 128 + c.g * 16;
+        if (off < c.plane) {
+            const unsigned char *src = c.ring + (size_t)(it % c.nb) * (4 * 1024) + c.lane * 16;
+            uint4 cur[L];
+#pragma unroll
+            for (int u = 0; u < L; ++u) cur[u] = *(const uint4 *)(src + u * 1024);
+            const unsigned char *vrow = c.vlds + (size_t)ci * MV * c.cb + off;
+            uint4 bv[MV];                                        // all validation chunks requested up front
+#pragma unroll
+            for (int j = 0; j < MV; ++j) bv[j] = *(const uint4 *)(vrow + j * c.cb);
+#pragma unroll
+            for (int j = 0; j < MV; ++j) {
+                const uint4 b = bv[j];
+                if (BITS == 1) {
+#pragma unroll
+                    for (int p = 0; p < PB; ++p)
+                        accP[p][j] += __popc(cur[p].x ^ b.x) + __popc(cur[p].y ^ b.y) +
+                                      __popc(cur[p].z ^ b.z) + __popc(cur[p].w ^ b.w);
+                } else {
+                    const uint4 d = *(const uint4 *)(vrow + j * c.cb + c.plane);
+#pragma unroll
+                    for (int p = 0; p < PB; ++p) {
+                        const uint4 tn = cur[p * NPL], tg = cur[p * NPL + NPL - 1];
+                        uint32_t t;
+                        t = tn.x & b.x; accP[p][j] += __popc(t); accN[p][j] += __popc(t & (tg.x ^ d.x));
+                        t = tn.y & b.y; accP[p][j] += __popc(t); accN[p][j] += __popc(t & (tg.y ^ d.y));
+                        t = tn.z & b.z; accP[p][j] += __popc(t); accN[p][j] += __popc(t & (tg.z ^ d.z));
+                        t = tn.w & b.w; accP[p][j] += __popc(t); accN[p][j] += __popc(t & (tg.w ^ d.w));
+                    }
+                }
+            }
+        }
+        if (sl == c.nsl - 1) {
+            // checkpoint epilogue: every lane of a row ends up with the row's dot products
+#pragma unroll
+            for (int p = 0; p < PB; ++p) {
+                const float rt = a.tr[ci][row[p]];
+#pragma unroll
+                for (int j = 0; j < MV; ++j) {
+                    const float wv = c.wlds[ci * MV + j];
+                    const int P = sum_over_8_lanes(accP[p][j]);
+                    const int D = BITS == 1 ? a.k - 2 * P : P - 2 * sum_over_8_lanes(accN[BITS == 2 ? p : 0][j]);
+                    const float t = __fmul_rn(__fmul_rn((float)D, rt), wv);
+                    facc[p][j] = __fadd_rn(facc[p][j], t);
+                    accP[p][j] = 0;
+                    if (BITS == 2) accN[p][j] = 0;
+                }
+            }
+        }
+    }
+    // outputs: lane g of a row writes column g of the full matrix, lane 0 the row maximum
+#pragma unroll
+    for (int p = 0; p < PB; ++p) {
+        const int64_t r = (rbp + p) * 8 + c.rr;
+        if (r >= a.N) continue;
+        float m = neg_inf(), mine = 0.0f;
+#pragma unroll
+        for (int j = 0; j < MV; ++j) {
+            if (j < a.M) m = fmaxf(m, facc[p][j]);
+            if (j == c.g) mine = facc[p][j];
+        }
+        if (a.full && c.g < a.M) a.full[r * a.M + c.g] = mine;
+        if (a.score && c.g == 0) a.score[r] = m;
+    }
+}
+
+template <int BITS, int MV>                   // MV = 4 or 8 validation columns computed (M <= MV)
+__global__ void __launch_bounds__(512, 2)
+score_stream_kernel(ScoreArgs a, int64_t total_rb, int64_t rb_per_wave, int nb, unsigned ring_off) {
+    constexpr int PB = 4 / BITS;                // row blocks of a full panel (4 KB per slice)
+    // LDS: [C][MV][cb] validation codes | [C][MV] weights | per wave a ring of nb slices x 4 KB
+    extern __shared__ __attribute__((aligned(16))) unsigned char vlds[];
+    StreamCtx c;
+    c.lane = threadIdx.x & 63;
+    c.g = c.lane & 7; c.rr = c.lane >> 3;
+    const int wv_id = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t wave = (int64_t)blockIdx.x * 8 + wv_id;
+    const int64_t rb0 = wave * rb_per_wave;
+    int64_t rb1 = rb0 + rb_per_wave;
+    if (rb1 > total_rb) rb1 = total_rb;
+    c.nb = nb;
+    c.cb = a.k * BITS / 8;                      // bytes per row
+    c.plane = a.k / 8;                          // bytes per bit plane, a multiple of 16 here
+    c.nsl = (c.plane + 127) / 128;              // 128-byte slices per plane
+    c.T = a.C * c.nsl;                          // slices of a panel over all checkpoints
+    c.vlds = vlds;
+    c.wlds = (const float *)(vlds + (size_t)a.C * MV * c.cb);
+    c.ring = vlds + ring_off + (size_t)wv_id * nb * 4096;
+    c.ring_lds = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)c.ring);
+
+    // validation codes and weights eta * rnorm' of every checkpoint -> LDS (rows past M repeat the
+    // last one; they are masked at the output)
+    {
+        const int per_row = c.cb / 16, total = a.C * MV * per_row;
+        for (int i = threadIdx.x; i < total; i += 512) {
+            const int c16 = i % per_row, j = (i / per_row) % MV, ci = i / (per_row * MV);
+            const int jc = j < a.M ? j : a.M - 1;
+            *(uint4 *)(vlds + (size_t)i * 16) = *(const uint4 *)(a.vc[ci] + (int64_t)jc * c.cb + c16 * 16);
+        }
+        float *wdst = (float *)(vlds + (size_t)a.C * MV * c.cb);
+        for (int i = threadIdx.x; i < a.C * MV; i += 512) {
+            const int j = i % MV, ci = i / MV;
+            wdst[i] = __fmul_rn(a.eta[ci], a.vr[ci][j < a.M ? j : a.M - 1]);
+        }
+        __syncthreads();
+    }
+    // full panels, then the remaining row blocks one at a time (wave-uniform loops)
+    int64_t rbp = rb0;
+    for (; rbp + PB <= rb1; rbp += PB) stream_panel<BITS, MV, PB>(a, c, rbp);
+    for (; rbp < rb1; ++rbp) stream_panel<BITS, MV, 1>(a, c, rbp);
+}
+
+// ------------------------------------------------------------------------------------------
 // int8 MFMA kernel for all four code widths.
 //
 // A small pre-pass expands the validation codes of every checkpoint to int8 rows (padded to the
@@ -221,7 +404,6 @@ score_popcount_kernel(ScoreArgs a) {
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(16))) int i32x16;
 
-constexpr int kMT = 256;                       // train rows per workgroup tile
 constexpr int kKE = 128;                       // code elements per pipeline stage
 
 struct ScorePrep {                             // workspace views (device pointers)
@@ -300,30 +482,37 @@ __global__ void score_finish_kernel(const unsigned int *smax, int64_t N, float *
         score[i] = f32_from_order_key(smax[i]);
 }
 
-// Shape of the 8 waves of a workgroup: WX waves across the val tile, 8 / WX down the 256 train
-// rows; each wave owns WR x WC accumulators of 32 x 32.  Val tile width VT = 32 WC WX:
-//   M > 64: <2, 2, 2> (64 x 64 per wave, VT = 128);  M <= 64: <1, 2, 1> (VT = 64);  M <= 32: <1, 1, 1>.
-template <int BITS, int WR, int WC, int WX>
+// Shape of the NW waves of a workgroup: WX waves across the val tile, NW / WX down the train
+// rows; each wave owns WR x WC accumulators of 32 x 32.  Train tile height MT = 32 WR NW / WX, val
+// tile width VT = 32 WC WX:
+//   M > 64: <2, 2, 2, 8> (64 x 64 per wave, 256 x 128 per workgroup);  M <= 64: <1, 2, 1, 8> (256 x 64);
+//   M <= 32: <1, 1, 1, 8> (256 x 32) or <1, 1, 1, 4> (128 x 32), whichever fills the chip more evenly.
+template <int BITS, int WR, int WC, int WX, int NW>
 struct MfmaShape {
-    static constexpr int WY = 8 / WX;
+    static constexpr int WY = NW / WX;
+    static constexpr int MT = 32 * WR * WY;
     static constexpr int VT = 32 * WC * WX;
     static constexpr int TB = kKE * BITS / 8;            // train bytes per row per stage: 128 / 64 / 32 / 16
     static constexpr int TCPR = TB / 16;                 // 16-byte chunks per train row
-    static constexpr int TRAIN_BYTES = kMT * TB, VAL_BYTES = VT * kKE;
-    static constexpr int TCH = kMT * TCPR, VCH = VT * (kKE / 16);
+    static constexpr int TRAIN_BYTES = MT * TB, VAL_BYTES = VT * kKE;
+    static constexpr int TCH = MT * TCPR, VCH = VT * (kKE / 16);
     static constexpr int NINST = (TCH + VCH) / 64;       // wavefront-wide copies per stage
-    static constexpr int LPW = (NINST + 7) / 8;          // per wave
+    static constexpr int LPW = (NINST + NW - 1) / NW;    // per wave
     static constexpr int BUF = TRAIN_BYTES + VAL_BYTES + 1024;   // + 1 KB landing zone for padding copies
-    static constexpr int NBUF = (158 * 1024) / BUF >= 4 ? 4 : 3; // LDS ring depth
-    static_assert(32 * WR * WY == kMT, "8 waves cover the 256 train rows");
-    static_assert((TCH + VCH) % 64 == 0, "whole wavefront copies");
-    static_assert((158 * 1024) / BUF >= 3, "at least three stages fit");
+    // LDS ring depth.  The narrow shapes serve few validation vectors, where scoring streams the
+    // train codes from HBM: two stages per workgroup and several workgroups per compute unit,
+    // whose barriers and epilogues then overlap each other's copies.
+    static constexpr bool NARROW = WR * WC == 1;
+    static constexpr int NBUF = NARROW ? 2 : ((158 * 1024) / BUF >= 4 ? 4 : 3);
+    static_assert(WY * WX == NW && TCH % 64 == 0 && (TCH + VCH) % 64 == 0, "whole wavefront copies");
+    static_assert(NBUF * BUF <= (NARROW ? 79 : 158) * 1024, "the ring fits in LDS");
 };
 
-template <int BITS, int WR, int WC, int WX>
-__global__ void __launch_bounds__(512, 2)
+template <int BITS, int WR, int WC, int WX, int NW>
+__global__ void __launch_bounds__(64 * NW, (WR * WC == 1 ? 4 : 2))
 score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
-    using Sh = MfmaShape<BITS, WR, WC, WX>;
+    using Sh = MfmaShape<BITS, WR, WC, WX, NW>;
+    constexpr int kMT = Sh::MT;
     constexpr int KE = kKE, TB = Sh::TB, TCPR = Sh::TCPR, VT = Sh::VT;
     constexpr int TRAIN_BYTES = Sh::TRAIN_BYTES, VAL_BYTES = Sh::VAL_BYTES, TCH = Sh::TCH;
     constexpr int NINST = Sh::NINST, LPW = Sh::LPW, BUF = Sh::BUF, NBUF = Sh::NBUF;
@@ -559,6 +748,17 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     }
 }
 
+constexpr size_t kLdsPerCU = 160 * 1024;       // LDS of one compute unit
+constexpr size_t kStaticLds = 1024;            // s_rowmax
+// Compute units of the current device (256 on MI355X).
+static int compute_units() {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        cus = 256;
+    return cus;
+}
+
 struct MfmaPlan { int32_t vt, Mp, kp; size_t off_vw, off_vsum, off_smax, total; };
 static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int C) {
     MfmaPlan p{};
@@ -579,24 +779,55 @@ static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int C) {
 // too fine for the copy pipeline; the popcount kernels stream them faster.
 static bool use_mfma_path(int bits, int32_t M, int32_t k) { return bits >= 4 || (k % 128 == 0 && M > 16); }
 
-template <int BITS, int WR, int WC, int WX>
-static qless_status launch_mfma_shape(const ScoreArgs &a, const ScorePrep &w, hipStream_t st) {
-    using Sh = MfmaShape<BITS, WR, WC, WX>;
-    const size_t lds = (size_t)Sh::NBUF * Sh::BUF;
-    static bool once = false;
-    if (!once) {
-        if (hipFuncSetAttribute((const void *)score_mfma_kernel<BITS, WR, WC, WX>,
+// per_cu > 0 asks for exactly that many workgroups per compute unit (by padding the LDS request).
+template <int BITS, int WR, int WC, int WX, int NW>
+static qless_status launch_mfma_shape(const ScoreArgs &a, const ScorePrep &w, int per_cu, hipStream_t st) {
+    using Sh = MfmaShape<BITS, WR, WC, WX, NW>;
+    size_t lds = (size_t)Sh::NBUF * Sh::BUF;
+    if (per_cu > 0) {
+        const size_t share = ((size_t)kLdsPerCU / per_cu - kStaticLds) & ~(size_t)511;
+        if (share > lds) lds = share;
+    }
+    static size_t allowed = 0;
+    if (lds > allowed) {
+        if (hipFuncSetAttribute((const void *)score_mfma_kernel<BITS, WR, WC, WX, NW>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return QLESS_ERR_DEVICE;
-        once = true;
+        allowed = lds;
     }
-    const int64_t ttiles = (a.N + kMT - 1) / kMT;
+    const int64_t ttiles = (a.N + Sh::MT - 1) / Sh::MT;
     const int vtiles = w.Mp / Sh::VT;
     const int64_t grid = 8 * (int64_t)vtiles * ((ttiles + 7) / 8);
     if (grid > 0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((score_mfma_kernel<BITS, WR, WC, WX>), dim3((unsigned)grid), dim3(512), lds, st, a, w,
+    hipLaunchKernelGGL((score_mfma_kernel<BITS, WR, WC, WX, NW>), dim3((unsigned)grid), dim3(64 * NW), lds, st, a, w,
                        (int)ttiles, vtiles);
     return QLESS_OK;
+}
+
+// Few validation vectors: every workgroup streams its train rows at the same pace, so the launch
+// takes ceil(tiles / slots) rounds of equal length.  Pick the tile height (256 or 128 rows) and the
+// number of workgroups per compute unit whose last round is fullest.
+struct NarrowChoice { int nw, per_cu; };
+template <int BITS>
+static NarrowChoice choose_narrow(int64_t N) {
+    const int cus = compute_units();
+    NarrowChoice best{8, 2};
+    double best_eff = -1.0;
+    for (int nw = 8; nw >= 4; nw -= 4) {
+        const size_t need = nw == 8 ? (size_t)MfmaShape<BITS, 1, 1, 1, 8>::NBUF * MfmaShape<BITS, 1, 1, 1, 8>::BUF
+                                    : (size_t)MfmaShape<BITS, 1, 1, 1, 4>::NBUF * MfmaShape<BITS, 1, 1, 1, 4>::BUF;
+        const int64_t tiles = (N + 32 * nw - 1) / (32 * nw);
+        int cap = (int)(kLdsPerCU / (need + kStaticLds));
+        if (cap > 16 / nw) cap = 16 / nw;                 // at most 16 wavefronts per compute unit
+        for (int pc = cap; pc >= 1; --pc) {
+            if (pc * nw < 8) break;                       // keep at least 8 wavefronts per compute unit
+            const int64_t slots = (int64_t)cus * pc;
+            const int64_t rounds = (tiles + slots - 1) / slots;
+            const double eff = (double)tiles / (double)(rounds * slots);
+            if (eff > best_eff + 1e-9) { best_eff = eff; best = NarrowChoice{nw, pc}; }
+        }
+    }
+    return best;
 }
 
 template <int BITS>
@@ -608,9 +839,13 @@ static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st) {
     w.smax = (unsigned int *)(base + p.off_smax); w.Mp = p.Mp; w.kp = p.kp;
     hipLaunchKernelGGL((score_prepare_kernel<BITS>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
     qless_status rc;
-    if (p.vt == 128) rc = launch_mfma_shape<BITS, 2, 2, 2>(a, w, st);
-    else if (p.vt == 64) rc = launch_mfma_shape<BITS, 1, 2, 1>(a, w, st);
-    else rc = launch_mfma_shape<BITS, 1, 1, 1>(a, w, st);
+    if (p.vt == 128) rc = launch_mfma_shape<BITS, 2, 2, 2, 8>(a, w, 0, st);
+    else if (p.vt == 64) rc = launch_mfma_shape<BITS, 1, 2, 1, 8>(a, w, 0, st);
+    else {
+        const NarrowChoice c = choose_narrow<BITS>(a.N);
+        if (c.nw == 8) rc = launch_mfma_shape<BITS, 1, 1, 1, 8>(a, w, c.per_cu, st);
+        else rc = launch_mfma_shape<BITS, 1, 1, 1, 4>(a, w, c.per_cu, st);
+    }
     if (rc != QLESS_OK) return rc;
     if (a.score) {
         int64_t blocks = (a.N + 255) / 256;
@@ -668,7 +903,38 @@ extern "C" qless_status qless_score(const void *const *train_codes, const float 
         if (bits == 2) return launch_mfma<2>(a, ws, st);
         return launch_mfma<1>(a, ws, st);
     }
-    // bit-plane codes with rows that are not multiples of 16 bytes, or very few val vectors: popcount kernels
+    // bit-plane codes against a handful of val vectors: the streaming kernel
+    // bit-plane codes against a handful of val vectors: the streaming kernel, if the validation
+    // codes of all checkpoints and a ring of at least two slices per wavefront fit in LDS
+    const int mv = M <= 4 ? 4 : kStreamVal;                         // validation columns the kernel computes
+    const size_t stream_val = (((size_t)C * mv * ((size_t)k * bits / 8 + 4)) + 1023) & ~(size_t)1023;
+    if (M <= kStreamVal && k % 128 == 0 && stream_val + 8 * 2 * 4096 <= 158 * 1024) {
+        const int nb = stream_val + 8 * 3 * 4096 <= 158 * 1024 ? 3 : 2;
+        const size_t lds = stream_val + (size_t)8 * nb * 4096;
+        static size_t allowed = 64 * 1024;                           // more has to be allowed per kernel
+        if (lds > allowed) {
+            const void *fns[4] = {(const void *)score_stream_kernel<1, 4>, (const void *)score_stream_kernel<1, 8>,
+                                  (const void *)score_stream_kernel<2, 4>, (const void *)score_stream_kernel<2, 8>};
+            for (const void *f : fns)
+                if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 158 * 1024) != hipSuccess)
+                    return QLESS_ERR_DEVICE;
+            allowed = 158 * 1024;
+        }
+        const int64_t total_rb = (N + 7) / 8;
+        const int per_cu = lds * 2 + 1024 <= kLdsPerCU ? 2 : 1;      // workgroups of 8 wavefronts per compute unit
+        int64_t waves = (int64_t)compute_units() * 8 * per_cu;
+        if (waves > total_rb) waves = total_rb;
+        const int64_t rb_per_wave = (total_rb + waves - 1) / waves;
+        const int64_t used = (total_rb + rb_per_wave - 1) / rb_per_wave;
+        const dim3 grid((unsigned)((used + 7) / 8)), block(512);
+        const unsigned ro = (unsigned)stream_val;
+        if (bits == 1 && mv == 4) hipLaunchKernelGGL((score_stream_kernel<1, 4>), grid, block, lds, st, a, total_rb, rb_per_wave, nb, ro);
+        else if (bits == 1) hipLaunchKernelGGL((score_stream_kernel<1, 8>), grid, block, lds, st, a, total_rb, rb_per_wave, nb, ro);
+        else if (mv == 4) hipLaunchKernelGGL((score_stream_kernel<2, 4>), grid, block, lds, st, a, total_rb, rb_per_wave, nb, ro);
+        else hipLaunchKernelGGL((score_stream_kernel<2, 8>), grid, block, lds, st, a, total_rb, rb_per_wave, nb, ro);
+        return launch_status();
+    }
+    // bit-plane codes with rows that are not multiples of 16 bytes, or few val vectors: popcount kernels
     if (bits == 1) {
         if (M > 32) launch_popcount<1, 8, 4, 16, 16>(a, st);
         else if (M > 8) launch_popcount<1, 8, 4, 32, 8>(a, st);

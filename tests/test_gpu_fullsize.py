@@ -124,6 +124,30 @@ def test_config4_large_datastore_scoring(bits):
     assert set(planted.cpu().tolist()) <= set(oi.tolist())
 
 
+@pytest.mark.parametrize("M", [24, 7])
+@pytest.mark.parametrize("bits", [8, 4, 2, 1])
+def test_hbm_bound_regime_few_validation_vectors(bits, M):
+    """N = 270000 with a few validation vectors (Sec. 4.1 has few-shot validation sets): the launch
+    shapes that stream the train codes (narrow matrix-core tiles with several workgroups per compute
+    unit; for bit planes and M <= 8 the popcount streaming kernel); sampled rows bit-exact."""
+    N, k, C = 270000, 1024, 2
+    _say("few validation vectors: score %d-bit N=270000 M=%d k=1024 C=2" % (bits, M))
+    tcs, trs, vcs, vrs, planted = _big_datastore(N, M, k, C, bits, 4100 + bits)
+    eta = ETA[:C]
+    score, full = Q.score(tcs, trs, vcs, vrs, eta, k, bits, want_full=True)
+    assert torch.equal(score, Q.score(tcs, trs, vcs, vrs, eta, k, bits))
+    assert torch.equal(score, full.max(dim=1).values)
+    rng = np.random.default_rng(100 + bits)
+    sample = np.unique(np.concatenate([rng.integers(0, N, 200), planted[:8].cpu().numpy(),
+                                       [0, 127, 128, 255, 256, N - 129, N - 128, N - 1]]))
+    idx_t = torch.from_numpy(sample).to(DEV)
+    ref, ref_full = oracle.score([t[idx_t].cpu().numpy() for t in tcs], [t[idx_t].cpu().numpy() for t in trs],
+                                 [v.cpu().numpy() for v in vcs], [v.cpu().numpy() for v in vrs], eta, k, bits,
+                                 want_full=True)
+    np.testing.assert_array_equal(score[idx_t].cpu().numpy().view(np.uint32), ref.view(np.uint32))
+    np.testing.assert_array_equal(full[idx_t].cpu().numpy().view(np.uint32), ref_full.view(np.uint32))
+
+
 def test_config2_multi_bit_sweep_pipeline():
     """N = 16384, M = 256, d = 2^20 bf16 Student-t, k = 2048, C = 4, widths 8/4/2/1, top 5 %.
     Gradients are produced per batch on the device; every stage is checked on samples."""
