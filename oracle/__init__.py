@@ -52,6 +52,8 @@ def lib():
         L.oracle_quantize_unpacked.argtypes = [_vp, _i64, _i64, _i32, _c.c_int, _c.c_int, _vp, _vp]
         L.oracle_quantize.restype = _c.c_int
         L.oracle_quantize.argtypes = [_vp, _i64, _i64, _i32, _c.c_int, _vp, _vp, _vp]
+        L.oracle_quantize_absmean.restype = _c.c_int
+        L.oracle_quantize_absmean.argtypes = [_vp, _i64, _i64, _i32, _c.c_int, _vp, _vp, _vp, _vp]
         L.oracle_score.restype = _c.c_int
         L.oracle_score.argtypes = [_vp, _vp, _vp, _vp, _vp, _c.c_int, _i64, _i32, _i32, _c.c_int,
                                    _vp, _vp]
@@ -159,6 +161,20 @@ def quantize_unpacked(P, bits, literal=False):
     _check(lib().oracle_quantize_unpacked(_ptr(P), k, n, k, bits, int(literal), _ptr(q), _ptr(S)),
            "quantize_unpacked")
     return q, S
+
+
+def quantize_absmean(P, bits, want_unpacked=False):
+    """Absmean variant (Sec. 5): (codes, S = mean|g|, rnorm[, q int8 [n, k]])."""
+    P = np.ascontiguousarray(P, dtype=np.float32)
+    n, k = P.shape
+    codes = np.zeros((n, code_bytes(k, bits)), dtype=np.uint8)
+    q = np.zeros((n, k), dtype=np.int8) if want_unpacked else None
+    S = np.zeros(n, dtype=np.float32)
+    rn = np.zeros(n, dtype=np.float32)
+    _check(lib().oracle_quantize_absmean(_ptr(P), k, n, k, bits, _ptr(codes),
+                                         _ptr(q) if want_unpacked else None, _ptr(S), _ptr(rn)),
+           "quantize_absmean")
+    return (codes, S, rn, q) if want_unpacked else (codes, S, rn)
 
 
 def unpack(codes, k, bits):

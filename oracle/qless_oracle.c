@@ -9,6 +9,7 @@
  *                       Rademacher or Gaussian-like; R is a pure function of (seed, m, j).
  *   oracle_quantize     Eq.(4),(5), Sec. 2.3 / Sec. 3.1: S = max|g|, alpha = 2^(b-1)-1,
  *                       q = round(alpha g / S); b = 1 is the sign code of Table 3 / Sec. 5.
+ *   oracle_quantize_absmean  Sec. 5 / Table 3 variant; formula is this build's reading (see there).
  *   oracle_score        Eq.(6),(7), Sec. 3.2: cosine of the quantised vectors, learning-rate
  *                       weighted sum over checkpoints; then max over validation vectors.
  *   oracle_topk         Sec. 4.1 ("select the top 5 %"): largest scores, ties by smaller index.
@@ -260,6 +261,61 @@ static void quantize_row(const float *p, int32_t k, int bits, int literal, int8_
         }
     }
 }
+/* ------------------------------------------------------------------------------------------
+ * Absmean variant (Sec. 5, Table 3: the scale follows the mean absolute value instead of the
+ * maximum, which empties the zero bin at low widths).  The paper prints no formula; this build's
+ * reading (parity unpinned against the paper) is the BitNet-style rule
+ *     S = mean_m |g_m|,   q = clamp(rne(g / S), -alpha, alpha),   b = 1: the sign code.
+ * So that S does not depend on the order of a floating-point summation, the mean is defined in
+ * fixed point: with A = max|g| = f * 2^E, f in [0.5, 1),
+ *     u_m = trunc(|g_m| * 2^(32-E))   (an integer below 2^32),   U = sum_m u_m   (exact),
+ *     S = fl32( fl64(U) / k * 2^(E-32) ),   scale = fl32(1 / S),   q = clamp(rne(fl32(g * scale))).
+ * A zero vector gives S = 0 and zero codes (all +1 for b = 1).
+ * ------------------------------------------------------------------------------------------ */
+static void quantize_row_absmean(const float *p, int32_t k, int bits, int8_t *q, float *S_out) {
+    float A = 0.0f;
+    for (int32_t m = 0; m < k; ++m) { float a = fabsf(p[m]); if (a > A) A = a; }
+    if (bits == 1) for (int32_t m = 0; m < k; ++m) q[m] = (p[m] < 0.0f) ? -1 : 1;
+    else memset(q, 0, (size_t)k);
+    *S_out = 0.0f;
+    if (A == 0.0f) return;
+    int E;
+    (void)frexpf(A, &E);
+    uint64_t U = 0;
+    for (int32_t m = 0; m < k; ++m) U += (uint64_t)ldexpf(fabsf(p[m]), 32 - E);
+    double mean = ldexp((double)U / (double)k, E - 32);
+    float S = (float)mean;
+    *S_out = S;
+    if (bits == 1 || S == 0.0f) return;
+    int alpha = alpha_of(bits);
+    volatile float scale = 1.0f / S;
+    for (int32_t m = 0; m < k; ++m) {
+        volatile float t = p[m] * scale;
+        float r = nearbyintf(t);
+        if (r > (float)alpha) r = (float)alpha; if (r < -(float)alpha) r = -(float)alpha;
+        q[m] = (int8_t)r;
+    }
+}
+int oracle_quantize_absmean(const float *P, int64_t ldP, int64_t n, int32_t k, int bits,
+                            uint8_t *codes, int8_t *q_out, float *S, float *rnorm) {
+    if (!P || !S || !rnorm || k <= 0 || k % 64 || ldP < k ||
+        (bits != 1 && bits != 2 && bits != 4 && bits != 8)) return ORACLE_BAD_ARG;
+    int64_t cb = oracle_code_bytes(k, bits);
+    int64_t i;
+    #pragma omp parallel for
+    for (i = 0; i < n; ++i) {
+        int8_t *q = (int8_t *)malloc((size_t)k);
+        quantize_row_absmean(P + i * ldP, k, bits, q, S + i);
+        int64_t n2 = 0;
+        for (int32_t m = 0; m < k; ++m) n2 += (int64_t)q[m] * q[m];
+        rnorm[i] = n2 ? (float)(1.0 / sqrt((double)n2)) : 0.0f;
+        if (codes) pack_row(q, k, bits, codes + i * cb);
+        if (q_out) memcpy(q_out + i * (int64_t)k, q, (size_t)k);
+        free(q);
+    }
+    return ORACLE_OK;
+}
+
 int oracle_quantize_unpacked(const float *P, int64_t ldP, int64_t n, int32_t k, int bits,
                              int literal, int8_t *q, float *S) {
     if (!P || !q || !S || k <= 0 || ldP < k || (bits != 1 && bits != 2 && bits != 4 && bits != 8))
