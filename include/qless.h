@@ -96,6 +96,18 @@ qless_status qless_quantize(const float *P, int64_t ldP, int64_t n, int32_t k, i
                             void *codes, float *S, float *rnorm, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Absmean variant of the quantiser (Sec. 5 and Table 3 compare it with absmax; the paper gives no
+ * formula, the rule below is this library's reading):
+ *   S = mean_m |P[m]|;  bits >= 2: q = clamp(rne(P * fl32(1 / S)), -alpha, alpha);  bits == 1: the sign code.
+ * The mean is evaluated in fixed point (32 fractional bits below the binary exponent of max|P|, each
+ * term truncated, the integer sum divided by k in fp64 and rounded to fp32), so S does not depend on
+ * the order of the additions.  Arguments, packed layout and rnorm as for qless_quantize; S receives
+ * the mean.  Codes of either variant are scored by qless_score unchanged.
+ * ------------------------------------------------------------------------------------------- */
+qless_status qless_quantize_absmean(const float *P, int64_t ldP, int64_t n, int32_t k, int bits,
+                                    void *codes, float *S, float *rnorm, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Datastore build in one call (Sec. 3.1: project, then quantise and store): Eq.(1) followed by
  * Eq.(4),(5) on the same rows without a round trip of P through memory.  Arguments as in
  * qless_project (no accumulate: the call covers a whole gradient or one stand-alone slice; d_len >= 1)

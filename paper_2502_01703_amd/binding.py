@@ -29,6 +29,7 @@ EXPORTS = {
     "qless_generator_words": (_c.c_int, [_u64, _u32, _i32, _u32, _i32, _u32, _vp, _vp]),
     "qless_gaussian_table": (_c.c_int, [_vp]),
     "qless_quantize": (_c.c_int, [_vp, _i64, _i64, _i32, _c.c_int, _vp, _vp, _vp, _vp]),
+    "qless_quantize_absmean": (_c.c_int, [_vp, _i64, _i64, _i32, _c.c_int, _vp, _vp, _vp, _vp]),
     "qless_project_quantize": (_c.c_int, [_vp, _c.c_int, _i64, _i64, _i64, _i64, _i32, _c.c_int, _u64, _c.c_int,
                                           _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
     "qless_score_workspace": (_sz, [_i64, _i32, _i32, _c.c_int, _c.c_int]),
@@ -123,8 +124,9 @@ def code_bytes(k, bits):
     return k * bits // 8
 
 
-def quantize(P, bits, codes=None, S=None, rnorm=None):
-    """qless_quantize: P [n, k] fp32 -> (codes uint8 [n, k*bits/8], S fp32 [n], rnorm fp32 [n])."""
+def quantize(P, bits, codes=None, S=None, rnorm=None, absmean=False):
+    """qless_quantize (or qless_quantize_absmean): P [n, k] fp32 -> (codes uint8 [n, k*bits/8], S fp32 [n],
+    rnorm fp32 [n])."""
     assert P.is_cuda and P.dtype == torch.float32 and P.dim() == 2 and P.stride(1) == 1
     n, k = P.shape
     dev = P.device
@@ -134,9 +136,10 @@ def quantize(P, bits, codes=None, S=None, rnorm=None):
         S = torch.empty(n, dtype=torch.float32, device=dev)
     if rnorm is None:
         rnorm = torch.empty(n, dtype=torch.float32, device=dev)
-    _check(lib().qless_quantize(_vp(P.data_ptr()), P.stride(0) if n > 1 else max(k, P.stride(0)), n, k, bits,
-                                _vp(codes.data_ptr()), _vp(S.data_ptr()), _vp(rnorm.data_ptr()), _stream()),
-           "qless_quantize")
+    fn = lib().qless_quantize_absmean if absmean else lib().qless_quantize
+    _check(fn(_vp(P.data_ptr()), P.stride(0) if n > 1 else max(k, P.stride(0)), n, k, bits,
+              _vp(codes.data_ptr()), _vp(S.data_ptr()), _vp(rnorm.data_ptr()), _stream()),
+           "qless_quantize_absmean" if absmean else "qless_quantize")
     return codes, S, rnorm
 
 

@@ -167,7 +167,10 @@ __device__ inline void emit_elems(const float (&v)[E], int base, int32_t k, floa
     }
 }
 
-template <int BITS, int NG, bool SUM>   // NG > 0: the row fits NG register groups per thread; NG == 0: re-read it
+// MEAN selects the absmean variant (Sec. 5): the scale is 1 / mean|g| instead of alpha / max|g|, with
+// the mean taken in fixed point (32 fractional bits below the binary exponent of the row maximum), so
+// that it does not depend on the order of the additions.
+template <int BITS, int NG, bool SUM, bool MEAN = false>   // NG > 0: the row fits NG register groups per thread; NG == 0: re-read it
 __global__ void __launch_bounds__(kQThreads)
 quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned char *__restrict__ codes,
                 float *__restrict__ S_out, float *__restrict__ rnorm_out, int vec, int nsplit, size_t plane,
@@ -208,9 +211,38 @@ quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned ch
     amax = wave_max(amax);
     if (lane == 0) s_max[wave] = amax;
     __syncthreads();
-    const float S = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+    float S = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
     const float alpha = (float)((1 << (BITS - 1)) - 1);
-    const float scale = (BITS > 1 && S > 0.0f) ? __fdiv_rn(alpha, S) : 0.0f;
+    float scale = (BITS > 1 && S > 0.0f) ? __fdiv_rn(alpha, S) : 0.0f;
+    if (MEAN) {
+        __shared__ unsigned long long s_abs[4];
+        int ex = 0;
+        (void)frexpf(S, &ex);                                  // max|g| = f 2^ex, f in [0.5, 1)
+        unsigned long long u = 0;                             // sum of trunc(|g| 2^(32-ex)), each below 2^32
+        if (S > 0.0f) {
+            if (CACHED) {
+#pragma unroll
+                for (int g = 0; g < MAXG; ++g)
+                    if (g < ngroups) {
+#pragma unroll
+                        for (int e = 0; e < E; ++e) u += (uint32_t)ldexpf(fabsf(reg[g][e]), 32 - ex);
+                    }
+            } else {
+                for (int g = 0; g < ngroups; ++g) {
+                    load_elems<E, SUM>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[0]);
+#pragma unroll
+                    for (int e = 0; e < E; ++e) u += (uint32_t)ldexpf(fabsf(reg[0][e]), 32 - ex);
+                }
+            }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) u += __shfl_xor(u, o, 64);
+        if (lane == 0) s_abs[wave] = u;
+        __syncthreads();
+        const unsigned long long U = s_abs[0] + s_abs[1] + s_abs[2] + s_abs[3];
+        S = S > 0.0f ? (float)ldexp((double)U / (double)k, ex - 32) : 0.0f;
+        scale = (BITS > 1 && S > 0.0f) ? __fdiv_rn(1.0f, S) : 0.0f;
+    }
 
     uint32_t n2 = 0;        // per-thread partial: < 2^32 for rows up to 2^26 elements
     if (CACHED) {
@@ -326,6 +358,26 @@ static void launch_quantize(const float *P, int64_t ldP, int nsplit, size_t plan
     }
 }
 
+// Absmean variant: workgroup-per-row kernels only (an HBM-bound comparator, not the datastore path).
+template <int BITS>
+static void launch_quantize_absmean(const float *P, int64_t ldP, int64_t n, int32_t k, void *codes, float *S,
+                                    float *rnorm, hipStream_t st) {
+    const int groups = (k + kQThreads * 4 - 1) / (kQThreads * 4);
+    const int vec = ((uintptr_t)P % 16 == 0 && ldP % 4 == 0) ? 1 : 0;
+    for (int64_t r0 = 0; r0 < n; r0 += 0x40000000) {
+        const int64_t rows = n - r0 < 0x40000000 ? n - r0 : 0x40000000;
+        const float *p = P + r0 * ldP;
+        unsigned char *c = (unsigned char *)codes + r0 * ((int64_t)k * BITS / 8);
+#define QLESS_QM(NG) hipLaunchKernelGGL((quantize_kernel<BITS, NG, false, true>), dim3((unsigned)rows), dim3(kQThreads), 0, st, \
+                                        p, ldP, k, c, S + r0, rnorm + r0, vec, 1, (size_t)0, (float *)nullptr, (int64_t)0)
+        if (groups <= 4) QLESS_QM(4);
+        else if (groups <= 8) QLESS_QM(8);
+        else if (groups <= 16) QLESS_QM(16);
+        else QLESS_QM(0);
+#undef QLESS_QM
+    }
+}
+
 qless_status quantize_rows(const float *src, int64_t ld, int nsplit, size_t plane, float *keep, int64_t ldK,
                            int64_t n, int32_t k, int bits, void *codes, float *S, float *rnorm,
                            hipStream_t st) {
@@ -349,4 +401,20 @@ extern "C" qless_status qless_quantize(const float *P, int64_t ldP, int64_t n, i
     if (!valid_bits(bits) || k % 64 != 0) return QLESS_ERR_UNSUPPORTED;
     if (n == 0) return QLESS_OK;
     return quantize_rows(P, ldP, 1, 0, nullptr, 0, n, k, bits, codes, S, rnorm, (hipStream_t)stream);
+}
+
+extern "C" qless_status qless_quantize_absmean(const float *P, int64_t ldP, int64_t n, int32_t k, int bits,
+                                               void *codes, float *S, float *rnorm, void *stream) {
+    if (n < 0 || k <= 0 || ldP < k) return QLESS_ERR_INVALID_ARG;
+    if (n > 0 && (!P || !codes || !S || !rnorm)) return QLESS_ERR_INVALID_ARG;
+    if (!valid_bits(bits) || k % 64 != 0) return QLESS_ERR_UNSUPPORTED;
+    if (n == 0) return QLESS_OK;
+    hipStream_t st = (hipStream_t)stream;
+    switch (bits) {
+        case 8: launch_quantize_absmean<8>(P, ldP, n, k, codes, S, rnorm, st); break;
+        case 4: launch_quantize_absmean<4>(P, ldP, n, k, codes, S, rnorm, st); break;
+        case 2: launch_quantize_absmean<2>(P, ldP, n, k, codes, S, rnorm, st); break;
+        default: launch_quantize_absmean<1>(P, ldP, n, k, codes, S, rnorm, st); break;
+    }
+    return launch_status();
 }

@@ -164,6 +164,23 @@ def test_fused_project_quantize_matches_the_two_calls_and_the_oracle(bits, n, d,
     assert _rel_l2(fP.cpu().numpy(), ref).max() <= 1e-2
 
 
+@pytest.mark.parametrize("bits", [8, 4, 2, 1])
+@pytest.mark.parametrize("n,k", [(37, 576), (5, 64), (9, 8192), (3, 16384), (2, 40000 // 64 * 64), (1030, 1024)])
+def test_absmean_variant_codes_identical(bits, n, k):
+    """Sec. 5 variant: same codes, scale and norm as the oracle's absmean rule, from the same P."""
+    _say("quantize absmean n=%d k=%d bits=%d" % (n, k, bits))
+    rng = np.random.default_rng(n * 7 + k)
+    P = (rng.standard_normal((n, k)) * np.exp(rng.standard_normal((n, 1)))).astype(np.float32)
+    if n > 2:
+        P[1] = 0.0
+        P[2, ::3] = 0.0
+    oc, oS, orn = oracle.quantize_absmean(P, bits)
+    codes, S, rn = Q.quantize(torch.from_numpy(P).to(DEV), bits, absmean=True)
+    np.testing.assert_array_equal(S.cpu().numpy(), oS)
+    np.testing.assert_array_equal(codes.cpu().numpy(), oc)
+    np.testing.assert_array_equal(rn.cpu().numpy(), orn)
+
+
 # ------------------------------------------------------------------------------------ scoring
 def _datastore(n, k, bits, C, seed):
     rng = np.random.default_rng(seed)

@@ -75,6 +75,11 @@ def test_quantize_score_topk_argument_validation():
     assert q(one, 32, 4, 64, 8, one, one, one, None) == INVALID
     assert q(None, 64, 4, 64, 8, one, one, one, None) == INVALID
     assert q(None, 64, 0, 64, 8, None, None, None, None) == OK
+    qm = L.qless_quantize_absmean
+    assert qm(one, 64, 4, 64, 3, one, one, one, None) == UNSUPPORTED
+    assert qm(one, 32, 4, 64, 8, one, one, one, None) == INVALID
+    assert qm(one, 64, 4, 64, 8, None, one, one, None) == INVALID
+    assert qm(None, 64, 0, 64, 8, None, None, None, None) == OK
     ptrs = (ctypes.c_void_p * 1)(16)
     eta = (ctypes.c_float * 1)(1.0)
     s = L.qless_score
