@@ -61,6 +61,10 @@ def lib():
         L.oracle_topk.argtypes = [_vp, _i64, _i64, _vp, _vp]
         L.oracle_less_cosine.restype = _c.c_int
         L.oracle_less_cosine.argtypes = [_vp, _vp, _vp, _c.c_int, _i64, _i32, _i32, _vp]
+        L.oracle_less16_store.restype = _c.c_int
+        L.oracle_less16_store.argtypes = [_vp, _i64, _i64, _i32, _vp]
+        L.oracle_less16_score.restype = _c.c_int
+        L.oracle_less16_score.argtypes = [_vp, _vp, _vp, _c.c_int, _i64, _i32, _i32, _vp, _vp]
         L.oracle_num_threads.restype = _c.c_int
         _lib = L
     return _lib
@@ -237,3 +241,29 @@ def less_cosine(train_P, val_P, eta):
     _check(lib().oracle_less_cosine(_ptr_array(tp), _ptr_array(vp), _ptr(eta), C, N, M, k,
                                     _ptr(out)), "less_cosine")
     return out
+
+
+def less16_store(P):
+    """LESS 16-bit datastore rows: bfloat16 bit patterns (uint16 [n, k]) of the normalised projections."""
+    P = np.ascontiguousarray(P, dtype=np.float32)
+    n, k = P.shape
+    out = np.zeros((n, k), dtype=np.uint16)
+    _check(lib().oracle_less16_store(_ptr(P), k, n, k, _ptr(out)), "less16_store")
+    return out
+
+
+def less16_score(train16, val16, eta, want_full=False):
+    """Eq.(2),(3) from stored bfloat16 rows, fp64: score [N] (and full [N, M])."""
+    C = len(train16)
+    tr = [np.ascontiguousarray(a, dtype=np.uint16) for a in train16]
+    va = [np.ascontiguousarray(a, dtype=np.uint16) for a in val16]
+    eta = np.ascontiguousarray(eta, dtype=np.float32)
+    if not (len(va) == eta.size == C):
+        raise ValueError("oracle less16_score: one entry per checkpoint is needed in every list")
+    N, k = tr[0].shape
+    M = va[0].shape[0]
+    sc = np.zeros(N, dtype=np.float64)
+    full = np.zeros((N, M), dtype=np.float64) if want_full else None
+    _check(lib().oracle_less16_score(_ptr_array(tr), _ptr_array(va), _ptr(eta), C, N, M, k, _ptr(sc),
+                                     _ptr(full) if want_full else None), "less16_score")
+    return (sc, full) if want_full else sc

@@ -14,6 +14,7 @@
  *                       weighted sum over checkpoints; then max over validation vectors.
  *   oracle_topk         Sec. 4.1 ("select the top 5 %"): largest scores, ties by smaller index.
  *   oracle_less_cosine  Eq.(2),(3), Sec. 2.2: the un-quantised LESS influence (comparator only).
+ *   oracle_less16_*     the same comparator from a stored 16-bit (bfloat16) datastore (Table 1 baseline).
  *
  * Arithmetic: projection sums in fp64 in index order and rounds once to fp32; integer dot
  * products in int64; the score epilogue is a fixed sequence of single fp32 operations (this file
@@ -431,6 +432,62 @@ int oracle_less_cosine(const float *const *train_P, const float *const *val_P, c
             }
             out[z * (int64_t)M + v] = acc;
         }
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * LESS comparator in its stored 16-bit form (Sec. 2.2 / Table 1: the baseline keeps the normalised
+ * projected gradients at 16 bits).  This build's reading of "16-bit" is bfloat16:
+ *   store:  y = bf16_rne( fl32( x * fl32(1 / sqrt(sum_m x_m^2)) ) ),  the sum in fp64, index order;
+ *           a zero vector is stored as zeros.  Output: bfloat16 bit patterns.
+ *   score:  acc(z,z') = sum_i eta_i * <y_{z,i}, y_{z',i}>   in fp64 from the stored values (Eq.(2),(3)
+ *           with the cosine's denominators already folded into the store);  score = max_z' acc.
+ * ------------------------------------------------------------------------------------------ */
+static uint16_t bf16_bits_rne(float f) {
+    uint32_t u; memcpy(&u, &f, 4);
+    uint32_t r = u + 0x7FFFu + ((u >> 16) & 1u);      /* finite inputs only */
+    return (uint16_t)(r >> 16);
+}
+static double bf16_value(uint16_t b) {
+    uint32_t u = (uint32_t)b << 16; float f; memcpy(&f, &u, 4);
+    return (double)f;
+}
+int oracle_less16_store(const float *P, int64_t ldP, int64_t n, int32_t k, uint16_t *out) {
+    if (!P || !out || k <= 0 || ldP < k) return ORACLE_BAD_ARG;
+    int64_t i;
+    #pragma omp parallel for
+    for (i = 0; i < n; ++i) {
+        const float *x = P + i * ldP;
+        double ss = 0.0;
+        for (int32_t m = 0; m < k; ++m) ss += (double)x[m] * (double)x[m];
+        volatile float inv = ss > 0.0 ? (float)(1.0 / sqrt(ss)) : 0.0f;
+        for (int32_t m = 0; m < k; ++m) {
+            volatile float y = x[m] * inv;
+            out[i * (int64_t)k + m] = bf16_bits_rne(y);
+        }
+    }
+    return ORACLE_OK;
+}
+int oracle_less16_score(const uint16_t *const *train, const uint16_t *const *val, const float *eta,
+                        int C, int64_t N, int32_t M, int32_t k, double *score, double *full) {
+    if (!train || !val || !eta || C <= 0 || N < 0 || M <= 0 || k <= 0 || (!score && !full)) return ORACLE_BAD_ARG;
+    int64_t z;
+    #pragma omp parallel for
+    for (z = 0; z < N; ++z) {
+        double best = 0.0;
+        for (int32_t v = 0; v < M; ++v) {
+            double acc = 0.0;
+            for (int i = 0; i < C; ++i) {
+                const uint16_t *a = train[i] + z * (int64_t)k, *b = val[i] + (int64_t)v * k;
+                double d = 0.0;
+                for (int32_t m = 0; m < k; ++m) d += bf16_value(a[m]) * bf16_value(b[m]);
+                acc += (double)eta[i] * d;
+            }
+            if (full) full[z * (int64_t)M + v] = acc;
+            if (v == 0 || acc > best) best = acc;
+        }
+        if (score) score[z] = best;
+    }
     return ORACLE_OK;
 }
 
