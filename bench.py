@@ -194,6 +194,36 @@ def main():
                 oracle_sample = ([t[:2048].cpu().numpy() for t in tc4], [t[:2048].cpu().numpy() for t in tr4],
                                  [v.cpu().numpy() for v in vc4f], [v.cpu().numpy() for v in vr4f])
             del tc4, tr4, vc4f, vr4f, vc4, vr4
+        # the un-quantised 16-bit LESS store (Table 1 baseline) scored on the same machine, for comparison
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(60)
+        def store16(rows):
+            out = []
+            for _ in range(C):
+                st16 = torch.empty(rows, k, dtype=torch.bfloat16, device=dev)
+                for r0 in range(0, rows, 16384):
+                    r1 = min(rows, r0 + 16384)
+                    Q.normalize16(torch.randn(r1 - r0, k, generator=gen, device=dev), out=st16[r0:r1])
+                out.append(st16)
+            return out
+        t16, v16 = store16(N4), store16(1024)
+        ws16 = torch.empty(max(Q.score16_workspace(N4, 1024, k, C), 16), dtype=torch.uint8, device=dev)
+        Q.score16(t16, v16, eta, ws=ws16)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            Q.score16(t16, v16, eta, ws=ws16)
+        e1.record()
+        torch.cuda.synchronize()
+        t16ms = e0.elapsed_time(e1) / 3
+        macs16 = float(N4) * 1024 * C * k
+        extra["less16_M1024"] = {"workload": "N=270000 M=1024 k=8192 C=4, bfloat16 store (16-bit LESS comparator)",
+                                 "ms": round(t16ms, 3), "pair_scores_per_s": round(N4 * 1024 / (t16ms * 1e-3), 1),
+                                 "bf16_mfma_frac": round(2 * macs16 / (t16ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                                 "store_bytes": C * N4 * k * 2, "store_bytes_1bit": C * N4 * (k // 8 + 8)}
+        log("score 16-bit LESS store 270000x1024x4: %.2f ms (%.0f%% of bf16 MFMA peak), store %.2f GB vs %.2f GB at 1 bit" %
+            (t16ms, 100 * 2 * macs16 / (t16ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, C * N4 * k * 2 / 1e9, C * N4 * (k // 8 + 8) / 1e9))
+        del t16, v16, ws16
         # quantise throughput at the datastore size (HBM-bound kernel)
         Pq = torch.randn(N4, k, device=dev)
         cq = torch.empty(N4, Q.code_bytes(k, 1), dtype=torch.uint8, device=dev)

@@ -148,6 +148,27 @@ qless_status qless_score(const void *const *train_codes, const float *const *tra
                          float *score, float *full, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * The 16-bit LESS comparator (Sec. 2.2, Eq.(2),(3); the "16-bit" row of Table 1), for measuring the
+ * un-quantised baseline on the same machine.  "16-bit" is read as bfloat16.
+ *
+ * qless_normalize16:  out[i][m] = bf16_rne( fl32( P[i][m] * fl32(1 / ||P_i||_2) ) ), the squared norm
+ *   summed in fp64; a zero row is stored as zeros.
+ *     P    device, n x k fp32, leading dimension ldP >= k;  k a positive multiple of 64
+ *     out  device, n x k bfloat16 (dense rows)
+ * qless_score16:  acc(z, z') = sum_{i<C} eta[i] * <y_{z,i}, y_{z',i}> over the stored rows, products exact,
+ *   sums in fp32 on the matrix cores (order unspecified: results agree with an fp64 evaluation to
+ *   about 1e-5, not bit for bit);  score[z] = max_{z'} acc(z, z').
+ *     train16, val16  host arrays of C device pointers to N (resp. M) bfloat16 rows of k, 16-byte aligned
+ *     eta             host, C weights;  k a multiple of 64, at most 32768
+ *     score, full, ws, ws_bytes, stream   as for qless_score; workspace from qless_score16_workspace
+ * ------------------------------------------------------------------------------------------- */
+qless_status qless_normalize16(const float *P, int64_t ldP, int64_t n, int32_t k, void *out, void *stream);
+size_t qless_score16_workspace(int64_t N, int32_t M, int32_t k, int C);
+qless_status qless_score16(const void *const *train16, const void *const *val16, const float *eta,
+                           int C, int64_t N, int32_t M, int32_t k, float *score, float *full,
+                           void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Selection (Sec. 4.1: the top 5 % by score): indices of the k_sel largest scores ordered by
  * (score descending, index ascending); +0 and -0 compare equal.
  *

@@ -35,6 +35,9 @@ EXPORTS = {
     "qless_score_workspace": (_sz, [_i64, _i32, _i32, _c.c_int, _c.c_int]),
     "qless_score": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _c.c_int, _i64, _i32, _i32, _c.c_int, _vp, _vp,
                                _vp, _sz, _vp]),
+    "qless_normalize16": (_c.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
+    "qless_score16_workspace": (_sz, [_i64, _i32, _i32, _c.c_int]),
+    "qless_score16": (_c.c_int, [_vp, _vp, _vp, _c.c_int, _i64, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
     "qless_topk_workspace": (_sz, [_i64, _i64]),
     "qless_topk": (_c.c_int, [_vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
 }
@@ -191,6 +194,44 @@ def score(train_codes, train_rnorm, val_codes, val_rnorm, eta, k, bits, want_sco
                              _vp(score_out.data_ptr()) if score_out is not None else None,
                              _vp(full_out.data_ptr()) if full_out is not None else None,
                              _vp(w.data_ptr()), w.numel(), _stream()), "qless_score")
+    if want_score and want_full:
+        return score_out, full_out
+    return score_out if want_score else full_out
+
+
+def normalize16(P, out=None):
+    """qless_normalize16: P [n, k] fp32 -> unit rows in bfloat16 [n, k] (the 16-bit LESS store)."""
+    assert P.is_cuda and P.dtype == torch.float32 and P.dim() == 2 and P.stride(1) == 1
+    n, k = P.shape
+    if out is None:
+        out = torch.empty(n, k, dtype=torch.bfloat16, device=P.device)
+    assert out.is_cuda and out.dtype == torch.bfloat16 and out.is_contiguous()
+    _check(lib().qless_normalize16(_vp(P.data_ptr()), P.stride(0) if n > 1 else max(k, P.stride(0)), n, k,
+                                   _vp(out.data_ptr()), _stream()), "qless_normalize16")
+    return out
+
+
+def score16_workspace(N, M, k, C):
+    return int(lib().qless_score16_workspace(N, M, k, C))
+
+
+def score16(train16, val16, eta, want_score=True, want_full=False, ws=None):
+    """qless_score16: per-checkpoint lists of bfloat16 stores -> score [N] (and/or full [N, M])."""
+    C = len(train16)
+    assert len(val16) == C and len(eta) == C
+    N, k = train16[0].shape
+    M = val16[0].shape[0]
+    dev = val16[0].device
+    for t in list(train16) + list(val16):
+        assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.shape[1] == k
+    score_out = torch.empty(N, dtype=torch.float32, device=dev) if want_score else None
+    full_out = torch.empty(N, M, dtype=torch.float32, device=dev) if want_full else None
+    eta_arr = (_c.c_float * C)(*[float(e) for e in eta])
+    w = _ws(score16_workspace(N, M, k, C), dev, ws)
+    _check(lib().qless_score16(_ptr_array(train16), _ptr_array(val16), _c.cast(eta_arr, _vp), C, N, M, k,
+                               _vp(score_out.data_ptr()) if want_score else None,
+                               _vp(full_out.data_ptr()) if want_full else None,
+                               _vp(w.data_ptr()), w.numel(), _stream()), "qless_score16")
     if want_score and want_full:
         return score_out, full_out
     return score_out if want_score else full_out

@@ -390,9 +390,65 @@ qless_status quantize_rows(const float *src, int64_t ld, int nsplit, size_t plan
     return launch_status();
 }
 
+// 16-bit LESS comparator store (Sec. 2.2, Table 1 baseline): rows normalised to unit length and
+// rounded to bfloat16.  One workgroup per row; the squared norm is summed in fp64, the row is read
+// a second time (from L2) for the scaling pass.  HBM-bound: 4k bytes in, 2k out.
+__device__ inline uint16_t bf16_rne_bits(float f) {
+    const uint32_t u = __float_as_uint(f);
+    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);        // finite inputs
+}
+__global__ void __launch_bounds__(kQThreads)
+normalize16_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, uint16_t *__restrict__ out, int vec) {
+    __shared__ double s_ss[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row = blockIdx.x;
+    const float *p = P + row * ldP;
+    uint16_t *o = out + row * (int64_t)k;
+    double ss = 0.0;
+    if (vec) {
+        for (int m = tid * 4; m < k; m += kQThreads * 4) {
+            const float4 f = *(const float4 *)(p + m);
+            ss += (double)f.x * f.x + (double)f.y * f.y + (double)f.z * f.z + (double)f.w * f.w;
+        }
+    } else {
+        for (int m = tid; m < k; m += kQThreads) ss += (double)p[m] * p[m];
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    if (lane == 0) s_ss[wave] = ss;
+    __syncthreads();
+    const double tot = (s_ss[0] + s_ss[1]) + (s_ss[2] + s_ss[3]);
+    const float inv = tot > 0.0 ? (float)(1.0 / sqrt(tot)) : 0.0f;
+    if (vec) {
+        for (int m = tid * 4; m < k; m += kQThreads * 4) {
+            const float4 f = *(const float4 *)(p + m);
+            const uint32_t lo = bf16_rne_bits(__fmul_rn(f.x, inv)) | ((uint32_t)bf16_rne_bits(__fmul_rn(f.y, inv)) << 16);
+            const uint32_t hi = bf16_rne_bits(__fmul_rn(f.z, inv)) | ((uint32_t)bf16_rne_bits(__fmul_rn(f.w, inv)) << 16);
+            *(uint2 *)(o + m) = make_uint2(lo, hi);
+        }
+    } else {
+        for (int m = tid; m < k; m += kQThreads) o[m] = bf16_rne_bits(__fmul_rn(p[m], inv));
+    }
+}
+
 }  // namespace qless
 
 using namespace qless;
+
+extern "C" qless_status qless_normalize16(const float *P, int64_t ldP, int64_t n, int32_t k, void *out,
+                                          void *stream) {
+    if (n < 0 || k <= 0 || ldP < k) return QLESS_ERR_INVALID_ARG;
+    if (n > 0 && (!P || !out)) return QLESS_ERR_INVALID_ARG;
+    if (k % 64 != 0) return QLESS_ERR_UNSUPPORTED;
+    if (n == 0) return QLESS_OK;
+    const int vec = ((uintptr_t)P % 16 == 0 && ldP % 4 == 0 && (uintptr_t)out % 8 == 0) ? 1 : 0;
+    for (int64_t r0 = 0; r0 < n; r0 += 0x40000000) {
+        const int64_t rows = n - r0 < 0x40000000 ? n - r0 : 0x40000000;
+        hipLaunchKernelGGL(normalize16_kernel, dim3((unsigned)rows), dim3(kQThreads), 0, (hipStream_t)stream,
+                           P + r0 * ldP, ldP, k, (uint16_t *)out + r0 * (int64_t)k, vec);
+    }
+    return launch_status();
+}
 
 extern "C" qless_status qless_quantize(const float *P, int64_t ldP, int64_t n, int32_t k, int bits,
                                        void *codes, float *S, float *rnorm, void *stream) {

@@ -437,7 +437,7 @@ __device__ inline int val_source_element(int p) {
     return 64 * g + 32 * h + 8 * b + 4 * s + jj;
 }
 
-template <int BITS>
+template <int BITS, bool F16 = false>        // F16: rows are bfloat16 bytes, no code norms (see score_mfma_kernel)
 __global__ void __launch_bounds__(256)
 score_prepare_kernel(ScoreArgs a, ScorePrep w) {
     const int row = blockIdx.x, ci = blockIdx.y;        // row < Mp
@@ -466,7 +466,7 @@ score_prepare_kernel(ScoreArgs a, ScorePrep w) {
     __syncthreads();
     if (threadIdx.x == 0) {
         w.vsum[ci * w.Mp + row] = s_part[0] + s_part[1] + s_part[2] + s_part[3];
-        w.vw[ci * w.Mp + row] = live ? __fmul_rn(a.eta[ci], a.vr[ci][row]) : 0.0f;
+        w.vw[ci * w.Mp + row] = live ? (F16 ? a.eta[ci] : __fmul_rn(a.eta[ci], a.vr[ci][row])) : 0.0f;
     }
     // the row-maximum keys start below every finite score
     if (ci == 0) {
@@ -480,6 +480,21 @@ __global__ void score_finish_kernel(const unsigned int *smax, int64_t N, float *
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N;
          i += (int64_t)gridDim.x * blockDim.x)
         score[i] = f32_from_order_key(smax[i]);
+}
+
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+template <bool F16> struct AccType { typedef i32x16 type; };
+template <> struct AccType<true> { typedef f32x16 type; };
+template <bool F16>
+__device__ inline typename AccType<F16>::type mfma_step(i32x4 a, i32x4 b, typename AccType<F16>::type c);
+template <>
+__device__ inline i32x16 mfma_step<false>(i32x4 a, i32x4 b, i32x16 c) {
+    return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+}
+template <>
+__device__ inline f32x16 mfma_step<true>(i32x4 a, i32x4 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
 // Shape of the NW waves of a workgroup: WX waves across the val tile, NW / WX down the train
@@ -508,9 +523,14 @@ struct MfmaShape {
     static_assert(NBUF * BUF <= (NARROW ? 79 : 158) * 1024, "the ring fits in LDS");
 };
 
-template <int BITS, int WR, int WC, int WX, int NW>
+// F16 (with BITS = 8 and k counted in bytes): the rows are bfloat16 vectors, the 16 bytes a lane feeds
+// to the matrix core are eight bfloat16 values for v_mfma_f32_32x32x16_bf16 (same bytes, same
+// addresses as the int8 operands), the accumulator is fp32 and the epilogue is acc += eta * D:
+// the 16-bit LESS comparator (Eq.(2),(3)) on pre-normalised rows.
+template <int BITS, int WR, int WC, int WX, int NW, bool F16 = false>
 __global__ void __launch_bounds__(64 * NW, (WR * WC == 1 ? 4 : 2))
 score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
+    static_assert(!F16 || BITS == 8, "bfloat16 rows use the byte geometry of the 8-bit codes");
     using Sh = MfmaShape<BITS, WR, WC, WX, NW>;
     constexpr int kMT = Sh::MT;
     constexpr int KE = kKE, TB = Sh::TB, TCPR = Sh::TCPR, VT = Sh::VT;
@@ -621,7 +641,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
 
     int g = 0;
     for (int ci = 0; ci < a.C; ++ci) {
-        i32x16 acc[WR][WC];
+        typename AccType<F16>::type acc[WR][WC];
 #pragma unroll
         for (int b = 0; b < WR; ++b)
 #pragma unroll
@@ -667,7 +687,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
                         for (int b = 0; b < WR; ++b)
 #pragma unroll
                             for (int c = 0; c < WC; ++c)
-                                acc[b][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[b][s2], bf[c], acc[b][c], 0, 0, 0);
+                                acc[b][c] = mfma_step<F16>(af[b][s2], bf[c], acc[b][c]);
                     }
                 }
             } else {
@@ -690,7 +710,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
                     for (int b = 0; b < WR; ++b)
 #pragma unroll
                         for (int c = 0; c < WC; ++c)
-                            acc[b][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[b], bf[c], acc[b][c], 0, 0, 0);
+                            acc[b][c] = mfma_step<F16>(af[b], bf[c], acc[b][c]);
                 }
             }
         }
@@ -698,7 +718,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
         // Lane L < 32 WR of the wave holds rnorm of train row (trow + L); rows are fetched by shuffle.
         int64_t myrow = row0 + trow + (lane & (32 * WR - 1));
         if (myrow > a.N - 1) myrow = a.N - 1;
-        const float rt_lane = a.tr[ci][myrow];
+        const float rt_lane = F16 ? 1.0f : a.tr[ci][myrow];
         float wv[WC];
         int vs[WC];
 #pragma unroll
@@ -714,8 +734,13 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
                 const float rt = __shfl(rt_lane, 32 * b + 8 * (v >> 2) + 4 * half + (v & 3), 64);
 #pragma unroll
                 for (int c = 0; c < WC; ++c) {
-                    const int D = BITS == 4 ? (acc[b][c][v] >> 4) : (BITS == 1 ? vs[c] - 2 * acc[b][c][v] : acc[b][c][v]);
-                    const float t = __fmul_rn(__fmul_rn((float)D, rt), wv[c]);
+                    float t;
+                    if (F16) {
+                        t = __fmul_rn((float)acc[b][c][v], wv[c]);
+                    } else {
+                        const int D = BITS == 4 ? ((int)acc[b][c][v] >> 4) : (BITS == 1 ? vs[c] - 2 * (int)acc[b][c][v] : (int)acc[b][c][v]);
+                        t = __fmul_rn(__fmul_rn((float)D, rt), wv[c]);
+                    }
                     facc[b][c][v] = __fadd_rn(facc[b][c][v], t);
                 }
             }
@@ -780,7 +805,7 @@ static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int C) {
 static bool use_mfma_path(int bits, int32_t M, int32_t k) { return bits >= 4 || (k % 128 == 0 && M > kStreamVal); }
 
 // per_cu > 0 asks for exactly that many workgroups per compute unit (by padding the LDS request).
-template <int BITS, int WR, int WC, int WX, int NW>
+template <int BITS, int WR, int WC, int WX, int NW, bool F16 = false>
 static qless_status launch_mfma_shape(const ScoreArgs &a, const ScorePrep &w, int per_cu, hipStream_t st) {
     using Sh = MfmaShape<BITS, WR, WC, WX, NW>;
     size_t lds = (size_t)Sh::NBUF * Sh::BUF;
@@ -790,7 +815,7 @@ static qless_status launch_mfma_shape(const ScoreArgs &a, const ScorePrep &w, in
     }
     static size_t allowed = 0;
     if (lds > allowed) {
-        if (hipFuncSetAttribute((const void *)score_mfma_kernel<BITS, WR, WC, WX, NW>,
+        if (hipFuncSetAttribute((const void *)score_mfma_kernel<BITS, WR, WC, WX, NW, F16>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return QLESS_ERR_DEVICE;
         allowed = lds;
@@ -799,7 +824,7 @@ static qless_status launch_mfma_shape(const ScoreArgs &a, const ScorePrep &w, in
     const int vtiles = w.Mp / Sh::VT;
     const int64_t grid = 8 * (int64_t)vtiles * ((ttiles + 7) / 8);
     if (grid > 0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((score_mfma_kernel<BITS, WR, WC, WX, NW>), dim3((unsigned)grid), dim3(64 * NW), lds, st, a, w,
+    hipLaunchKernelGGL((score_mfma_kernel<BITS, WR, WC, WX, NW, F16>), dim3((unsigned)grid), dim3(64 * NW), lds, st, a, w,
                        (int)ttiles, vtiles);
     return QLESS_OK;
 }
@@ -830,21 +855,21 @@ static NarrowChoice choose_narrow(int64_t N) {
     return best;
 }
 
-template <int BITS>
+template <int BITS, bool F16 = false>
 static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st) {
     const MfmaPlan p = mfma_plan(a.N, a.M, a.k, a.C);
     ScorePrep w{};
     unsigned char *base = (unsigned char *)ws;
     w.vexp = (int8_t *)base; w.vw = (float *)(base + p.off_vw); w.vsum = (int *)(base + p.off_vsum);
     w.smax = (unsigned int *)(base + p.off_smax); w.Mp = p.Mp; w.kp = p.kp;
-    hipLaunchKernelGGL((score_prepare_kernel<BITS>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
+    hipLaunchKernelGGL((score_prepare_kernel<BITS, F16>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
     qless_status rc;
-    if (p.vt == 128) rc = launch_mfma_shape<BITS, 2, 2, 2, 8>(a, w, 0, st);
-    else if (p.vt == 64) rc = launch_mfma_shape<BITS, 1, 2, 1, 8>(a, w, 0, st);
+    if (p.vt == 128) rc = launch_mfma_shape<BITS, 2, 2, 2, 8, F16>(a, w, 0, st);
+    else if (p.vt == 64) rc = launch_mfma_shape<BITS, 1, 2, 1, 8, F16>(a, w, 0, st);
     else {
         const NarrowChoice c = choose_narrow<BITS>(a.N);
-        if (c.nw == 8) rc = launch_mfma_shape<BITS, 1, 1, 1, 8>(a, w, c.per_cu, st);
-        else rc = launch_mfma_shape<BITS, 1, 1, 1, 4>(a, w, c.per_cu, st);
+        if (c.nw == 8) rc = launch_mfma_shape<BITS, 1, 1, 1, 8, F16>(a, w, c.per_cu, st);
+        else rc = launch_mfma_shape<BITS, 1, 1, 1, 4, F16>(a, w, c.per_cu, st);
     }
     if (rc != QLESS_OK) return rc;
     if (a.score) {
@@ -945,4 +970,33 @@ extern "C" qless_status qless_score(const void *const *train_codes, const float 
         else launch_popcount<2, 8, 1, 32, 8>(a, st);
     }
     return launch_status();
+}
+
+// 16-bit LESS comparator: bfloat16 rows scored by the 8-bit kernel geometry on 2k bytes per row.
+extern "C" size_t qless_score16_workspace(int64_t N, int32_t M, int32_t k, int C) {
+    if (N < 0 || M < 1 || k <= 0 || k > 32768 || C < 1) return 0;
+    return mfma_plan(N, M, 2 * k, C).total;
+}
+
+extern "C" qless_status qless_score16(const void *const *train16, const void *const *val16, const float *eta,
+                                      int C, int64_t N, int32_t M, int32_t k, float *score, float *full,
+                                      void *ws, size_t ws_bytes, void *stream) {
+    if (!train16 || !val16 || !eta) return QLESS_ERR_INVALID_ARG;
+    if (C < 1 || N < 0 || M < 1 || k <= 0) return QLESS_ERR_INVALID_ARG;
+    if (!score && !full) return QLESS_ERR_INVALID_ARG;
+    if (C > QLESS_MAX_CHECKPOINTS || k % 64 != 0 || k > 32768) return QLESS_ERR_UNSUPPORTED;
+    if (N > (int64_t)0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
+    ScoreArgs a{};
+    for (int i = 0; i < C; ++i) {
+        if (!val16[i] || (N > 0 && !train16[i])) return QLESS_ERR_INVALID_ARG;
+        if ((uintptr_t)val16[i] % 16 || (uintptr_t)train16[i] % 16) return QLESS_ERR_INVALID_ARG;
+        a.tc[i] = (const unsigned char *)train16[i]; a.vc[i] = (const unsigned char *)val16[i];
+        a.tr[i] = nullptr; a.vr[i] = nullptr; a.eta[i] = eta[i];
+    }
+    a.C = C; a.N = N; a.M = M; a.k = 2 * k; a.score = score; a.full = full;     // k in bytes from here on
+    if (N == 0) return QLESS_OK;
+    const size_t need = mfma_plan(N, M, a.k, C).total;
+    if (!ws || ws_bytes < need) return QLESS_ERR_WORKSPACE;
+    if ((uintptr_t)ws % 16) return QLESS_ERR_INVALID_ARG;
+    return launch_mfma<8, true>(a, ws, (hipStream_t)stream);
 }

@@ -214,6 +214,47 @@ def test_score_bit_exact(bits, N, M, k, C):
 
 
 # -------------------------------------------------------------------------------------- top-k
+# ------------------------------------------------------------------------- 16-bit LESS comparator
+@pytest.mark.parametrize("n,k", [(33, 576), (4, 64), (7, 8192), (300, 1024)])
+def test_normalize16_matches_oracle_store(n, k):
+    _say("normalize16 n=%d k=%d" % (n, k))
+    rng = np.random.default_rng(n + k)
+    P = (rng.standard_normal((n, k)) * np.exp(rng.standard_normal((n, 1)))).astype(np.float32)
+    P[n // 2] = 0.0
+    ref = oracle.less16_store(P)
+    got = Q.normalize16(torch.from_numpy(P).to(DEV)).view(torch.int16).cpu().numpy().view(np.uint16)
+    # the fp64 sum of squares is taken in another order: the fp32 reciprocal can differ in its last bit,
+    # which moves a product across a bfloat16 rounding boundary for a few entries, by one step
+    diff = got.astype(np.int32) - ref.astype(np.int32)
+    assert np.abs(diff).max() <= 1
+    assert (diff != 0).mean() <= 1e-3
+    assert not got[n // 2].any()
+
+
+@pytest.mark.parametrize("N,M,k,C", [(300, 70, 576, 3), (129, 8, 1024, 2), (64, 33, 8192, 2), (1000, 130, 2048, 2),
+                                     (515, 300, 320, 4)])
+def test_score16_matches_oracle_from_the_same_store(N, M, k, C):
+    """Eq.(2),(3) from bfloat16 stores: products exact, fp32 sums on the matrix cores (order unspecified):
+    |acc_gpu - acc_fp64| <= C * 2^-17 (k terms of magnitude <= 1/k-ish, partial sums <= 1)."""
+    _say("score16 N=%d M=%d k=%d C=%d" % (N, M, k, C))
+    rng = np.random.default_rng(N + M + k)
+    eta = [1.0, 0.75, 0.5, 0.25][:C]
+    def store(rows):
+        P = (rng.standard_normal((rows, k)) * np.exp(rng.standard_normal((rows, 1)))).astype(np.float32)
+        return oracle.less16_store(P)
+    tr = [store(N) for _ in range(C)]
+    va = [store(M) for _ in range(C)]
+    for c in range(C):
+        va[c][: min(M, 8)] = tr[c][: min(M, 8)]                 # a few identical pairs: cosine 1 per checkpoint
+    ref_s, ref_f = oracle.less16_score(tr, va, eta, want_full=True)
+    to_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(DEV).view(torch.bfloat16)
+    sc, full = Q.score16([to_dev(a) for a in tr], [to_dev(a) for a in va], eta, want_full=True)
+    tol = C * 2.0 ** -17
+    assert np.abs(full.cpu().numpy().astype(np.float64) - ref_f).max() <= tol
+    assert np.abs(sc.cpu().numpy().astype(np.float64) - ref_s).max() <= tol
+    assert torch.equal(sc, full.max(dim=1).values)
+
+
 @pytest.mark.parametrize("N,k_sel", [(1000, 50), (100000, 5000), (100000, 20000), (5000, 5000),
                                      (4097, 4097), (7, 0), (1, 1), (270000, 13500)])
 def test_topk_identical_with_ties(N, k_sel):

@@ -15,7 +15,7 @@ OK, INVALID, UNSUPPORTED, WORKSPACE = 0, 1, 2, 3
 
 def test_header_symbols_are_all_exported():
     text = open(os.path.join(ROOT, "include", "qless.h")).read()
-    declared = set(re.findall(r"\b(qless_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(qless_[a-z0-9_]+)\s*\(", text))
     assert declared == set(binding.EXPORTS)
     L = binding.lib()
     for name in declared:
@@ -94,6 +94,21 @@ def test_quantize_score_topk_argument_validation():
     assert s(*args(N=0)) == OK
     bad = (ctypes.c_void_p * 1)(8)           # codes must be 16-byte aligned
     assert s(bad, ptrs, ptrs, ptrs, ctypes.cast(eta, ctypes.c_void_p), 1, 4, 2, 64, 8, one, None, None, 0, None) == INVALID
+    nz = L.qless_normalize16
+    assert nz(one, 32, 4, 64, one, None) == INVALID
+    assert nz(one, 96, 4, 96, one, None) == UNSUPPORTED
+    assert nz(None, 64, 0, 64, None, None) == OK
+    s16 = L.qless_score16
+    a16 = lambda C=1, N=4, M=2, k=64, score=one, p=ptrs: (p, p, ctypes.cast(eta, ctypes.c_void_p), C, N, M, k,
+                                                         score, None, None, 0, None)
+    assert s16(*a16(C=0)) == INVALID
+    assert s16(*a16(k=96)) == UNSUPPORTED
+    assert s16(*a16(k=65536)) == UNSUPPORTED
+    assert s16(*a16(score=None)) == INVALID
+    assert s16(*a16(p=bad)) == INVALID
+    assert s16(*a16()) == WORKSPACE
+    assert s16(*a16(N=0)) == OK
+    assert L.qless_score16_workspace(1000, 100, 512, 2) >= 2 * 128 * 1024
     t = L.qless_topk
     assert t(one, 10, 11, one, None, one, 1 << 20, None) == INVALID
     assert t(one, 10, -1, one, None, one, 1 << 20, None) == INVALID
