@@ -404,7 +404,9 @@ score_stream_kernel(ScoreArgs a, int64_t total_rb, int64_t rb_per_wave, int nb, 
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(16))) int i32x16;
 
-constexpr int kKE = 128;                       // code elements per pipeline stage
+constexpr int kKE = 128;                       // code elements per pipeline stage (most shapes)
+constexpr int kKE4Narrow = 256;                // ... of the 4-bit shape for at most 32 validation vectors
+constexpr int log2c(int x) { return x <= 1 ? 0 : 1 + log2c(x / 2); }
 
 struct ScorePrep {                             // workspace views (device pointers)
     int8_t *vexp;                              // [C][Mp][kp]
@@ -507,20 +509,26 @@ struct MfmaShape {
     static constexpr int WY = NW / WX;
     static constexpr int MT = 32 * WR * WY;
     static constexpr int VT = 32 * WC * WX;
-    static constexpr int TB = kKE * BITS / 8;            // train bytes per row per stage: 128 / 64 / 32 / 16
+    // Code elements per stage: a stage should bring 128 bytes of every train row (whole cache lines
+    // when the codes are streamed from HBM); the 4-bit shape for few validation vectors takes 256.
+    static constexpr bool NARROW = WR * WC == 1;
+    static constexpr int KE = (BITS == 4 && NARROW) ? kKE4Narrow : kKE;
+    static constexpr int TB = KE * BITS / 8;             // train bytes per row per stage: 128 / 64 or 128 / 32 / 16
     static constexpr int TCPR = TB / 16;                 // 16-byte chunks per train row
-    static constexpr int TRAIN_BYTES = MT * TB, VAL_BYTES = VT * kKE;
-    static constexpr int TCH = MT * TCPR, VCH = VT * (kKE / 16);
+    static constexpr int VCPR = KE / 16;                 // 16-byte chunks per expanded val row
+    // rows whose chunks share a bank group are 16 / CPR apart: the swizzle key is (row >> SH) % CPR
+    static constexpr int TSH = log2c(16 / TCPR), VSH = log2c(16 / VCPR);
+    static constexpr int TRAIN_BYTES = MT * TB, VAL_BYTES = VT * KE;
+    static constexpr int TCH = MT * TCPR, VCH = VT * VCPR;
     static constexpr int NINST = (TCH + VCH) / 64;       // wavefront-wide copies per stage
     static constexpr int LPW = (NINST + NW - 1) / NW;    // per wave
     static constexpr int BUF = TRAIN_BYTES + VAL_BYTES + 1024;   // + 1 KB landing zone for padding copies
     // LDS ring depth.  The narrow shapes serve few validation vectors, where scoring streams the
     // train codes from HBM: two stages per workgroup and several workgroups per compute unit,
     // whose barriers and epilogues then overlap each other's copies.
-    static constexpr bool NARROW = WR * WC == 1;
     static constexpr int NBUF = NARROW ? 2 : ((158 * 1024) / BUF >= 4 ? 4 : 3);
     static_assert(WY * WX == NW && TCH % 64 == 0 && (TCH + VCH) % 64 == 0, "whole wavefront copies");
-    static_assert(NBUF * BUF <= (NARROW ? 79 : 158) * 1024, "the ring fits in LDS");
+    static_assert(NBUF * BUF <= 158 * 1024, "the ring fits in LDS");
 };
 
 // F16 (with BITS = 8 and k counted in bytes): the rows are bfloat16 vectors, the 16 bytes a lane feeds
@@ -533,7 +541,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     static_assert(!F16 || BITS == 8, "bfloat16 rows use the byte geometry of the 8-bit codes");
     using Sh = MfmaShape<BITS, WR, WC, WX, NW>;
     constexpr int kMT = Sh::MT;
-    constexpr int KE = kKE, TB = Sh::TB, TCPR = Sh::TCPR, VT = Sh::VT;
+    constexpr int KE = Sh::KE, TB = Sh::TB, TCPR = Sh::TCPR, VCPR = Sh::VCPR, TSH = Sh::TSH, VSH = Sh::VSH, VT = Sh::VT;
     constexpr int TRAIN_BYTES = Sh::TRAIN_BYTES, VAL_BYTES = Sh::VAL_BYTES, TCH = Sh::TCH;
     constexpr int NINST = Sh::NINST, LPW = Sh::LPW, BUF = Sh::BUF, NBUF = Sh::NBUF;
     constexpr int TSTEP = BITS == 2 ? 16 : TB;      // bytes a train chunk's source advances per stage
@@ -556,7 +564,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     const int64_t row0 = tt * kMT;
     const int v0 = vt * VT;
     const int64_t cb = (int64_t)a.k * BITS / 8;
-    const int nstages = w.kp / KE;
+    const int nstages = (a.k + KE - 1) / KE;            // <= kp / KE: the expanded val rows cover every stage
     if (tid < kMT) s_rowmax[tid] = 0u;
     const unsigned lds0 = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)smem);
 
@@ -578,15 +586,15 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
         is_train[u] = qq * 64 < TCH;
         if (t < TCH) {
             const int r = t / TCPR, pos = t % TCPR;
-            const int c = BITS == 8 ? (pos ^ ((r >> 1) & 7)) : (BITS == 4 ? (pos ^ ((r >> 2) & 3)) : pos);
+            const int c = BITS >= 4 ? (pos ^ ((r >> TSH) & (TCPR - 1))) : pos;
             int64_t grow = row0 + r;
             if (grow > a.N - 1) grow = a.N - 1;          // rows past N re-read the last row (masked later)
             voff[u] = (unsigned)((grow - row0) * cb) + (BITS == 2 ? c * (a.k / 8) : c * 16);
             vcolb[u] = c * 16;
         } else {
             const int tv = t - TCH;
-            const int r = tv >> 3, pos = tv & 7;
-            voff[u] = (unsigned)r * (unsigned)w.kp + (pos ^ ((r >> 1) & 7)) * 16;
+            const int r = tv / VCPR, pos = tv % VCPR;
+            voff[u] = (unsigned)r * (unsigned)w.kp + (pos ^ ((r >> VSH) & (VCPR - 1))) * 16;
             vcolb[u] = 0;
         }
     }
@@ -597,14 +605,16 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
 #pragma unroll
     for (int b = 0; b < WR; ++b) {
         const int R = trow + 32 * b + l32;
-        if (BITS == 8) a_base[b] = R * 128 + (((l32 >> 1) & 7) >> 1) * 32 + ((half ^ ((l32 >> 1) & 1)) * 16);
-        else if (BITS == 4) a_base[b] = R * 64 + ((l32 >> 2) & 3) * 16 + half * 8;
+        const int sw = (l32 >> TSH) & (TCPR - 1);       // trow + 32 b is a multiple of 32: the key is l32's
+        if (BITS == 8) a_base[b] = R * TB + (sw >> 1) * 32 + ((half ^ (sw & 1)) * 16);
+        else if (BITS == 4) a_base[b] = R * TB + sw * 16 + half * 8;
         else a_base[b] = R * TB + half * 4;
     }
 #pragma unroll
     for (int c = 0; c < WC; ++c) {
         const int Rv = vcol + 32 * c + l32;
-        b_base[c] = TRAIN_BYTES + Rv * 128 + (((l32 >> 1) & 7) >> 1) * 32 + ((half ^ ((l32 >> 1) & 1)) * 16);
+        const int sw = (l32 >> VSH) & (VCPR - 1);
+        b_base[c] = TRAIN_BYTES + Rv * KE + (sw >> 1) * 32 + ((half ^ (sw & 1)) * 16);
     }
 
     float facc[WR][WC][16];
@@ -785,11 +795,12 @@ static int compute_units() {
 }
 
 struct MfmaPlan { int32_t vt, Mp, kp; size_t off_vw, off_vsum, off_smax, total; };
-static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int C) {
+static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int bits, int C) {
     MfmaPlan p{};
     p.vt = M > 64 ? 128 : (M > 32 ? 64 : 32);
     p.Mp = (M + p.vt - 1) / p.vt * p.vt;
-    p.kp = (k + kKE - 1) / kKE * kKE;
+    const int ke = (bits == 4 && p.vt == 32) ? kKE4Narrow : kKE;      // MfmaShape::KE of the shape used
+    p.kp = (k + ke - 1) / ke * ke;
     size_t o = (size_t)C * p.Mp * (size_t)p.kp;
     o = (o + 255) & ~(size_t)255;
     p.off_vw = o;   o += (size_t)C * p.Mp * 4;
@@ -857,7 +868,7 @@ static NarrowChoice choose_narrow(int64_t N) {
 
 template <int BITS, bool F16 = false>
 static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st) {
-    const MfmaPlan p = mfma_plan(a.N, a.M, a.k, a.C);
+    const MfmaPlan p = mfma_plan(a.N, a.M, a.k, BITS, a.C);
     ScorePrep w{};
     unsigned char *base = (unsigned char *)ws;
     w.vexp = (int8_t *)base; w.vw = (float *)(base + p.off_vw); w.vsum = (int *)(base + p.off_vsum);
@@ -896,7 +907,7 @@ using namespace qless;
 extern "C" size_t qless_score_workspace(int64_t N, int32_t M, int32_t k, int bits, int C) {
     if (N < 0 || M < 1 || k <= 0 || C < 1 || !valid_bits(bits)) return 0;
     if (!use_mfma_path(bits, M, k)) return 0;
-    return mfma_plan(N, M, k, C).total;
+    return mfma_plan(N, M, k, bits, C).total;
 }
 
 extern "C" qless_status qless_score(const void *const *train_codes, const float *const *train_rnorm,
@@ -919,7 +930,7 @@ extern "C" qless_status qless_score(const void *const *train_codes, const float 
     if (N == 0) return QLESS_OK;
     hipStream_t st = (hipStream_t)stream;
     if (use_mfma_path(bits, M, k)) {
-        const size_t need = mfma_plan(N, M, k, C).total;
+        const size_t need = mfma_plan(N, M, k, bits, C).total;
         if (!ws || ws_bytes < need) return QLESS_ERR_WORKSPACE;
         if ((uintptr_t)ws % 16) return QLESS_ERR_INVALID_ARG;
         if (N > (int64_t)0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
@@ -975,7 +986,7 @@ extern "C" qless_status qless_score(const void *const *train_codes, const float 
 // 16-bit LESS comparator: bfloat16 rows scored by the 8-bit kernel geometry on 2k bytes per row.
 extern "C" size_t qless_score16_workspace(int64_t N, int32_t M, int32_t k, int C) {
     if (N < 0 || M < 1 || k <= 0 || k > 32768 || C < 1) return 0;
-    return mfma_plan(N, M, 2 * k, C).total;
+    return mfma_plan(N, M, 2 * k, 8, C).total;
 }
 
 extern "C" qless_status qless_score16(const void *const *train16, const void *const *val16, const float *eta,
@@ -995,7 +1006,7 @@ extern "C" qless_status qless_score16(const void *const *train16, const void *co
     }
     a.C = C; a.N = N; a.M = M; a.k = 2 * k; a.score = score; a.full = full;     // k in bytes from here on
     if (N == 0) return QLESS_OK;
-    const size_t need = mfma_plan(N, M, a.k, C).total;
+    const size_t need = mfma_plan(N, M, a.k, 8, C).total;
     if (!ws || ws_bytes < need) return QLESS_ERR_WORKSPACE;
     if ((uintptr_t)ws % 16) return QLESS_ERR_INVALID_ARG;
     return launch_mfma<8, true>(a, ws, (hipStream_t)stream);
