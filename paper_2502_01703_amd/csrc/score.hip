@@ -405,7 +405,8 @@ typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(16))) int i32x16;
 
 constexpr int kKE = 128;                       // code elements per pipeline stage (most shapes)
-constexpr int kKE4Narrow = 256;                // ... of the 4-bit shape for at most 32 validation vectors
+constexpr int kKE4Narrow = 256;                // ... of the shapes for at most 32 validation vectors: 4-bit and 2-bit,
+constexpr int kKE1Narrow = 512;                // ... 1-bit
 constexpr int log2c(int x) { return x <= 1 ? 0 : 1 + log2c(x / 2); }
 
 struct ScorePrep {                             // workspace views (device pointers)
@@ -510,9 +511,10 @@ struct MfmaShape {
     static constexpr int MT = 32 * WR * WY;
     static constexpr int VT = 32 * WC * WX;
     // Code elements per stage: a stage should bring 128 bytes of every train row (whole cache lines
-    // when the codes are streamed from HBM); the 4-bit shape for few validation vectors takes 256.
+    // when the codes are streamed from HBM) as far as the expanded validation rows leave room in LDS:
+    // the shapes for few validation vectors take 256 elements (4- and 2-bit) or 512 (1-bit).
     static constexpr bool NARROW = WR * WC == 1;
-    static constexpr int KE = (BITS == 4 && NARROW) ? kKE4Narrow : kKE;
+    static constexpr int KE = !NARROW || BITS == 8 ? kKE : (BITS <= 2 ? kKE1Narrow : kKE4Narrow);
     static constexpr int TB = KE * BITS / 8;             // train bytes per row per stage: 128 / 64 or 128 / 32 / 16
     static constexpr int TCPR = TB / 16;                 // 16-byte chunks per train row
     static constexpr int VCPR = KE / 16;                 // 16-byte chunks per expanded val row
@@ -527,6 +529,9 @@ struct MfmaShape {
     // train codes from HBM: two stages per workgroup and several workgroups per compute unit,
     // whose barriers and epilogues then overlap each other's copies.
     static constexpr int NBUF = NARROW ? 2 : ((158 * 1024) / BUF >= 4 ? 4 : 3);
+    static constexpr int PLANES = BITS == 2 ? 2 : 1;     // separately stored bit planes of a train row
+    static constexpr int PCH = TCPR / PLANES;            // chunks per plane and stage
+    static constexpr int TSTEP = TB / PLANES;            // bytes a plane's source advances per stage
     static_assert(WY * WX == NW && TCH % 64 == 0 && (TCH + VCH) % 64 == 0, "whole wavefront copies");
     static_assert(NBUF * BUF <= 158 * 1024, "the ring fits in LDS");
 };
@@ -544,7 +549,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     constexpr int KE = Sh::KE, TB = Sh::TB, TCPR = Sh::TCPR, VCPR = Sh::VCPR, TSH = Sh::TSH, VSH = Sh::VSH, VT = Sh::VT;
     constexpr int TRAIN_BYTES = Sh::TRAIN_BYTES, VAL_BYTES = Sh::VAL_BYTES, TCH = Sh::TCH;
     constexpr int NINST = Sh::NINST, LPW = Sh::LPW, BUF = Sh::BUF, NBUF = Sh::NBUF;
-    constexpr int TSTEP = BITS == 2 ? 16 : TB;      // bytes a train chunk's source advances per stage
+    constexpr int TSTEP = Sh::TSTEP, PCH = Sh::PCH;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ unsigned int s_rowmax[kMT];
 
@@ -571,10 +576,10 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     // ---- copy roles of this lane: LPW wavefront copies per stage -------------------------------
     // Copy q covers LDS chunks 64 q .. 64 q + 63 of the stage buffer, laid out [train rows][val rows]
     // without padding; inside a row the 16-byte chunks are XOR-swizzled so that the MFMA operand
-    // reads (16 consecutive rows, same chunk) hit distinct banks.  2-bit train rows hold the
-    // "non-zero" chunk then the "negative" chunk of the stage (the planes are k/8 bytes apart).
+    // reads (consecutive rows, same chunk) spread over the banks.  2-bit train rows hold the
+    // "non-zero" chunks then the "negative" chunks of the stage (the planes are k/8 bytes apart).
     unsigned voff[LPW];         // lane offset from the stage's (uniform) train or val base
-    unsigned vcolb[LPW];        // byte offset of the lane's chunk inside the stage (8/4-bit train copies)
+    unsigned vcolb[LPW];        // byte offset of the lane's chunk inside its plane's share of the stage (train copies)
     bool is_train[LPW];         // wave-uniform: a copy is all train chunks or all val chunks
     unsigned dst_off[LPW];      // wave-uniform LDS offset inside the buffer
 #pragma unroll
@@ -586,11 +591,11 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
         is_train[u] = qq * 64 < TCH;
         if (t < TCH) {
             const int r = t / TCPR, pos = t % TCPR;
-            const int c = BITS >= 4 ? (pos ^ ((r >> TSH) & (TCPR - 1))) : pos;
+            const int c = pos ^ ((r >> TSH) & (TCPR - 1));
             int64_t grow = row0 + r;
             if (grow > a.N - 1) grow = a.N - 1;          // rows past N re-read the last row (masked later)
-            voff[u] = (unsigned)((grow - row0) * cb) + (BITS == 2 ? c * (a.k / 8) : c * 16);
-            vcolb[u] = c * 16;
+            voff[u] = (unsigned)((grow - row0) * cb) + (unsigned)((c / PCH) * (a.k / 8) + (c % PCH) * 16);
+            vcolb[u] = (c % PCH) * 16;
         } else {
             const int tv = t - TCH;
             const int r = tv / VCPR, pos = tv % VCPR;
@@ -598,7 +603,8 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
             vcolb[u] = 0;
         }
     }
-    const bool ragged = BITS >= 4 && (a.k % KE) != 0;  // last stage reaches past the end of the train rows
+    const bool ragged = (a.k % KE) != 0;               // the last stage reaches past the end of the train rows / planes
+    const int64_t plane_bytes = cb / Sh::PLANES;
 
     // ---- operand read addresses (swizzle folded into the lane's base, K-step applied by XOR) ---
     unsigned a_base[WR], b_base[WC];
@@ -608,7 +614,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
         const int sw = (l32 >> TSH) & (TCPR - 1);       // trow + 32 b is a multiple of 32: the key is l32's
         if (BITS == 8) a_base[b] = R * TB + (sw >> 1) * 32 + ((half ^ (sw & 1)) * 16);
         else if (BITS == 4) a_base[b] = R * TB + sw * 16 + half * 8;
-        else a_base[b] = R * TB + half * 4;
+        else a_base[b] = R * TB + sw * 16 + half * 4;   // bit planes: 4-byte reads, chunk chosen by XOR below
     }
 #pragma unroll
     for (int c = 0; c < WC; ++c) {
@@ -637,7 +643,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
             unsigned off = voff[u];
             if (tail && is_train[u]) {
                 // chunks past the row end re-read its last 16 bytes (the matching val bytes are zero)
-                const int64_t over = (int64_t)s * TB + vcolb[u] - (cb - 16);
+                const int64_t over = (int64_t)s * TSTEP + vcolb[u] - (plane_bytes - 16);
                 if (over > 0) off -= (unsigned)over;
             }
             global_to_lds16(is_train[u] ? tbase : vbase, off, buf + dst_off[u]);
@@ -673,13 +679,13 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
 #pragma unroll
                     for (int b = 0; b < WR; ++b) {
                         if (BITS == 1) {
-                            const unsigned int wd = *(const unsigned int *)(sb + a_base[b] + 8 * gp);
+                            const unsigned int wd = *(const unsigned int *)(sb + (a_base[b] ^ ((gp >> 1) << 4)) + 8 * (gp & 1));
 #pragma unroll
                             for (int jd = 0; jd < 8; ++jd)
                                 af[b][jd >> 2][jd & 3] = (int)((wd >> jd) & 0x01010101u);
                         } else {
-                            const unsigned int wn = *(const unsigned int *)(sb + a_base[b] + 8 * gp);
-                            const unsigned int wg = *(const unsigned int *)(sb + a_base[b] + 16 + 8 * gp);
+                            const unsigned int wn = *(const unsigned int *)(sb + (a_base[b] ^ ((gp >> 1) << 4)) + 8 * (gp & 1));
+                            const unsigned int wg = *(const unsigned int *)(sb + (a_base[b] ^ ((PCH + (gp >> 1)) << 4)) + 8 * (gp & 1));
 #pragma unroll
                             for (int jd = 0; jd < 8; ++jd) {
                                 const unsigned int tn = (wn >> jd) & 0x01010101u, tg = (wg >> jd) & 0x01010101u;
@@ -799,7 +805,7 @@ static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int bits, int C) {
     MfmaPlan p{};
     p.vt = M > 64 ? 128 : (M > 32 ? 64 : 32);
     p.Mp = (M + p.vt - 1) / p.vt * p.vt;
-    const int ke = (bits == 4 && p.vt == 32) ? kKE4Narrow : kKE;      // MfmaShape::KE of the shape used
+    const int ke = (p.vt != 32 || bits == 8) ? kKE : (bits <= 2 ? kKE1Narrow : kKE4Narrow);   // MfmaShape::KE of the shape used
     p.kp = (k + ke - 1) / ke * ke;
     size_t o = (size_t)C * p.Mp * (size_t)p.kp;
     o = (o + 255) & ~(size_t)255;
