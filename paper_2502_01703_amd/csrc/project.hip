@@ -233,6 +233,8 @@ project_kernel(ProjectArgs a, GaussTable gt) {
         __syncthreads();
     }
 
+    uint32_t fp4_one = 0x22222222u;                // eight FP4 codes of +1.0
+    asm volatile("" : "+v"(fp4_one));              // keep it in a vector register
     for (int s = 0; s < nstages; ++s) {
         const int buf = DIRECT ? s % kRing : (s & 1);
         if (DIRECT) {
@@ -262,7 +264,10 @@ project_kernel(ProjectArgs a, GaussTable gt) {
                     const uint32_t h = key_word(key[kb], wpair * kGold);
 #pragma unroll
                     for (int ks = 0; ks < 4; ++ks) {
-                        const uint32_t x = ((h << ks) & 0x88888888u) | 0x22222222u;
+                        // (h << ks) & 0x88888888 | 0x22222222 in two instructions: the fused and-or takes one
+                        // literal only, so the second constant is held in a register
+                        uint32_t x;
+                        asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(x) : "v"(h << ks), "s"(0x88888888u), "v"(fp4_one));
                         Frag bf;
                         bf.p[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(x, 1.0f, 0);
                         bf.p[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(x, 1.0f, 1);
