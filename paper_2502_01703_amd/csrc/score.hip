@@ -405,8 +405,10 @@ typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(16))) int i32x16;
 
 constexpr int kKE = 128;                       // code elements per pipeline stage (most shapes)
-constexpr int kKE4Narrow = 256;                // ... of the shapes for at most 32 validation vectors: 4-bit and 2-bit,
-constexpr int kKE1Narrow = 512;                // ... 1-bit
+// ... of the shapes for few validation vectors (val tile 32 or 64 wide) and codes below 8 bits
+constexpr int narrow_stage_elements(int bits, int vt) {
+    return (vt > 64 || bits == 8) ? kKE : (vt == 64 ? 256 : (bits <= 2 ? 512 : 256));
+}
 constexpr int log2c(int x) { return x <= 1 ? 0 : 1 + log2c(x / 2); }
 
 struct ScorePrep {                             // workspace views (device pointers)
@@ -513,8 +515,8 @@ struct MfmaShape {
     // Code elements per stage: a stage should bring 128 bytes of every train row (whole cache lines
     // when the codes are streamed from HBM) as far as the expanded validation rows leave room in LDS:
     // the shapes for few validation vectors take 256 elements (4- and 2-bit) or 512 (1-bit).
-    static constexpr bool NARROW = WR * WC == 1;
-    static constexpr int KE = !NARROW || BITS == 8 ? kKE : (BITS <= 2 ? kKE1Narrow : kKE4Narrow);
+    static constexpr bool NARROW = WR == 1;              // the shapes for at most 64 validation vectors
+    static constexpr int KE = narrow_stage_elements(BITS, NARROW ? 32 * WC * WX : 128);
     static constexpr int TB = KE * BITS / 8;             // train bytes per row per stage: 128 / 64 or 128 / 32 / 16
     static constexpr int TCPR = TB / 16;                 // 16-byte chunks per train row
     static constexpr int VCPR = KE / 16;                 // 16-byte chunks per expanded val row
@@ -541,7 +543,7 @@ struct MfmaShape {
 // addresses as the int8 operands), the accumulator is fp32 and the epilogue is acc += eta * D:
 // the 16-bit LESS comparator (Eq.(2),(3)) on pre-normalised rows.
 template <int BITS, int WR, int WC, int WX, int NW, bool F16 = false>
-__global__ void __launch_bounds__(64 * NW, (WR * WC == 1 ? 4 : 2))
+__global__ void __launch_bounds__(64 * NW, (WR == 1 ? 4 : 2))
 score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     static_assert(!F16 || BITS == 8, "bfloat16 rows use the byte geometry of the 8-bit codes");
     using Sh = MfmaShape<BITS, WR, WC, WX, NW>;
@@ -805,7 +807,7 @@ static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int bits, int C) {
     MfmaPlan p{};
     p.vt = M > 64 ? 128 : (M > 32 ? 64 : 32);
     p.Mp = (M + p.vt - 1) / p.vt * p.vt;
-    const int ke = (p.vt != 32 || bits == 8) ? kKE : (bits <= 2 ? kKE1Narrow : kKE4Narrow);   // MfmaShape::KE of the shape used
+    const int ke = narrow_stage_elements(bits, p.vt);                 // MfmaShape::KE of the shape used
     p.kp = (k + ke - 1) / ke * ke;
     size_t o = (size_t)C * p.Mp * (size_t)p.kp;
     o = (o + 255) & ~(size_t)255;
@@ -850,14 +852,14 @@ static qless_status launch_mfma_shape(const ScoreArgs &a, const ScorePrep &w, in
 // takes ceil(tiles / slots) rounds of equal length.  Pick the tile height (256 or 128 rows) and the
 // number of workgroups per compute unit whose last round is fullest.
 struct NarrowChoice { int nw, per_cu; };
-template <int BITS>
+template <int BITS, int WC>
 static NarrowChoice choose_narrow(int64_t N) {
     const int cus = compute_units();
     NarrowChoice best{8, 2};
     double best_eff = -1.0;
     for (int nw = 8; nw >= 4; nw -= 4) {
-        const size_t need = nw == 8 ? (size_t)MfmaShape<BITS, 1, 1, 1, 8>::NBUF * MfmaShape<BITS, 1, 1, 1, 8>::BUF
-                                    : (size_t)MfmaShape<BITS, 1, 1, 1, 4>::NBUF * MfmaShape<BITS, 1, 1, 1, 4>::BUF;
+        const size_t need = nw == 8 ? (size_t)MfmaShape<BITS, 1, WC, 1, 8>::NBUF * MfmaShape<BITS, 1, WC, 1, 8>::BUF
+                                    : (size_t)MfmaShape<BITS, 1, WC, 1, 4>::NBUF * MfmaShape<BITS, 1, WC, 1, 4>::BUF;
         const int64_t tiles = (N + 32 * nw - 1) / (32 * nw);
         int cap = (int)(kLdsPerCU / (need + kStaticLds));
         if (cap > 16 / nw) cap = 16 / nw;                 // at most 16 wavefronts per compute unit
@@ -882,9 +884,12 @@ static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st) {
     hipLaunchKernelGGL((score_prepare_kernel<BITS, F16>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
     qless_status rc;
     if (p.vt == 128) rc = launch_mfma_shape<BITS, 2, 2, 2, 8, F16>(a, w, 0, st);
-    else if (p.vt == 64) rc = launch_mfma_shape<BITS, 1, 2, 1, 8, F16>(a, w, 0, st);
-    else {
-        const NarrowChoice c = choose_narrow<BITS>(a.N);
+    else if (p.vt == 64) {
+        const NarrowChoice c = choose_narrow<BITS, 2>(a.N);
+        if (c.nw == 8) rc = launch_mfma_shape<BITS, 1, 2, 1, 8, F16>(a, w, c.per_cu, st);
+        else rc = launch_mfma_shape<BITS, 1, 2, 1, 4, F16>(a, w, c.per_cu, st);
+    } else {
+        const NarrowChoice c = choose_narrow<BITS, 1>(a.N);
         if (c.nw == 8) rc = launch_mfma_shape<BITS, 1, 1, 1, 8, F16>(a, w, c.per_cu, st);
         else rc = launch_mfma_shape<BITS, 1, 1, 1, 4, F16>(a, w, c.per_cu, st);
     }
