@@ -407,7 +407,8 @@ typedef __attribute__((ext_vector_type(16))) int i32x16;
 constexpr int kKE = 128;                       // code elements per pipeline stage (most shapes)
 // ... of the shapes for few validation vectors (val tile 32 or 64 wide) and codes below 8 bits
 constexpr int narrow_stage_elements(int bits, int vt) {
-    return (vt > 64 || bits == 8) ? kKE : (vt == 64 ? 256 : (bits <= 2 ? 512 : 256));
+    return bits == 1 ? (vt > 64 ? 256 : 512)             // FP4 operands: half a byte per validation element
+                     : ((vt > 64 || bits == 8) ? kKE : (vt == 64 ? 256 : (bits == 2 ? 512 : 256)));
 }
 constexpr int log2c(int x) { return x <= 1 ? 0 : 1 + log2c(x / 2); }
 
@@ -416,7 +417,8 @@ struct ScorePrep {                             // workspace views (device pointe
     float *vw;                                 // [C][Mp]
     int *vsum;                                 // [C][Mp]
     unsigned int *smax;                        // [N] order-preserving keys of the row maxima
-    int32_t Mp, kp;
+    int32_t Mp, kp;                            // padded validation rows / elements per row
+    int32_t vrow;                              // bytes per expanded validation row: kp, or kp / 2 for 1-bit (FP4 codes)
 };
 
 __device__ inline unsigned int f32_order_key(float f) {
@@ -437,7 +439,12 @@ __device__ inline int val_source_element(int p) {
         const int d = i >> 2, b = i & 3;               // dword d, byte b
         return base + 8 * (d >> 1) + 2 * b + (d & 1);
     }
-    // bit planes: K-step pair g (64 elements), step s, half h, dword jj, byte b
+    if (BITS == 1) {
+        // FP4 codes: K step g (64 elements), half h, dword j, nibble n <- bit 4 n + 3 - j of the lane's word
+        const int g = p >> 6, h = (p >> 5) & 1, j = (p >> 3) & 3, n = p & 7;
+        return 64 * g + 32 * h + 4 * n + 3 - j;
+    }
+    // 2-bit planes: K-step pair g (64 elements), step s, half h, dword jj, byte b
     const int g = p >> 6, s = (p >> 5) & 1, h = (p >> 4) & 1, jj = (p >> 2) & 3, b = p & 3;
     return 64 * g + 32 * h + 8 * b + 4 * s + jj;
 }
@@ -446,10 +453,26 @@ template <int BITS, bool F16 = false>        // F16: rows are bfloat16 bytes, no
 __global__ void __launch_bounds__(256)
 score_prepare_kernel(ScoreArgs a, ScorePrep w) {
     const int row = blockIdx.x, ci = blockIdx.y;        // row < Mp
-    int8_t *dst = w.vexp + ((size_t)ci * w.Mp + row) * (size_t)w.kp;
+    int8_t *dst = w.vexp + ((size_t)ci * w.Mp + row) * (size_t)w.vrow;
     const bool live = row < a.M;
     const unsigned char *src = a.vc[ci] + (int64_t)(live ? row : 0) * ((int64_t)a.k * BITS / 8);
     int part = 0;
+    if (BITS == 1) {
+        // two FP4 codes per byte: 0x2 = +1.0, 0xA = -1.0, 0 past the end of the vector
+        for (int bi = threadIdx.x; bi < w.vrow; bi += 256) {
+            unsigned byte = 0;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int pos = 2 * bi + e;
+                if (live && pos < a.k) {
+                    const int m = val_source_element<1>(pos);
+                    const unsigned neg = (src[m >> 3] >> (m & 7)) & 1u;
+                    byte |= (0x2u | (neg << 3)) << (4 * e);
+                }
+            }
+            dst[bi] = (int8_t)byte;
+        }
+    } else
     for (int p = threadIdx.x; p < w.kp; p += 256) {
         int q = 0;
         if (live && p < a.k) {
@@ -497,6 +520,11 @@ template <>
 __device__ inline i32x16 mfma_step<false>(i32x4 a, i32x4 b, i32x16 c) {
     return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
 }
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+// 64 FP4 (E2M1) products per lane pair, both scales 2^0: the sign codes' dot products, exact in fp32
+__device__ inline f32x16 mfma_fp4(i32x8 a, i32x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 4, 4, 0, 127, 0, 127);
+}
 template <>
 __device__ inline f32x16 mfma_step<true>(i32x4 a, i32x4 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -516,13 +544,15 @@ struct MfmaShape {
     // when the codes are streamed from HBM) as far as the expanded validation rows leave room in LDS:
     // the shapes for few validation vectors take 256 elements (4- and 2-bit) or 512 (1-bit).
     static constexpr bool NARROW = WR == 1;              // the shapes for at most 64 validation vectors
-    static constexpr int KE = narrow_stage_elements(BITS, NARROW ? 32 * WC * WX : 128);
-    static constexpr int TB = KE * BITS / 8;             // train bytes per row per stage: 128 / 64 or 128 / 32 / 16
+    static constexpr int KE = narrow_stage_elements(BITS, 32 * WC * WX);
+    static constexpr bool FP4 = BITS == 1;               // sign codes go to the matrix core as FP4 +-1.0
+    static constexpr int TB = KE * BITS / 8;             // train bytes per row per stage
     static constexpr int TCPR = TB / 16;                 // 16-byte chunks per train row
-    static constexpr int VCPR = KE / 16;                 // 16-byte chunks per expanded val row
+    static constexpr int VROWB = FP4 ? KE / 2 : KE;      // bytes per expanded val row per stage
+    static constexpr int VCPR = VROWB / 16;              // 16-byte chunks per expanded val row
     // rows whose chunks share a bank group are 16 / CPR apart: the swizzle key is (row >> SH) % CPR
     static constexpr int TSH = log2c(16 / TCPR), VSH = log2c(16 / VCPR);
-    static constexpr int TRAIN_BYTES = MT * TB, VAL_BYTES = VT * KE;
+    static constexpr int TRAIN_BYTES = MT * TB, VAL_BYTES = VT * VROWB;
     static constexpr int TCH = MT * TCPR, VCH = VT * VCPR;
     static constexpr int NINST = (TCH + VCH) / 64;       // wavefront-wide copies per stage
     static constexpr int LPW = (NINST + NW - 1) / NW;    // per wave
@@ -601,7 +631,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
         } else {
             const int tv = t - TCH;
             const int r = tv / VCPR, pos = tv % VCPR;
-            voff[u] = (unsigned)r * (unsigned)w.kp + (pos ^ ((r >> VSH) & (VCPR - 1))) * 16;
+            voff[u] = (unsigned)r * (unsigned)w.vrow + (pos ^ ((r >> VSH) & (VCPR - 1))) * 16;
             vcolb[u] = 0;
         }
     }
@@ -622,7 +652,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     for (int c = 0; c < WC; ++c) {
         const int Rv = vcol + 32 * c + l32;
         const int sw = (l32 >> VSH) & (VCPR - 1);
-        b_base[c] = TRAIN_BYTES + Rv * KE + (sw >> 1) * 32 + ((half ^ (sw & 1)) * 16);
+        b_base[c] = TRAIN_BYTES + Rv * Sh::VROWB + (sw >> 1) * 32 + ((half ^ (sw & 1)) * 16);
     }
 
     float facc[WR][WC][16];
@@ -637,7 +667,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     auto issue = [&](int g) {                        // start the copies of global stage g
         const int ci = g / nstages, s = g - ci * nstages;
         const unsigned char *tbase = a.tc[ci] + row0 * cb + (int64_t)s * TSTEP;
-        const unsigned char *vbase = (const unsigned char *)w.vexp + ((size_t)ci * w.Mp + v0) * (size_t)w.kp + (size_t)s * KE;
+        const unsigned char *vbase = (const unsigned char *)w.vexp + ((size_t)ci * w.Mp + v0) * (size_t)w.vrow + (size_t)s * Sh::VROWB;
         const unsigned buf = lds0 + (unsigned)(g % NBUF) * BUF;
         const bool tail = ragged && s == nstages - 1;
 #pragma unroll
@@ -659,7 +689,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
 
     int g = 0;
     for (int ci = 0; ci < a.C; ++ci) {
-        typename AccType<F16>::type acc[WR][WC];
+        typename AccType<F16 || BITS == 1>::type acc[WR][WC];
 #pragma unroll
         for (int b = 0; b < WR; ++b)
 #pragma unroll
@@ -674,18 +704,39 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
             __syncthreads();                         // stage g visible to all; buffer of stage g-1 free
             if (g + NBUF - 1 < total) issue(g + NBUF - 1);
             const unsigned char *sb = smem + (g % NBUF) * BUF;
-            if (BITS <= 2) {
+            if constexpr (BITS == 1) {
+                // sign codes as FP4: one 64-element K step per matrix-core instruction.  A lane's word
+                // (32 signs of its row) becomes four dwords of FP4 codes, dword j = bits 3 - j of every
+                // nibble: ((w << j) & 0x88888888) | 0x22222222 -> 0x2 = +1.0, 0xA = -1.0.
+#pragma unroll
+                for (int ks = 0; ks < KE / 64; ++ks) {
+                    i32x8 af[WR], bf[WC];
+#pragma unroll
+                    for (int b = 0; b < WR; ++b) {
+                        const unsigned int wd = *(const unsigned int *)(sb + (a_base[b] ^ ((ks >> 1) << 4)) + 8 * (ks & 1));
+#pragma unroll
+                        for (int jd = 0; jd < 4; ++jd) af[b][jd] = (int)(((wd << jd) & 0x88888888u) | 0x22222222u);
+#pragma unroll
+                        for (int jd = 4; jd < 8; ++jd) af[b][jd] = 0;
+                    }
+#pragma unroll
+                    for (int c = 0; c < WC; ++c) {
+                        const i32x4 lo = *(const i32x4 *)(sb + (b_base[c] ^ (ks << 5)));
+                        bf[c] = i32x8{lo[0], lo[1], lo[2], lo[3], 0, 0, 0, 0};
+                    }
+#pragma unroll
+                    for (int b = 0; b < WR; ++b)
+#pragma unroll
+                        for (int c = 0; c < WC; ++c)
+                            acc[b][c] = mfma_fp4(af[b], bf[c], acc[b][c]);
+                }
+            } else if constexpr (BITS == 2) {
 #pragma unroll
                 for (int gp = 0; gp < KE / 64; ++gp) {          // K-step pairs
                     i32x4 af[WR][2];
 #pragma unroll
                     for (int b = 0; b < WR; ++b) {
-                        if (BITS == 1) {
-                            const unsigned int wd = *(const unsigned int *)(sb + (a_base[b] ^ ((gp >> 1) << 4)) + 8 * (gp & 1));
-#pragma unroll
-                            for (int jd = 0; jd < 8; ++jd)
-                                af[b][jd >> 2][jd & 3] = (int)((wd >> jd) & 0x01010101u);
-                        } else {
+                        {
                             const unsigned int wn = *(const unsigned int *)(sb + (a_base[b] ^ ((gp >> 1) << 4)) + 8 * (gp & 1));
                             const unsigned int wg = *(const unsigned int *)(sb + (a_base[b] ^ ((PCH + (gp >> 1)) << 4)) + 8 * (gp & 1));
 #pragma unroll
@@ -738,12 +789,10 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
         if (myrow > a.N - 1) myrow = a.N - 1;
         const float rt_lane = F16 ? 1.0f : a.tr[ci][myrow];
         float wv[WC];
-        int vs[WC];
 #pragma unroll
         for (int c = 0; c < WC; ++c) {
             const int col = v0 + vcol + 32 * c + l32;               // < Mp (padded)
             wv[c] = w.vw[ci * w.Mp + col];
-            vs[c] = BITS == 1 ? w.vsum[ci * w.Mp + col] : 0;
         }
 #pragma unroll
         for (int b = 0; b < WR; ++b)
@@ -756,7 +805,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
                     if (F16) {
                         t = __fmul_rn((float)acc[b][c][v], wv[c]);
                     } else {
-                        const int D = BITS == 4 ? ((int)acc[b][c][v] >> 4) : (BITS == 1 ? vs[c] - 2 * (int)acc[b][c][v] : (int)acc[b][c][v]);
+                        const int D = BITS == 4 ? ((int)acc[b][c][v] >> 4) : (int)acc[b][c][v];   // 1-bit: an exact integer in fp32
                         t = __fmul_rn(__fmul_rn((float)D, rt), wv[c]);
                     }
                     facc[b][c][v] = __fadd_rn(facc[b][c][v], t);
@@ -881,6 +930,7 @@ static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st) {
     unsigned char *base = (unsigned char *)ws;
     w.vexp = (int8_t *)base; w.vw = (float *)(base + p.off_vw); w.vsum = (int *)(base + p.off_vsum);
     w.smax = (unsigned int *)(base + p.off_smax); w.Mp = p.Mp; w.kp = p.kp;
+    w.vrow = BITS == 1 ? p.kp / 2 : p.kp;
     hipLaunchKernelGGL((score_prepare_kernel<BITS, F16>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
     qless_status rc;
     if (p.vt == 128) rc = launch_mfma_shape<BITS, 2, 2, 2, 8, F16>(a, w, 0, st);
