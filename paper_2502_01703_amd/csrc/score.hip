@@ -407,7 +407,7 @@ typedef __attribute__((ext_vector_type(16))) int i32x16;
 constexpr int kKE = 128;                       // code elements per pipeline stage (most shapes)
 // ... of the shapes for few validation vectors (val tile 32 or 64 wide) and codes below 8 bits
 constexpr int narrow_stage_elements(int bits, int vt) {
-    return bits == 1 ? (vt > 64 ? 256 : 512)             // FP4 operands: half a byte per validation element
+    return bits == 1 ? (vt > 64 ? 512 : 512)             // FP4 operands: half a byte per validation element
                      : ((vt > 64 || bits == 8) ? kKE : (vt == 64 ? 256 : (bits == 2 ? 512 : 256)));
 }
 constexpr int log2c(int x) { return x <= 1 ? 0 : 1 + log2c(x / 2); }
