@@ -407,7 +407,7 @@ typedef __attribute__((ext_vector_type(16))) int i32x16;
 constexpr int kKE = 128;                       // code elements per pipeline stage (most shapes)
 // ... of the shapes for few validation vectors (val tile 32 or 64 wide) and codes below 8 bits
 constexpr int narrow_stage_elements(int bits, int vt) {
-    return bits == 1 ? (vt > 64 ? 512 : 512)             // FP4 operands: half a byte per validation element
+    return bits == 1 ? 512                               // sign codes stay packed in LDS: 64 bytes per row and stage
                      : ((vt > 64 || bits == 8) ? kKE : (vt == 64 ? 256 : (bits == 2 ? 512 : 256)));
 }
 constexpr int log2c(int x) { return x <= 1 ? 0 : 1 + log2c(x / 2); }
@@ -458,7 +458,8 @@ score_prepare_kernel(ScoreArgs a, ScorePrep w) {
     const unsigned char *src = a.vc[ci] + (int64_t)(live ? row : 0) * ((int64_t)a.k * BITS / 8);
     int part = 0;
     if (BITS == 1) {
-        // two FP4 codes per byte: 0x2 = +1.0, 0xA = -1.0, 0 past the end of the vector
+        // wide tiles (vrow != 0): two FP4 codes per byte, 0x2 = +1.0, 0xA = -1.0, 0 past the end of the
+        // vector.  Few validation vectors (vrow == 0): the main kernel stages the packed codes itself.
         for (int bi = threadIdx.x; bi < w.vrow; bi += 256) {
             unsigned byte = 0;
 #pragma unroll
@@ -548,7 +549,10 @@ struct MfmaShape {
     static constexpr bool FP4 = BITS == 1;               // sign codes go to the matrix core as FP4 +-1.0
     static constexpr int TB = KE * BITS / 8;             // train bytes per row per stage
     static constexpr int TCPR = TB / 16;                 // 16-byte chunks per train row
-    static constexpr int VROWB = FP4 ? KE / 2 : KE;      // bytes per expanded val row per stage
+    // val bytes per row per stage: int8-expanded; for the sign codes FP4-expanded by the pre-pass (wide
+    // tiles, where the VALU has no room to expand both operands), or the packed signs themselves
+    static constexpr bool VPACKED = FP4 && NARROW;
+    static constexpr int VROWB = VPACKED ? KE / 8 : (FP4 ? KE / 2 : KE);
     static constexpr int VCPR = VROWB / 16;              // 16-byte chunks per expanded val row
     // rows whose chunks share a bank group are 16 / CPR apart: the swizzle key is (row >> SH) % CPR
     static constexpr int TSH = log2c(16 / TCPR), VSH = log2c(16 / VCPR);
@@ -631,8 +635,16 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
         } else {
             const int tv = t - TCH;
             const int r = tv / VCPR, pos = tv % VCPR;
-            voff[u] = (unsigned)r * (unsigned)w.vrow + (pos ^ ((r >> VSH) & (VCPR - 1))) * 16;
-            vcolb[u] = 0;
+            const int c = pos ^ ((r >> VSH) & (VCPR - 1));
+            if (Sh::VPACKED) {
+                // 1-bit, few validation vectors: the packed validation rows are staged as they are (rows past M re-read the last one)
+                const int rc = v0 + r < a.M ? r : a.M - 1 - v0;
+                voff[u] = (unsigned)rc * (unsigned)cb + c * 16;
+                vcolb[u] = c * 16;
+            } else {
+                voff[u] = (unsigned)r * (unsigned)w.vrow + c * 16;
+                vcolb[u] = 0;
+            }
         }
     }
     const bool ragged = (a.k % KE) != 0;               // the last stage reaches past the end of the train rows / planes
@@ -652,7 +664,8 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     for (int c = 0; c < WC; ++c) {
         const int Rv = vcol + 32 * c + l32;
         const int sw = (l32 >> VSH) & (VCPR - 1);
-        b_base[c] = TRAIN_BYTES + Rv * Sh::VROWB + (sw >> 1) * 32 + ((half ^ (sw & 1)) * 16);
+        if (Sh::VPACKED) b_base[c] = TRAIN_BYTES + Rv * Sh::VROWB + sw * 16 + half * 4;  // 4-byte reads, chunk chosen by XOR
+        else b_base[c] = TRAIN_BYTES + Rv * Sh::VROWB + (sw >> 1) * 32 + ((half ^ (sw & 1)) * 16);
     }
 
     float facc[WR][WC][16];
@@ -667,15 +680,17 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     auto issue = [&](int g) {                        // start the copies of global stage g
         const int ci = g / nstages, s = g - ci * nstages;
         const unsigned char *tbase = a.tc[ci] + row0 * cb + (int64_t)s * TSTEP;
-        const unsigned char *vbase = (const unsigned char *)w.vexp + ((size_t)ci * w.Mp + v0) * (size_t)w.vrow + (size_t)s * Sh::VROWB;
+        const unsigned char *vbase = Sh::VPACKED ? a.vc[ci] + (int64_t)v0 * cb + (int64_t)s * Sh::VROWB
+                                             : (const unsigned char *)w.vexp + ((size_t)ci * w.Mp + v0) * (size_t)w.vrow + (size_t)s * Sh::VROWB;
         const unsigned buf = lds0 + (unsigned)(g % NBUF) * BUF;
         const bool tail = ragged && s == nstages - 1;
 #pragma unroll
         for (int u = 0; u < LPW; ++u) {
             unsigned off = voff[u];
-            if (tail && is_train[u]) {
-                // chunks past the row end re-read its last 16 bytes (the matching val bytes are zero)
-                const int64_t over = (int64_t)s * TSTEP + vcolb[u] - (plane_bytes - 16);
+            if (tail && (is_train[u] || Sh::VPACKED)) {
+                // chunks past the row end re-read its last 16 bytes (the matching val bytes are zero, or,
+                // for the packed sign codes, the K steps past the end are not computed)
+                const int64_t over = (int64_t)s * (is_train[u] ? TSTEP : Sh::VROWB) + vcolb[u] - (plane_bytes - 16);
                 if (over > 0) off -= (unsigned)over;
             }
             global_to_lds16(is_train[u] ? tbase : vbase, off, buf + dst_off[u]);
@@ -708,8 +723,11 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
                 // sign codes as FP4: one 64-element K step per matrix-core instruction.  A lane's word
                 // (32 signs of its row) becomes four dwords of FP4 codes, dword j = bits 3 - j of every
                 // nibble: ((w << j) & 0x88888888) | 0x22222222 -> 0x2 = +1.0, 0xA = -1.0.
+                // K steps of the last stage that start past the end of the vectors are skipped (k % 64 == 0)
+                const int ksteps = (a.k - s * KE) / 64 < KE / 64 ? (a.k - s * KE) / 64 : KE / 64;
 #pragma unroll
                 for (int ks = 0; ks < KE / 64; ++ks) {
+                    if (Sh::VPACKED && ks >= ksteps) break;    // (pre-expanded validation rows are zero there)
                     i32x8 af[WR], bf[WC];
 #pragma unroll
                     for (int b = 0; b < WR; ++b) {
@@ -721,8 +739,16 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
                     }
 #pragma unroll
                     for (int c = 0; c < WC; ++c) {
-                        const i32x4 lo = *(const i32x4 *)(sb + (b_base[c] ^ (ks << 5)));
-                        bf[c] = i32x8{lo[0], lo[1], lo[2], lo[3], 0, 0, 0, 0};
+                        if (Sh::VPACKED) {
+                            const unsigned int wd = *(const unsigned int *)(sb + (b_base[c] ^ ((ks >> 1) << 4)) + 8 * (ks & 1));
+#pragma unroll
+                            for (int jd = 0; jd < 4; ++jd) bf[c][jd] = (int)(((wd << jd) & 0x88888888u) | 0x22222222u);
+#pragma unroll
+                            for (int jd = 4; jd < 8; ++jd) bf[c][jd] = 0;
+                        } else {
+                            const i32x4 lo = *(const i32x4 *)(sb + (b_base[c] ^ (ks << 5)));
+                            bf[c] = i32x8{lo[0], lo[1], lo[2], lo[3], 0, 0, 0, 0};
+                        }
                     }
 #pragma unroll
                     for (int b = 0; b < WR; ++b)
@@ -930,7 +956,7 @@ static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st) {
     unsigned char *base = (unsigned char *)ws;
     w.vexp = (int8_t *)base; w.vw = (float *)(base + p.off_vw); w.vsum = (int *)(base + p.off_vsum);
     w.smax = (unsigned int *)(base + p.off_smax); w.Mp = p.Mp; w.kp = p.kp;
-    w.vrow = BITS == 1 ? p.kp / 2 : p.kp;
+    w.vrow = BITS == 1 ? (p.vt > 64 ? p.kp / 2 : 0) : p.kp;
     hipLaunchKernelGGL((score_prepare_kernel<BITS, F16>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
     qless_status rc;
     if (p.vt == 128) rc = launch_mfma_shape<BITS, 2, 2, 2, 8, F16>(a, w, 0, st);
