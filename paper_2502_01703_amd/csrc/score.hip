@@ -407,8 +407,9 @@ typedef __attribute__((ext_vector_type(16))) int i32x16;
 constexpr int kKE = 128;                       // code elements per pipeline stage (most shapes)
 // ... of the shapes for few validation vectors (val tile 32 or 64 wide) and codes below 8 bits
 constexpr int narrow_stage_elements(int bits, int vt) {
-    return bits == 1 ? 512                               // sign codes stay packed in LDS: 64 bytes per row and stage
-                     : ((vt > 64 || bits == 8) ? kKE : (vt == 64 ? 256 : (bits == 2 ? 512 : 256)));
+    return bits == 1 ? 512                               // sign codes: 64 bytes per train row and stage
+         : bits == 2 ? (vt > 64 ? 256 : 512)             // two planes of 32 or 64 bytes
+                     : ((vt > 64 || bits == 8) ? kKE : 256);
 }
 constexpr int log2c(int x) { return x <= 1 ? 0 : 1 + log2c(x / 2); }
 
@@ -439,14 +440,9 @@ __device__ inline int val_source_element(int p) {
         const int d = i >> 2, b = i & 3;               // dword d, byte b
         return base + 8 * (d >> 1) + 2 * b + (d & 1);
     }
-    if (BITS == 1) {
-        // FP4 codes: K step g (64 elements), half h, dword j, nibble n <- bit 4 n + 3 - j of the lane's word
-        const int g = p >> 6, h = (p >> 5) & 1, j = (p >> 3) & 3, n = p & 7;
-        return 64 * g + 32 * h + 4 * n + 3 - j;
-    }
-    // 2-bit planes: K-step pair g (64 elements), step s, half h, dword jj, byte b
-    const int g = p >> 6, s = (p >> 5) & 1, h = (p >> 4) & 1, jj = (p >> 2) & 3, b = p & 3;
-    return 64 * g + 32 * h + 8 * b + 4 * s + jj;
+    // FP4 codes (1- and 2-bit): K step g (64 elements), half h, dword j, nibble n <- bit 4 n + 3 - j of the lane's word
+    const int g = p >> 6, h = (p >> 5) & 1, j = (p >> 3) & 3, n = p & 7;
+    return 64 * g + 32 * h + 4 * n + 3 - j;
 }
 
 template <int BITS, bool F16 = false>        // F16: rows are bfloat16 bytes, no code norms (see score_mfma_kernel)
@@ -457,18 +453,24 @@ score_prepare_kernel(ScoreArgs a, ScorePrep w) {
     const bool live = row < a.M;
     const unsigned char *src = a.vc[ci] + (int64_t)(live ? row : 0) * ((int64_t)a.k * BITS / 8);
     int part = 0;
-    if (BITS == 1) {
-        // wide tiles (vrow != 0): two FP4 codes per byte, 0x2 = +1.0, 0xA = -1.0, 0 past the end of the
-        // vector.  Few validation vectors (vrow == 0): the main kernel stages the packed codes itself.
+    if (BITS <= 2) {
+        // two FP4 codes per byte: 0x2 = +1.0, 0xA = -1.0, 0x0 = 0 (2-bit zeros, and past the end of the
+        // vector).  1-bit with few validation vectors (vrow == 0): the main kernel stages the packed codes itself.
         for (int bi = threadIdx.x; bi < w.vrow; bi += 256) {
             unsigned byte = 0;
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
                 const int pos = 2 * bi + e;
                 if (live && pos < a.k) {
-                    const int m = val_source_element<1>(pos);
-                    const unsigned neg = (src[m >> 3] >> (m & 7)) & 1u;
-                    byte |= (0x2u | (neg << 3)) << (4 * e);
+                    const int m = val_source_element<BITS>(pos);
+                    unsigned nz = 1u, neg;
+                    if (BITS == 2) {
+                        nz = (src[m >> 3] >> (m & 7)) & 1u;
+                        neg = (src[a.k / 8 + (m >> 3)] >> (m & 7)) & 1u;
+                    } else {
+                        neg = (src[m >> 3] >> (m & 7)) & 1u;
+                    }
+                    byte |= ((nz << 1) | (neg << 3)) << (4 * e);
                 }
             }
             dst[bi] = (int8_t)byte;
@@ -546,12 +548,12 @@ struct MfmaShape {
     // the shapes for few validation vectors take 256 elements (4- and 2-bit) or 512 (1-bit).
     static constexpr bool NARROW = WR == 1;              // the shapes for at most 64 validation vectors
     static constexpr int KE = narrow_stage_elements(BITS, 32 * WC * WX);
-    static constexpr bool FP4 = BITS == 1;               // sign codes go to the matrix core as FP4 +-1.0
+    static constexpr bool FP4 = BITS <= 2;               // sign / ternary codes go to the matrix core as FP4 +-1.0, 0
     static constexpr int TB = KE * BITS / 8;             // train bytes per row per stage
     static constexpr int TCPR = TB / 16;                 // 16-byte chunks per train row
     // val bytes per row per stage: int8-expanded; for the sign codes FP4-expanded by the pre-pass (wide
     // tiles, where the VALU has no room to expand both operands), or the packed signs themselves
-    static constexpr bool VPACKED = FP4 && NARROW;
+    static constexpr bool VPACKED = BITS == 1 && NARROW;
     static constexpr int VROWB = VPACKED ? KE / 8 : (FP4 ? KE / 2 : KE);
     static constexpr int VCPR = VROWB / 16;              // 16-byte chunks per expanded val row
     // rows whose chunks share a bank group are 16 / CPR apart: the swizzle key is (row >> SH) % CPR
@@ -704,7 +706,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
 
     int g = 0;
     for (int ci = 0; ci < a.C; ++ci) {
-        typename AccType<F16 || BITS == 1>::type acc[WR][WC];
+        typename AccType<F16 || BITS <= 2>::type acc[WR][WC];
 #pragma unroll
         for (int b = 0; b < WR; ++b)
 #pragma unroll
@@ -757,33 +759,33 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
                             acc[b][c] = mfma_fp4(af[b], bf[c], acc[b][c]);
                 }
             } else if constexpr (BITS == 2) {
+                // ternary codes as FP4 {-1.0, 0, +1.0}: nibble bit 3 <- "negative" plane, bit 1 <- "non-zero"
+                // plane (0xA, 0x0, 0x2); dword j takes bits 4 n + 3 - j of the lane's two plane words
 #pragma unroll
-                for (int gp = 0; gp < KE / 64; ++gp) {          // K-step pairs
-                    i32x4 af[WR][2];
+                for (int ks = 0; ks < KE / 64; ++ks) {
+                    i32x8 af[WR], bf[WC];
 #pragma unroll
                     for (int b = 0; b < WR; ++b) {
-                        {
-                            const unsigned int wn = *(const unsigned int *)(sb + (a_base[b] ^ ((gp >> 1) << 4)) + 8 * (gp & 1));
-                            const unsigned int wg = *(const unsigned int *)(sb + (a_base[b] ^ ((PCH + (gp >> 1)) << 4)) + 8 * (gp & 1));
+                        const unsigned int wn = *(const unsigned int *)(sb + (a_base[b] ^ ((ks >> 1) << 4)) + 8 * (ks & 1));
+                        const unsigned int wg = *(const unsigned int *)(sb + (a_base[b] ^ ((PCH + (ks >> 1)) << 4)) + 8 * (ks & 1));
 #pragma unroll
-                            for (int jd = 0; jd < 8; ++jd) {
-                                const unsigned int tn = (wn >> jd) & 0x01010101u, tg = (wg >> jd) & 0x01010101u;
-                                af[b][jd >> 2][jd & 3] = (int)(tn | (tg * 0xFEu));   // bytes 0, 1 or 0xFF (-1)
-                            }
+                        for (int jd = 0; jd < 4; ++jd) {
+                            const unsigned int zs = jd >= 2 ? wn << (jd - 2) : wn >> (2 - jd);
+                            af[b][jd] = (int)(((wg << jd) & 0x88888888u) | (zs & 0x22222222u));
                         }
+#pragma unroll
+                        for (int jd = 4; jd < 8; ++jd) af[b][jd] = 0;
                     }
 #pragma unroll
-                    for (int s2 = 0; s2 < 2; ++s2) {
-                        i32x4 bf[WC];
+                    for (int c = 0; c < WC; ++c) {
+                        const i32x4 lo = *(const i32x4 *)(sb + (b_base[c] ^ (ks << 5)));
+                        bf[c] = i32x8{lo[0], lo[1], lo[2], lo[3], 0, 0, 0, 0};
+                    }
+#pragma unroll
+                    for (int b = 0; b < WR; ++b)
 #pragma unroll
                         for (int c = 0; c < WC; ++c)
-                            bf[c] = *(const i32x4 *)(sb + (b_base[c] ^ ((2 * gp + s2) << 5)));
-#pragma unroll
-                        for (int b = 0; b < WR; ++b)
-#pragma unroll
-                            for (int c = 0; c < WC; ++c)
-                                acc[b][c] = mfma_step<F16>(af[b][s2], bf[c], acc[b][c]);
-                    }
+                            acc[b][c] = mfma_fp4(af[b], bf[c], acc[b][c]);
                 }
             } else {
 #pragma unroll
@@ -956,7 +958,7 @@ static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st) {
     unsigned char *base = (unsigned char *)ws;
     w.vexp = (int8_t *)base; w.vw = (float *)(base + p.off_vw); w.vsum = (int *)(base + p.off_vsum);
     w.smax = (unsigned int *)(base + p.off_smax); w.Mp = p.Mp; w.kp = p.kp;
-    w.vrow = BITS == 1 ? (p.vt > 64 ? p.kp / 2 : 0) : p.kp;
+    w.vrow = BITS == 1 ? (p.vt > 64 ? p.kp / 2 : 0) : (BITS == 2 ? p.kp / 2 : p.kp);
     hipLaunchKernelGGL((score_prepare_kernel<BITS, F16>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
     qless_status rc;
     if (p.vt == 128) rc = launch_mfma_shape<BITS, 2, 2, 2, 8, F16>(a, w, 0, st);
