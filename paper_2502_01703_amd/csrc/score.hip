@@ -408,7 +408,7 @@ constexpr int kKE = 128;                       // code elements per pipeline sta
 // ... of the shapes for few validation vectors (val tile 32 or 64 wide) and codes below 8 bits
 constexpr int narrow_stage_elements(int bits, int vt) {
     return bits == 1 ? 512                               // sign codes: 64 bytes per train row and stage
-         : bits == 2 ? (vt > 64 ? 256 : 512)             // two planes of 32 or 64 bytes
+         : bits == 2 ? 512                               // two planes of 64 bytes
                      : ((vt > 64 || bits == 8) ? kKE : 256);
 }
 constexpr int log2c(int x) { return x <= 1 ? 0 : 1 + log2c(x / 2); }
@@ -566,12 +566,12 @@ struct MfmaShape {
     // LDS ring depth.  The narrow shapes serve few validation vectors, where scoring streams the
     // train codes from HBM: two stages per workgroup and several workgroups per compute unit,
     // whose barriers and epilogues then overlap each other's copies.
-    static constexpr int NBUF = NARROW ? 2 : ((158 * 1024) / BUF >= 4 ? 4 : 3);
+    static constexpr int NBUF = NARROW ? 2 : ((158 * 1024) / BUF >= 4 ? 4 : (158 * 1024) / BUF);
     static constexpr int PLANES = BITS == 2 ? 2 : 1;     // separately stored bit planes of a train row
     static constexpr int PCH = TCPR / PLANES;            // chunks per plane and stage
     static constexpr int TSTEP = TB / PLANES;            // bytes a plane's source advances per stage
     static_assert(WY * WX == NW && TCH % 64 == 0 && (TCH + VCH) % 64 == 0, "whole wavefront copies");
-    static_assert(NBUF * BUF <= 158 * 1024, "the ring fits in LDS");
+    static_assert(NBUF >= 2 && NBUF * BUF <= 158 * 1024, "a ring of at least two stages fits in LDS");
 };
 
 // F16 (with BITS = 8 and k counted in bytes): the rows are bfloat16 vectors, the 16 bytes a lane feeds
