@@ -3,10 +3,12 @@
 // reduced by max over validation examples.
 //
 // Integer dot products are exact; how they are formed depends on the code width:
-//   all widths, more than 16 val vectors: int8 x int8 -> int32 MFMA (v_mfma_i32_32x32x32_i8) on
-//           codes unpacked to int8 in registers (see score_mfma_kernel)
-//   1-bit, few val vectors   D = k - 2 popcount(a ^ b)                  (XOR + V_BCNT)
-//   2-bit, few val vectors   D = popcount(nz_a & nz_b) - 2 popcount(nz_a & nz_b & (sg_a ^ sg_b))
+//   8-/4-bit: int8 x int8 -> int32 MFMA (v_mfma_i32_32x32x32_i8) on codes unpacked in registers
+//   2-/1-bit, more than 8 val vectors: the codes {-1, 0, +1} are exactly representable as FP4 (E2M1)
+//           values; v_mfma_scale_f32_32x32x64_f8f6f4 multiplies 64 of them per lane pair and sums in
+//           fp32, which is exact for these integers (|D| <= k <= 65536 < 2^24)   (see score_mfma_kernel)
+//   1-bit, at most 8 val vectors   D = k - 2 popcount(a ^ b)                  (XOR + V_BCNT)
+//   2-bit, at most 8 val vectors   D = popcount(nz_a & nz_b) - 2 popcount(nz_a & nz_b & (sg_a ^ sg_b))
 // The fp32 epilogue is a fixed sequence of single operations (compiled without contraction):
 //   acc += ((float)D * rnorm_train) * (eta * rnorm_val), checkpoints in order, starting from +0.
 //
@@ -384,19 +386,22 @@ score_stream_kernel(ScoreArgs a, int64_t total_rb, int64_t rb_per_wave, int nb, 
 }
 
 // ------------------------------------------------------------------------------------------
-// int8 MFMA kernel for all four code widths.
+// Matrix-core kernel for all four code widths.
 //
-// A small pre-pass expands the validation codes of every checkpoint to int8 rows (padded to the
-// tile size, in the K order in which the train operand is unpacked) together with
-// w'[c][z'] = eta_c * rnorm'_c(z') and, for 1-bit, vsum = sum of the +-1 codes of the row.
-// The main kernel runs one workgroup of 8 waves per (256 train rows) x (32 / 64 / 128 val rows)
-// tile with accumulators of v_mfma_i32_32x32x32_i8.  Train operands are unpacked in registers on
-// their way from LDS to the MFMA:
-//   8-bit  bytes as stored
+// A small pre-pass expands the validation codes of every checkpoint to int8 rows (8-/4-bit) or
+// FP4 rows (2-/1-bit), padded to the tile size and in the K order in which the train operand is
+// unpacked, together with w'[c][z'] = eta_c * rnorm'_c(z').  The main kernel runs one workgroup
+// per (256 or 128 train rows) x (32 / 64 / 128 val rows) tile.  Train operands are unpacked in
+// registers on their way from LDS to the MFMA:
+//   8-bit  bytes as stored                                              v_mfma_i32_32x32x32_i8
 //   4-bit  (w<<4)&0xF0F0F0F0 and w&0xF0F0F0F0: bytes 16 q (even / odd elements); acc = 16 D
-//   2-bit  nz = (w_nz>>j)&0x01010101, sg likewise: bytes nz | sg*0xFE in {0, 1, 0xFF}
-//   1-bit  (w>>j)&0x01010101, j = 0..7: bytes a in {0,1} (1 = negative); D = vsum - 2 sum a v
-// Operand stages travel global -> LDS asynchronously through a ring of 3-4 swizzled buffers.
+//   1-bit  a lane's 32 signs w become four dwords of FP4 codes,         v_mfma_scale_f32_32x32x64_f8f6f4
+//          dword j = ((w << j) & 0x88888888) | 0x22222222: 0x2 = +1.0, 0xA = -1.0 (nibble n <- bit 4n+3-j)
+//   2-bit  likewise from the two planes: ((sg << j) & 0x88888888) | ((nz shifted by j-2) & 0x22222222):
+//          0xA = -1.0, 0x0 = 0, 0x2 = +1.0
+// (for 1-bit codes and at most 64 validation vectors the packed validation rows are staged as they are
+// and expanded in registers as well).
+// Operand stages travel global -> LDS asynchronously through a ring of 2-4 swizzled buffers.
 // Workgroups of the same train tile get ids 8 apart, so they run on one XCD and share the train
 // rows through its L2; the row maximum over val tiles is combined with an order-preserving
 // integer atomicMax (exact, order independent) and decoded by a last small kernel.
@@ -416,7 +421,6 @@ constexpr int log2c(int x) { return x <= 1 ? 0 : 1 + log2c(x / 2); }
 struct ScorePrep {                             // workspace views (device pointers)
     int8_t *vexp;                              // [C][Mp][kp]
     float *vw;                                 // [C][Mp]
-    int *vsum;                                 // [C][Mp]
     unsigned int *smax;                        // [N] order-preserving keys of the row maxima
     int32_t Mp, kp;                            // padded validation rows / elements per row
     int32_t vrow;                              // bytes per expanded validation row: kp, or kp / 2 for 1-bit (FP4 codes)
@@ -452,7 +456,6 @@ score_prepare_kernel(ScoreArgs a, ScorePrep w) {
     int8_t *dst = w.vexp + ((size_t)ci * w.Mp + row) * (size_t)w.vrow;
     const bool live = row < a.M;
     const unsigned char *src = a.vc[ci] + (int64_t)(live ? row : 0) * ((int64_t)a.k * BITS / 8);
-    int part = 0;
     if (BITS <= 2) {
         // two FP4 codes per byte: 0x2 = +1.0, 0xA = -1.0, 0x0 = 0 (2-bit zeros, and past the end of the
         // vector).  1-bit with few validation vectors (vrow == 0): the main kernel stages the packed codes itself.
@@ -475,30 +478,19 @@ score_prepare_kernel(ScoreArgs a, ScorePrep w) {
             }
             dst[bi] = (int8_t)byte;
         }
-    } else
-    for (int p = threadIdx.x; p < w.kp; p += 256) {
-        int q = 0;
-        if (live && p < a.k) {
-            const int m = val_source_element<BITS>(p);
-            if (BITS == 8) q = (int8_t)src[m];
-            else if (BITS == 4) { q = (src[m >> 1] >> (4 * (m & 1))) & 0xF; if (q & 8) q -= 16; }
-            else if (BITS == 2) {
-                const int nz = (src[m >> 3] >> (m & 7)) & 1, sg = (src[a.k / 8 + (m >> 3)] >> (m & 7)) & 1;
-                q = nz ? (sg ? -1 : 1) : 0;
-            } else q = ((src[m >> 3] >> (m & 7)) & 1) ? -1 : 1;
+    } else {
+        for (int p = threadIdx.x; p < w.kp; p += 256) {
+            int q = 0;
+            if (live && p < a.k) {
+                const int m = val_source_element<BITS>(p);
+                if (BITS == 8) q = (int8_t)src[m];
+                else { q = (src[m >> 1] >> (4 * (m & 1))) & 0xF; if (q & 8) q -= 16; }
+            }
+            dst[p] = (int8_t)q;
         }
-        dst[p] = (int8_t)q;
-        part += q;
     }
-    __shared__ int s_part[4];
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
-    if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = part;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        w.vsum[ci * w.Mp + row] = s_part[0] + s_part[1] + s_part[2] + s_part[3];
+    if (threadIdx.x == 0)
         w.vw[ci * w.Mp + row] = live ? (F16 ? a.eta[ci] : __fmul_rn(a.eta[ci], a.vr[ci][row])) : 0.0f;
-    }
     // the row-maximum keys start below every finite score
     if (ci == 0) {
         const int64_t per = (a.N + gridDim.x - 1) / gridDim.x;
@@ -879,7 +871,7 @@ static int compute_units() {
     return cus;
 }
 
-struct MfmaPlan { int32_t vt, Mp, kp; size_t off_vw, off_vsum, off_smax, total; };
+struct MfmaPlan { int32_t vt, Mp, kp; size_t off_vw, off_smax, total; };
 static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int bits, int C) {
     MfmaPlan p{};
     p.vt = M > 64 ? 128 : (M > 32 ? 64 : 32);
@@ -889,7 +881,6 @@ static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int bits, int C) {
     size_t o = (size_t)C * p.Mp * (size_t)p.kp;
     o = (o + 255) & ~(size_t)255;
     p.off_vw = o;   o += (size_t)C * p.Mp * 4;
-    p.off_vsum = o; o += (size_t)C * p.Mp * 4;
     o = (o + 255) & ~(size_t)255;
     p.off_smax = o; o += (size_t)(N > 0 ? N : 1) * 4;
     p.total = o;
@@ -956,7 +947,7 @@ static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st) {
     const MfmaPlan p = mfma_plan(a.N, a.M, a.k, BITS, a.C);
     ScorePrep w{};
     unsigned char *base = (unsigned char *)ws;
-    w.vexp = (int8_t *)base; w.vw = (float *)(base + p.off_vw); w.vsum = (int *)(base + p.off_vsum);
+    w.vexp = (int8_t *)base; w.vw = (float *)(base + p.off_vw);
     w.smax = (unsigned int *)(base + p.off_smax); w.Mp = p.Mp; w.kp = p.kp;
     w.vrow = BITS == 1 ? (p.vt > 64 ? p.kp / 2 : 0) : (BITS == 2 ? p.kp / 2 : p.kp);
     hipLaunchKernelGGL((score_prepare_kernel<BITS, F16>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
