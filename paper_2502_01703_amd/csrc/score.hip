@@ -4,11 +4,14 @@
 //
 // Integer dot products are exact; how they are formed depends on the code width:
 //   8-/4-bit: int8 x int8 -> int32 MFMA (v_mfma_i32_32x32x32_i8) on codes unpacked in registers
-//   2-/1-bit, more than 8 val vectors: the codes {-1, 0, +1} are exactly representable as FP4 (E2M1)
-//           values; v_mfma_scale_f32_32x32x64_f8f6f4 multiplies 64 of them per lane pair and sums in
-//           fp32, which is exact for these integers (|D| <= k <= 65536 < 2^24)   (see score_mfma_kernel)
-//   1-bit, at most 8 val vectors   D = k - 2 popcount(a ^ b)                  (XOR + V_BCNT)
-//   2-bit, at most 8 val vectors   D = popcount(nz_a & nz_b) - 2 popcount(nz_a & nz_b & (sg_a ^ sg_b))
+//   2-/1-bit: the codes {-1, 0, +1} are exactly representable as FP4 (E2M1) values; the scaled FP4
+//           matrix-core instructions multiply them and sum in fp32, which is exact for these integers
+//           (|D| <= k <= 65536 < 2^24): v_mfma_scale_f32_32x32x64_f8f6f4 in score_mfma_kernel, and for at
+//           most 16 val vectors v_mfma_scale_f32_16x16x128_f8f6f4 in score_stream_mfma_kernel, which
+//           streams the train codes once at the speed of HBM
+//   2-/1-bit with k not a multiple of 128 (or val codes too large for LDS): popcounts,
+//           1-bit D = k - 2 popcount(a ^ b),
+//           2-bit D = popcount(nz_a & nz_b) - 2 popcount(nz_a & nz_b & (sg_a ^ sg_b))
 // The fp32 epilogue is a fixed sequence of single operations (compiled without contraction):
 //   acc += ((float)D * rnorm_train) * (eta * rnorm_val), checkpoints in order, starting from +0.
 //
@@ -202,188 +205,7 @@ score_popcount_kernel(ScoreArgs a) {
     }
 }
 
-// ------------------------------------------------------------------------------------------
-// 1-bit / 2-bit codes against at most 8 validation vectors: streaming kernel, bound by HBM.
-//
-// No barrier after the start: every wavefront owns a contiguous range of 8-row blocks and streams
-// them through a private LDS ring with asynchronous 16-byte copies (one copy instruction = 8 rows x
-// 128 bytes, whole cache lines; lane = row rr = lane / 8, 16-byte chunk g = lane % 8 of the
-// 128-byte slice), nb - 1 slices ahead of their use.  Every lane reads back exactly the 16 bytes it
-// requested.  The validation codes and weights of all checkpoints sit in LDS for the whole kernel.
-// Popcounts accumulate per lane over the whole row; the 8 lanes of a row are summed once per
-// checkpoint with three DPP steps.  Ranges are split in units of 8 rows, so all wavefronts finish
-// within one row block of each other (no tail of half-empty rounds).
-// Lanes whose chunk lies past the end of a plane copy its last 16 bytes and skip the arithmetic.
-// ------------------------------------------------------------------------------------------
-constexpr int kStreamVal = 8;                  // validation vectors the streaming kernel handles
-
-__device__ inline int sum_over_8_lanes(int v) {
-    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
-    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
-    v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true);   // row_half_mirror: the other quad
-    return v;
-}
-struct StreamCtx {                              // per-wavefront constants of the streaming kernel
-    const unsigned char *vlds;                  // [C][MV][cb] validation codes
-    const float *wlds;                          // [C][MV] eta * rnorm'
-    unsigned char *ring;                        // this wavefront's ring (generic pointer) ...
-    unsigned ring_lds;                          // ... and its LDS address
-    int nb, cb, plane, nsl, T, lane, g, rr;
-};
-
-// One panel of PB row blocks starting at block rbp: all checkpoints, all slices, outputs.
-template <int BITS, int MV, int PB>
-__device__ inline void stream_panel(const ScoreArgs &a, const StreamCtx &c, int64_t rbp) {
-    constexpr int NPL = BITS;                   // bit planes per row
-    constexpr int L = PB * NPL;                 // 1 KB copies per slice
-    const int64_t prow0 = rbp * 8;              // first row of the panel (wave-uniform)
-    int64_t row[PB];
-    unsigned rel[PB];                           // byte offset of the lane's row from the panel's first
-#pragma unroll
-    for (int p = 0; p < PB; ++p) {
-        const int64_t r = (rbp + p) * 8 + c.rr;
-        row[p] = r < a.N ? r : a.N - 1;         // clamped; masked at the output
-        rel[p] = (unsigned)(row[p] - prow0) * (unsigned)c.cb;
-    }
-    float facc[PB][MV];
-    int accP[PB][MV], accN[BITS == 2 ? PB : 1][MV];
-#pragma unroll
-    for (int p = 0; p < PB; ++p)
-#pragma unroll
-        for (int j = 0; j < MV; ++j) { facc[p][j] = 0.0f; accP[p][j] = 0; if (BITS == 2) accN[p][j] = 0; }
-
-    // slice `it` of the panel: checkpoint it / nsl, slice it % nsl, ring slot it % nb
-    auto fetch = [&](int it) {
-        const int ci = it / c.nsl, sl = it - ci * c.nsl;
-        int off = sl * 128 + c.g * 16;
-        if (off >= c.plane) off = c.plane - 16;                  // such lanes skip the arithmetic
-        const unsigned char *base = a.tc[ci] + prow0 * c.cb;     // wave-uniform
-        const unsigned slot = c.ring_lds + (unsigned)(it % c.nb) * (4 * 1024);
-#pragma unroll
-        for (int p = 0; p < PB; ++p)
-#pragma unroll
-            for (int q = 0; q < NPL; ++q)
-                global_to_lds16(base, rel[p] + (unsigned)(q * c.plane + off), slot + (unsigned)(p * NPL + q) * 1024u);
-    };
-    for (int it = 0; it < c.nb - 1 && it < c.T; ++it) fetch(it);
-    for (int it = 0; it < c.T; ++it) {
-        // copies issued after this slice's: nb - 2 more slices, fewer at the end of the panel
-        const int younger = c.T - 1 - it < c.nb - 2 ? c.T - 1 - it : c.nb - 2;
-        if (younger >= 1) wait_vmcnt<L>(); else wait_vmcnt<0>();
-        // the slot of slice it - 1 is free: this wave's reads of it were consumed in the last step
-        if (it + c.nb - 1 < c.T) fetch(it + c.nb - 1);
-        const int ci = it / c.nsl, sl = it - ci * c.nsl;
-        const int off = sl * 128 + c.g * 16;
-        if (off < c.plane) {
-            const unsigned char *src = c.ring + (size_t)(it % c.nb) * (4 * 1024) + c.lane * 16;
-            uint4 cur[L];
-#pragma unroll
-            for (int u = 0; u < L; ++u) cur[u] = *(const uint4 *)(src + u * 1024);
-            const unsigned char *vrow = c.vlds + (size_t)ci * MV * c.cb + off;
-            uint4 bv[MV];                                        // all validation chunks requested up front
-#pragma unroll
-            for (int j = 0; j < MV; ++j) bv[j] = *(const uint4 *)(vrow + j * c.cb);
-#pragma unroll
-            for (int j = 0; j < MV; ++j) {
-                const uint4 b = bv[j];
-                if (BITS == 1) {
-#pragma unroll
-                    for (int p = 0; p < PB; ++p)
-                        accP[p][j] += __popc(cur[p].x ^ b.x) + __popc(cur[p].y ^ b.y) +
-                                      __popc(cur[p].z ^ b.z) + __popc(cur[p].w ^ b.w);
-                } else {
-                    const uint4 d = *(const uint4 *)(vrow + j * c.cb + c.plane);
-#pragma unroll
-                    for (int p = 0; p < PB; ++p) {
-                        const uint4 tn = cur[p * NPL], tg = cur[p * NPL + NPL - 1];
-                        uint32_t t;
-                        t = tn.x & b.x; accP[p][j] += __popc(t); accN[p][j] += __popc(t & (tg.x ^ d.x));
-                        t = tn.y & b.y; accP[p][j] += __popc(t); accN[p][j] += __popc(t & (tg.y ^ d.y));
-                        t = tn.z & b.z; accP[p][j] += __popc(t); accN[p][j] += __popc(t & (tg.z ^ d.z));
-                        t = tn.w & b.w; accP[p][j] += __popc(t); accN[p][j] += __popc(t & (tg.w ^ d.w));
-                    }
-                }
-            }
-        }
-        if (sl == c.nsl - 1) {
-            // checkpoint epilogue: every lane of a row ends up with the row's dot products
-#pragma unroll
-            for (int p = 0; p < PB; ++p) {
-                const float rt = a.tr[ci][row[p]];
-#pragma unroll
-                for (int j = 0; j < MV; ++j) {
-                    const float wv = c.wlds[ci * MV + j];
-                    const int P = sum_over_8_lanes(accP[p][j]);
-                    const int D = BITS == 1 ? a.k - 2 * P : P - 2 * sum_over_8_lanes(accN[BITS == 2 ? p : 0][j]);
-                    const float t = __fmul_rn(__fmul_rn((float)D, rt), wv);
-                    facc[p][j] = __fadd_rn(facc[p][j], t);
-                    accP[p][j] = 0;
-                    if (BITS == 2) accN[p][j] = 0;
-                }
-            }
-        }
-    }
-    // outputs: lane g of a row writes column g of the full matrix, lane 0 the row maximum
-#pragma unroll
-    for (int p = 0; p < PB; ++p) {
-        const int64_t r = (rbp + p) * 8 + c.rr;
-        if (r >= a.N) continue;
-        float m = neg_inf(), mine = 0.0f;
-#pragma unroll
-        for (int j = 0; j < MV; ++j) {
-            if (j < a.M) m = fmaxf(m, facc[p][j]);
-            if (j == c.g) mine = facc[p][j];
-        }
-        if (a.full && c.g < a.M) a.full[r * a.M + c.g] = mine;
-        if (a.score && c.g == 0) a.score[r] = m;
-    }
-}
-
-template <int BITS, int MV>                   // MV = 4 or 8 validation columns computed (M <= MV)
-__global__ void __launch_bounds__(512, 2)
-score_stream_kernel(ScoreArgs a, int64_t total_rb, int64_t rb_per_wave, int nb, unsigned ring_off) {
-    constexpr int PB = 4 / BITS;                // row blocks of a full panel (4 KB per slice)
-    // LDS: [C][MV][cb] validation codes | [C][MV] weights | per wave a ring of nb slices x 4 KB
-    extern __shared__ __attribute__((aligned(16))) unsigned char vlds[];
-    StreamCtx c;
-    c.lane = threadIdx.x & 63;
-    c.g = c.lane & 7; c.rr = c.lane >> 3;
-    const int wv_id = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t wave = (int64_t)blockIdx.x * 8 + wv_id;
-    const int64_t rb0 = wave * rb_per_wave;
-    int64_t rb1 = rb0 + rb_per_wave;
-    if (rb1 > total_rb) rb1 = total_rb;
-    c.nb = nb;
-    c.cb = a.k * BITS / 8;                      // bytes per row
-    c.plane = a.k / 8;                          // bytes per bit plane, a multiple of 16 here
-    c.nsl = (c.plane + 127) / 128;              // 128-byte slices per plane
-    c.T = a.C * c.nsl;                          // slices of a panel over all checkpoints
-    c.vlds = vlds;
-    c.wlds = (const float *)(vlds + (size_t)a.C * MV * c.cb);
-    c.ring = vlds + ring_off + (size_t)wv_id * nb * 4096;
-    c.ring_lds = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)c.ring);
-
-    // validation codes and weights eta * rnorm' of every checkpoint -> LDS (rows past M repeat the
-    // last one; they are masked at the output)
-    {
-        const int per_row = c.cb / 16, total = a.C * MV * per_row;
-        for (int i = threadIdx.x; i < total; i += 512) {
-            const int c16 = i % per_row, j = (i / per_row) % MV, ci = i / (per_row * MV);
-            const int jc = j < a.M ? j : a.M - 1;
-            *(uint4 *)(vlds + (size_t)i * 16) = *(const uint4 *)(a.vc[ci] + (int64_t)jc * c.cb + c16 * 16);
-        }
-        float *wdst = (float *)(vlds + (size_t)a.C * MV * c.cb);
-        for (int i = threadIdx.x; i < a.C * MV; i += 512) {
-            const int j = i % MV, ci = i / MV;
-            wdst[i] = __fmul_rn(a.eta[ci], a.vr[ci][j < a.M ? j : a.M - 1]);
-        }
-        __syncthreads();
-    }
-    // full panels, then the remaining row blocks one at a time (wave-uniform loops)
-    int64_t rbp = rb0;
-    for (; rbp + PB <= rb1; rbp += PB) stream_panel<BITS, MV, PB>(a, c, rbp);
-    for (; rbp < rb1; ++rbp) stream_panel<BITS, MV, 1>(a, c, rbp);
-}
+constexpr int kStreamVal = 8;                  // bit-plane codes against at most this many val vectors never take the tile kernel (no workspace)
 
 // ------------------------------------------------------------------------------------------
 // Matrix-core kernel for all four code widths.
@@ -516,6 +338,18 @@ __device__ inline i32x16 mfma_step<false>(i32x4 a, i32x4 b, i32x16 c) {
     return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
 }
 typedef __attribute__((ext_vector_type(8))) int i32x8;
+// (x & 0x88888888) | y in one instruction.  The fused and-or takes a single literal, so callers
+// keep a constant y (0x22222222: eight FP4 codes of +1.0) in a vector register.
+__device__ inline uint32_t sign_bits_or(uint32_t x, uint32_t y) {
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "s"(0x88888888u), "v"(y));
+    return r;
+}
+__device__ inline uint32_t fp4_ones() {
+    uint32_t one = 0x22222222u;
+    asm volatile("" : "+v"(one));                // held in a vector register
+    return one;
+}
 // 64 FP4 (E2M1) products per lane pair, both scales 2^0: the sign codes' dot products, exact in fp32
 __device__ inline f32x16 mfma_fp4(i32x8 a, i32x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 4, 4, 0, 127, 0, 127);
@@ -523,6 +357,247 @@ __device__ inline f32x16 mfma_fp4(i32x8 a, i32x8 b, f32x16 c) {
 template <>
 __device__ inline f32x16 mfma_step<true>(i32x4 a, i32x4 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// ------------------------------------------------------------------------------------------
+// 1-bit / 2-bit codes against at most 16 validation vectors on the matrix cores: streaming kernel,
+// bound by HBM.
+//
+// No barrier after the start: every wavefront streams its own contiguous row range through a
+// private LDS ring of 4 KB slots filled by asynchronous 16-byte copies; the validation codes and
+// weights of all checkpoints stay in LDS for the whole kernel.  The dot products are formed by
+// v_mfma_scale_f32_16x16x128_f8f6f4 on FP4 operands expanded in registers (7 vector ALU operations
+// per 32 one-bit codes of a train row, whatever the number of validation vectors; popcounts would
+// need 2 per validation vector):
+//   * a wavefront takes passes of up to 160 rows = 10 panels of 16 rows.  For every (checkpoint,
+//     128-byte slice) it expands the validation fragments of that slice once (A operand: val row
+//     lane % 16; lane group lane / 16 takes 16-byte chunks 4 c + lane / 16, c = 0, 1, of the slice)
+//     and multiplies them with all panels of the pass (B operand: train row lane % 16, same chunks),
+//     8 instructions per panel and slice.  Both operands use the same chunk -> K position map, so
+//     the order of the K elements inside an instruction does not matter.
+//   * a ring slot holds one slice of 32 / BITS rows (PPS = 2 / BITS panels): 1 KB copies of 8 rows
+//     x 128 bytes (whole cache lines).  Copy lane (row rr = lane / 8, position lane % 8) fetches
+//     chunk (lane % 8) ^ rr, so the 8 rows of a copy that are read together come from 8 different
+//     bank groups.  The ring has as many slots as LDS allows, normally 3.
+//   * accumulator register v of lane (row lane % 16, group lane / 16) belongs to validation vector
+//     4 (lane / 16) + v; after the last slice of a checkpoint it goes through the fp32 epilogue.
+// Chunks past the end of a plane (k / 8 not a multiple of 128 bytes) are zeroed on the validation
+// side (FP4 code 0), so whatever the train copy fetched there contributes nothing.
+// ------------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+constexpr int kStreamMfmaVal = 16;             // validation vectors the kernel handles
+constexpr int kStreamPassRows = 160;           // train rows of one pass of a wavefront
+
+// 32 codes (bit c of `sg`: negative; bit c of `nz`: non-zero, 2-bit codes only) -> four dwords of FP4
+// codes; nibble n of dword j holds code 4 n + 3 - j (0x2 = +1.0, 0xA = -1.0, 0x0 = 0); ones = fp4_ones()
+template <int BITS>
+__device__ inline i32x8 fp4_codes(uint32_t sg, uint32_t nz, uint32_t ones) {
+    i32x8 r = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t mag = BITS == 1 ? ones : ((j >= 2 ? nz << (j - 2) : nz >> (2 - j)) & 0x22222222u);
+        r[j] = (int)sign_bits_or(sg << j, mag);
+    }
+    return r;
+}
+
+// blocks until at most n (wave-uniform, even, <= 14) vector memory operations are outstanding
+__device__ inline void wait_vmcnt_even(int n) {
+    switch (n) {
+    case 0: wait_vmcnt<0>(); break;
+    case 2: wait_vmcnt<2>(); break;
+    case 4: wait_vmcnt<4>(); break;
+    case 6: wait_vmcnt<6>(); break;
+    case 8: wait_vmcnt<8>(); break;
+    case 10: wait_vmcnt<10>(); break;
+    case 12: wait_vmcnt<12>(); break;
+    case 14: wait_vmcnt<14>(); break;
+    default: wait_vmcnt<0>(); break;
+    }
+}
+
+// MV = 8 or 16 validation rows held in LDS (M <= MV); NW wavefronts per workgroup, one workgroup per compute unit
+template <int BITS, int MV, int NW, int PPS>
+__global__ void __launch_bounds__(64 * NW, NW / 4)
+score_stream_mfma_kernel(ScoreArgs a, int64_t rb_each, int64_t rb_extra, int nb, unsigned ring_off) {
+    constexpr int NPL = BITS;                   // bit planes per row
+    constexpr int L = 2 * NPL * PPS;            // 1 KB copies per ring slot (PPS panels, one slice)
+    constexpr int SLOT = L * 1024;
+    constexpr int PASS = kStreamPassRows * 8 / NW;   // rows of a pass: fewer with more wavefronts (registers)
+    constexpr int NP = PASS / 16;               // panels per pass
+    static_assert(NP % PPS == 0, "whole ring slots per pass");
+    // LDS: [C][MV] validation rows of cb + 16 bytes | [C][MV] weights | per wave a ring of nb slots
+    extern __shared__ __attribute__((aligned(16))) unsigned char vlds[];
+    const int lane = threadIdx.x & 63;
+    const int cg = lane & 7, crr = lane >> 3;  // copy role: position and row inside a 1 KB copy
+    const int l16 = lane & 15, kg = lane >> 4; // matrix role: row of the panel and chunk group
+    const int wv_id = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // 8-row blocks are dealt out evenly: wavefront w takes rb_each blocks, the first rb_extra
+    // wavefronts one more; w counts across workgroups first, so every compute unit gets its share
+    // of the longer ranges
+    const int64_t wave = (int64_t)wv_id * gridDim.x + blockIdx.x;
+    const int64_t rb0 = wave * rb_each + (wave < rb_extra ? wave : rb_extra);
+    const int64_t rb1 = rb0 + rb_each + (wave < rb_extra ? 1 : 0);
+    const int cb = a.k * BITS / 8;              // bytes per row
+    const int plane = a.k / 8;                  // bytes per bit plane, a multiple of 16 here
+    const int nsl = (plane + 127) / 128;        // 128-byte slices per plane
+    const int vstride = cb + 16;                // rows 4 banks apart: 8 rows read together do not collide
+    const float *wlds = (const float *)(vlds + (size_t)a.C * MV * vstride);
+    unsigned char *ring = vlds + ring_off + (size_t)wv_id * nb * SLOT;
+    const unsigned ring_lds = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)ring);
+
+    // validation codes and weights eta * rnorm' of every checkpoint -> LDS (rows past M repeat the
+    // last one; they are masked at the output)
+    {
+        const int per_row = cb / 16, total = a.C * MV * per_row;
+        for (int i = threadIdx.x; i < total; i += 64 * NW) {
+            const int c16 = i % per_row, rowi = i / per_row, j = rowi % MV, ci = rowi / MV;
+            const int jc = j < a.M ? j : a.M - 1;
+            *(uint4 *)(vlds + (size_t)rowi * vstride + c16 * 16) = *(const uint4 *)(a.vc[ci] + (int64_t)jc * cb + c16 * 16);
+        }
+        float *wdst = (float *)(vlds + (size_t)a.C * MV * vstride);
+        for (int i = threadIdx.x; i < a.C * MV; i += 64 * NW) {
+            const int j = i % MV, ci = i / MV;
+            wdst[i] = __fmul_rn(a.eta[ci], a.vr[ci][j < a.M ? j : a.M - 1]);
+        }
+        __syncthreads();
+    }
+    int64_t r_end = rb1 * 8;
+    if (r_end > a.N) r_end = a.N;                // only the last block of all can be partial
+    const uint32_t ones = fp4_ones();
+
+    for (int64_t rp = rb0 * 8; rp < r_end; rp += PASS) {          // wave-uniform loops
+        const int rows = r_end - rp < PASS ? (int)(r_end - rp) : PASS;
+        const int np = (rows + 15) / 16;
+        const int ns = (np + PPS - 1) / PPS;     // ring slots per slice
+        const int T = a.C * nsl * ns;            // ring slots the pass consumes
+        const int last = rows - 1;
+        // producer state: the next slot to request is (f_ci, f_sl, f_p) into ring position f_pos
+        int f_ci = 0, f_sl = 0, f_p = 0, f_pos = 0, f_it = 0;
+        auto fetch = [&]() {
+            int off = f_sl * 128 + ((cg ^ crr) << 4);
+            if (off >= plane) off = plane - 16;                              // zeroed on the validation side
+            const unsigned char *base = a.tc[f_ci] + rp * cb;               // wave-uniform
+            const unsigned slot = ring_lds + (unsigned)f_pos * (unsigned)SLOT;
+#pragma unroll
+            for (int b = 0; b < 2 * PPS; ++b) {
+                int rl = f_p * (16 * PPS) + b * 8 + crr;
+                if (rl > last) rl = last;                                    // clamped; masked at the output
+#pragma unroll
+                for (int q = 0; q < NPL; ++q)
+                    global_to_lds16(base, (unsigned)(rl * cb + q * plane + off), slot + (unsigned)(b * NPL + q) * 1024u);
+            }
+            ++f_it;
+            if (++f_pos == nb) f_pos = 0;
+            if (++f_p == ns) { f_p = 0; if (++f_sl == nsl) { f_sl = 0; ++f_ci; } }
+        };
+        f32x4 acc[NP];
+        float facc[NP][4];
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) { acc[p][v] = 0.0f; facc[p][v] = 0.0f; }
+
+        for (int i = 0; i < nb - 1 && i < T; ++i) fetch();
+        int it = 0, pos = 0;
+        for (int ci = 0; ci < a.C; ++ci) {
+            for (int sl = 0; sl < nsl; ++sl) {
+                // validation fragments of this slice: 8 K steps (2 chunks x 4 dwords) of 4 FP4 dwords
+                i32x8 vf[8];
+                {
+                    const unsigned char *vrow = vlds + (size_t)(ci * MV + (l16 & (MV - 1))) * vstride;
+#pragma unroll
+                    for (int c2 = 0; c2 < 2; ++c2) {
+                        const int off = sl * 128 + (4 * c2 + kg) * 16;
+                        const bool inside = off < plane;
+                        const int offc = inside ? off : 0;
+                        const uint4 sg = *(const uint4 *)(vrow + (NPL - 1) * plane + offc);
+                        const uint4 nz = BITS == 2 ? *(const uint4 *)(vrow + offc) : sg;
+                        vf[4 * c2 + 0] = fp4_codes<BITS>(sg.x, nz.x, ones);
+                        vf[4 * c2 + 1] = fp4_codes<BITS>(sg.y, nz.y, ones);
+                        vf[4 * c2 + 2] = fp4_codes<BITS>(sg.z, nz.z, ones);
+                        vf[4 * c2 + 3] = fp4_codes<BITS>(sg.w, nz.w, ones);
+                        if (sl * 128 + 128 > plane) {                        // wave-uniform: last, partial slice
+                            const int keep = inside ? -1 : 0;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) vf[4 * c2 + e][j] &= keep;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int g = 0; g < NP / PPS; ++g) {
+                    if (g < ns) {
+                        // copies issued after this slot's: nb - 2 more slots, fewer at the end of the pass
+                        const int younger = T - 1 - it < nb - 2 ? T - 1 - it : nb - 2;
+                        wait_vmcnt_even(L * younger);
+                        // the slot of step it - 1 is free: this wave's reads of it were consumed there
+                        if (f_it < T) fetch();
+                        const int rr = l16 & 7;
+                        const unsigned char *rowp = ring + (size_t)pos * SLOT + (size_t)((l16 >> 3) * NPL) * 1024 + rr * 128;
+                        uint4 sgv[PPS][2], nzv[PPS][2];
+#pragma unroll
+                        for (int h = 0; h < PPS; ++h)
+#pragma unroll
+                            for (int c2 = 0; c2 < 2; ++c2) {
+                                const int chunk = ((4 * c2 + kg) ^ rr) << 4;
+                                sgv[h][c2] = *(const uint4 *)(rowp + (2 * h * NPL + NPL - 1) * 1024 + chunk);
+                                nzv[h][c2] = BITS == 2 ? *(const uint4 *)(rowp + 2 * h * NPL * 1024 + chunk) : sgv[h][c2];
+                            }
+#pragma unroll
+                        for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                                for (int h = 0; h < PPS; ++h) {
+                                    const uint4 sg = sgv[h][c2], nz = nzv[h][c2];
+                                    const uint32_t sw = e == 0 ? sg.x : e == 1 ? sg.y : e == 2 ? sg.z : sg.w;
+                                    const uint32_t nw = e == 0 ? nz.x : e == 1 ? nz.y : e == 2 ? nz.z : nz.w;
+                                    acc[g * PPS + h] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                                        vf[4 * c2 + e], fp4_codes<BITS>(sw, nw, ones), acc[g * PPS + h], 4, 4, 0, 127, 0, 127);
+                                }
+                        ++it;
+                        if (++pos == nb) pos = 0;
+                    }
+                }
+            }
+            // checkpoint epilogue
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                if (p < np) {
+                    const float rt = a.tr[ci][rp + (p * 16 + l16 < rows ? p * 16 + l16 : last)];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float wv = wlds[ci * MV + ((4 * kg + v) & (MV - 1))];
+                        const float t = __fmul_rn(__fmul_rn(acc[p][v], rt), wv);      // acc holds the integer D exactly
+                        facc[p][v] = __fadd_rn(facc[p][v], t);
+                        acc[p][v] = 0.0f;
+                    }
+                }
+            }
+        }
+        // outputs: lane (row, group kg) holds validation vectors 4 kg .. 4 kg + 3
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            if (p < np) {
+                const bool live = p * 16 + l16 < rows;
+                const int64_t r = rp + p * 16 + l16;
+                float m = neg_inf();
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int j = 4 * kg + v;
+                    if (j < a.M) {
+                        m = fmaxf(m, facc[p][v]);
+                        if (a.full && live) a.full[r * a.M + j] = facc[p][v];
+                    }
+                }
+                m = fmaxf(m, __shfl_xor(m, 16));
+                m = fmaxf(m, __shfl_xor(m, 32));
+                if (a.score && live && kg == 0) a.score[r] = m;
+            }
+        }
+    }
 }
 
 // Shape of the NW waves of a workgroup: WX waves across the val tile, NW / WX down the train
@@ -697,6 +772,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
         if (g < total) issue(g);
 
     int g = 0;
+    const uint32_t ones = fp4_ones();
     for (int ci = 0; ci < a.C; ++ci) {
         typename AccType<F16 || BITS <= 2>::type acc[WR][WC];
 #pragma unroll
@@ -727,7 +803,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
                     for (int b = 0; b < WR; ++b) {
                         const unsigned int wd = *(const unsigned int *)(sb + (a_base[b] ^ ((ks >> 1) << 4)) + 8 * (ks & 1));
 #pragma unroll
-                        for (int jd = 0; jd < 4; ++jd) af[b][jd] = (int)(((wd << jd) & 0x88888888u) | 0x22222222u);
+                        for (int jd = 0; jd < 4; ++jd) af[b][jd] = (int)sign_bits_or(wd << jd, ones);
 #pragma unroll
                         for (int jd = 4; jd < 8; ++jd) af[b][jd] = 0;
                     }
@@ -736,7 +812,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
                         if (Sh::VPACKED) {
                             const unsigned int wd = *(const unsigned int *)(sb + (b_base[c] ^ ((ks >> 1) << 4)) + 8 * (ks & 1));
 #pragma unroll
-                            for (int jd = 0; jd < 4; ++jd) bf[c][jd] = (int)(((wd << jd) & 0x88888888u) | 0x22222222u);
+                            for (int jd = 0; jd < 4; ++jd) bf[c][jd] = (int)sign_bits_or(wd << jd, ones);
 #pragma unroll
                             for (int jd = 4; jd < 8; ++jd) bf[c][jd] = 0;
                         } else {
@@ -763,7 +839,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
 #pragma unroll
                         for (int jd = 0; jd < 4; ++jd) {
                             const unsigned int zs = jd >= 2 ? wn << (jd - 2) : wn >> (2 - jd);
-                            af[b][jd] = (int)(((wg << jd) & 0x88888888u) | (zs & 0x22222222u));
+                            af[b][jd] = (int)sign_bits_or(wg << jd, zs & 0x22222222u);
                         }
 #pragma unroll
                         for (int jd = 4; jd < 8; ++jd) af[b][jd] = 0;
@@ -971,6 +1047,46 @@ static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st) {
     return launch_status();
 }
 
+// LDS plan of score_stream_mfma_kernel: validation rows and weights, then 8 rings of nb slots
+// (nb = 0: does not fit)
+constexpr int kStreamWaves = 8;                                      // wavefronts per workgroup of the kernel
+struct StreamMfmaPlan { int mv, nb; size_t val_bytes, lds; };
+static StreamMfmaPlan stream_mfma_plan(int32_t M, int32_t k, int bits, int C) {
+    StreamMfmaPlan p{};
+    p.mv = M <= 8 ? 8 : 16;
+    p.val_bytes = (((size_t)C * p.mv * ((size_t)k * bits / 8 + 16 + 4)) + 1023) & ~(size_t)1023;
+    const size_t slot = 4096;                                        // 32 / bits rows of one 128-byte slice
+    const size_t room = 158 * 1024 > p.val_bytes ? (158 * 1024 - p.val_bytes) / (kStreamWaves * slot) : 0;
+    p.nb = room < 2 ? 0 : (room > 5 ? 5 : (int)room);                // waits: 4 copies per slot x (nb - 2) <= 14
+    p.lds = p.val_bytes + (size_t)kStreamWaves * p.nb * slot;
+    return p;
+}
+static qless_status launch_stream_mfma(const ScoreArgs &a, int bits, const StreamMfmaPlan &sp, hipStream_t st) {
+    constexpr int NW = kStreamWaves;
+    static bool allowed = false;                                     // LDS above 64 KB has to be allowed per kernel
+    if (!allowed) {
+        const void *fns[4] = {(const void *)score_stream_mfma_kernel<1, 8, NW, 2>, (const void *)score_stream_mfma_kernel<1, 16, NW, 2>,
+                              (const void *)score_stream_mfma_kernel<2, 8, NW, 1>, (const void *)score_stream_mfma_kernel<2, 16, NW, 1>};
+        for (const void *f : fns)
+            if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 158 * 1024) != hipSuccess)
+                return QLESS_ERR_DEVICE;
+        allowed = true;
+    }
+    // at most one workgroup per compute unit; the 8-row blocks are dealt out evenly over all wavefronts
+    const int64_t total_rb = (a.N + 7) / 8;
+    int64_t groups = compute_units();
+    if (groups * NW > total_rb) groups = (total_rb + NW - 1) / NW;
+    const int64_t waves = groups * NW;
+    const int64_t each = total_rb / waves, extra = total_rb % waves;
+    const dim3 grid((unsigned)groups), block(64 * NW);
+    const unsigned ro = (unsigned)sp.val_bytes;
+    if (bits == 1 && sp.mv == 8) hipLaunchKernelGGL((score_stream_mfma_kernel<1, 8, NW, 2>), grid, block, sp.lds, st, a, each, extra, sp.nb, ro);
+    else if (bits == 1) hipLaunchKernelGGL((score_stream_mfma_kernel<1, 16, NW, 2>), grid, block, sp.lds, st, a, each, extra, sp.nb, ro);
+    else if (sp.mv == 8) hipLaunchKernelGGL((score_stream_mfma_kernel<2, 8, NW, 1>), grid, block, sp.lds, st, a, each, extra, sp.nb, ro);
+    else hipLaunchKernelGGL((score_stream_mfma_kernel<2, 16, NW, 1>), grid, block, sp.lds, st, a, each, extra, sp.nb, ro);
+    return launch_status();
+}
+
 template <int BITS, int RT, int CT, int TY, int TX>
 static void launch_popcount(const ScoreArgs &a, hipStream_t st) {
     constexpr int TN = RT * TY, TM = CT * TX, SW = BITS * 16 + 4, RSTEP = 256 / (8 * BITS);
@@ -1009,6 +1125,10 @@ extern "C" qless_status qless_score(const void *const *train_codes, const float 
     a.C = C; a.N = N; a.M = M; a.k = k; a.score = score; a.full = full;
     if (N == 0) return QLESS_OK;
     hipStream_t st = (hipStream_t)stream;
+    if (bits <= 2 && M <= kStreamMfmaVal && k % 128 == 0) {
+        const StreamMfmaPlan sp = stream_mfma_plan(M, k, bits, C);
+        if (sp.nb >= 2) return launch_stream_mfma(a, bits, sp, st);
+    }
     if (use_mfma_path(bits, M, k)) {
         const size_t need = mfma_plan(N, M, k, bits, C).total;
         if (!ws || ws_bytes < need) return QLESS_ERR_WORKSPACE;
@@ -1019,38 +1139,8 @@ extern "C" qless_status qless_score(const void *const *train_codes, const float 
         if (bits == 2) return launch_mfma<2>(a, ws, st);
         return launch_mfma<1>(a, ws, st);
     }
-    // bit-plane codes against a handful of val vectors: the streaming kernel
-    // bit-plane codes against a handful of val vectors: the streaming kernel, if the validation
-    // codes of all checkpoints and a ring of at least two slices per wavefront fit in LDS
-    const int mv = M <= 4 ? 4 : kStreamVal;                         // validation columns the kernel computes
-    const size_t stream_val = (((size_t)C * mv * ((size_t)k * bits / 8 + 4)) + 1023) & ~(size_t)1023;
-    if (M <= kStreamVal && k % 128 == 0 && stream_val + 8 * 2 * 4096 <= 158 * 1024) {
-        const int nb = stream_val + 8 * 3 * 4096 <= 158 * 1024 ? 3 : 2;
-        const size_t lds = stream_val + (size_t)8 * nb * 4096;
-        static size_t allowed = 64 * 1024;                           // more has to be allowed per kernel
-        if (lds > allowed) {
-            const void *fns[4] = {(const void *)score_stream_kernel<1, 4>, (const void *)score_stream_kernel<1, 8>,
-                                  (const void *)score_stream_kernel<2, 4>, (const void *)score_stream_kernel<2, 8>};
-            for (const void *f : fns)
-                if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 158 * 1024) != hipSuccess)
-                    return QLESS_ERR_DEVICE;
-            allowed = 158 * 1024;
-        }
-        const int64_t total_rb = (N + 7) / 8;
-        const int per_cu = lds * 2 + 1024 <= kLdsPerCU ? 2 : 1;      // workgroups of 8 wavefronts per compute unit
-        int64_t waves = (int64_t)compute_units() * 8 * per_cu;
-        if (waves > total_rb) waves = total_rb;
-        const int64_t rb_per_wave = (total_rb + waves - 1) / waves;
-        const int64_t used = (total_rb + rb_per_wave - 1) / rb_per_wave;
-        const dim3 grid((unsigned)((used + 7) / 8)), block(512);
-        const unsigned ro = (unsigned)stream_val;
-        if (bits == 1 && mv == 4) hipLaunchKernelGGL((score_stream_kernel<1, 4>), grid, block, lds, st, a, total_rb, rb_per_wave, nb, ro);
-        else if (bits == 1) hipLaunchKernelGGL((score_stream_kernel<1, 8>), grid, block, lds, st, a, total_rb, rb_per_wave, nb, ro);
-        else if (mv == 4) hipLaunchKernelGGL((score_stream_kernel<2, 4>), grid, block, lds, st, a, total_rb, rb_per_wave, nb, ro);
-        else hipLaunchKernelGGL((score_stream_kernel<2, 8>), grid, block, lds, st, a, total_rb, rb_per_wave, nb, ro);
-        return launch_status();
-    }
-    // bit-plane codes with rows that are not multiples of 16 bytes, or few val vectors: popcount kernels
+    // bit-plane codes with rows that are not multiples of 16 bytes, or a handful of val vectors whose
+    // codes do not fit in LDS: popcount kernels
     if (bits == 1) {
         if (M > 32) launch_popcount<1, 8, 4, 16, 16>(a, st);
         else if (M > 8) launch_popcount<1, 8, 4, 32, 8>(a, st);

@@ -197,3 +197,23 @@ def test_config2_multi_bit_sweep_pipeline():
         hit = len(set(oi.tolist()) & set(range(n_pl)))
         if b != 2:      # absmax 2-bit codes keep ~5 % non-zero entries (Sec. 5): too noisy at k = 2048
             assert hit >= 0.95 * n_pl, (b, hit)
+
+
+@pytest.mark.parametrize("bits", [2, 1])
+def test_streaming_wavefronts_take_several_passes(bits):
+    """More train rows than one pass of every wavefront of the few-validation-vector bit-plane
+    kernel covers (Eq. (6), (7) on a large, short-vector datastore): whole output bit-exact."""
+    N, M, k, C = 400000, 11, 256, 2
+    _say("several passes per wavefront: score %d-bit N=%d M=%d k=%d C=%d" % (bits, N, M, k, C))
+    rng = np.random.default_rng(77 + bits)
+    t0 = oracle.quantize(rng.standard_normal((N, k), dtype=np.float32), bits)
+    v = [oracle.quantize(rng.standard_normal((M, k), dtype=np.float32), bits) for _ in range(C)]
+    # second checkpoint: the same code vectors assigned to other rows
+    tc, tr = [t0[0], np.roll(t0[0], 3, axis=0).copy()], [t0[2], np.roll(t0[2], 3).copy()]
+    vc, vr = [o[0] for o in v], [o[2] for o in v]
+    eta = ETA[:C]
+    ref, ref_full = oracle.score(tc, tr, vc, vr, eta, k, bits, want_full=True)
+    dev = lambda arrs: [torch.from_numpy(a).to(DEV) for a in arrs]
+    score, full = Q.score(dev(tc), dev(tr), dev(vc), dev(vr), eta, k, bits, want_full=True)
+    np.testing.assert_array_equal(full.cpu().numpy().view(np.uint32), ref_full.view(np.uint32))
+    np.testing.assert_array_equal(score.cpu().numpy().view(np.uint32), ref.view(np.uint32))

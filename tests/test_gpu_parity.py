@@ -195,7 +195,8 @@ def _datastore(n, k, bits, C, seed):
                                      (64, 33, 8192, 4), (1000, 130, 2048, 2), (515, 17, 256, 3),
                                      (260, 16, 128, 1), (40, 300, 384, 5), (600, 257, 192, 3),
                                      (513, 512, 640, 1), (1025, 129, 1152, 4), (1000, 5, 256, 3),
-                                     (4100, 8, 384, 2), (70, 3, 8192, 4)])
+                                     (4100, 8, 384, 2), (70, 3, 8192, 4), (2000, 16, 1152, 3),
+                                     (333, 12, 128, 2), (161, 9, 2048, 4), (50, 2, 8192, 4), (7, 6, 640, 1)])
 def test_score_bit_exact(bits, N, M, k, C):
     _say("score bits=%d N=%d M=%d k=%d C=%d" % (bits, N, M, k, C))
     tc, tr = _datastore(N, k, bits, C, 1000 + bits)
