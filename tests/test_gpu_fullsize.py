@@ -124,12 +124,12 @@ def test_config4_large_datastore_scoring(bits):
     assert set(planted.cpu().tolist()) <= set(oi.tolist())
 
 
-@pytest.mark.parametrize("M", [24, 7])
+@pytest.mark.parametrize("M", [24, 13, 7])
 @pytest.mark.parametrize("bits", [8, 4, 2, 1])
 def test_hbm_bound_regime_few_validation_vectors(bits, M):
     """N = 270000 with a few validation vectors (Sec. 4.1 has few-shot validation sets): the launch
     shapes that stream the train codes (narrow matrix-core tiles with several workgroups per compute
-    unit; for bit planes and M <= 8 the popcount streaming kernel); sampled rows bit-exact."""
+    unit; for bit planes and M <= 16 the barrier-free streaming kernel); sampled rows bit-exact."""
     N, k, C = 270000, 1024, 2
     _say("few validation vectors: score %d-bit N=270000 M=%d k=1024 C=2" % (bits, M))
     tcs, trs, vcs, vrs, planted = _big_datastore(N, M, k, C, bits, 4100 + bits)
