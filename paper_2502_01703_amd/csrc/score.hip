@@ -600,6 +600,271 @@ score_stream_mfma_kernel(ScoreArgs a, int64_t rb_each, int64_t rb_extra, int nb,
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// 1-bit codes against a chunk of up to 64 validation vectors: the train rows are streamed as above,
+// the products are 32 x 32 x 64 FP4 instructions.
+//
+// A wavefront works on tiles of 64 train rows (two panels of 32) x 64 validation vectors (two blocks
+// of 32): per 64-element K step it expands one dword of each panel and block (4 x 7 vector ALU
+// operations) for 4 matrix-core instructions, which keeps the vector ALU below the matrix cores.
+// The per-checkpoint sums of the tile stay in registers, so a wavefront walks its rows in passes
+// of up to 64; the wavefronts of a workgroup have equally many passes.
+//   * Train rows: a private ring per wavefront; a slot is a 64-byte slice of the 64 rows (four 1 KB
+//     copies of 16 rows x 64 bytes, chunk (lane % 4) ^ ((row / 2) % 4) at position lane % 4, so that 8
+//     rows read together use all banks).  The ring runs through all passes without a break.
+//   * Validation rows: all of them do not fit in LDS next to the rings, so the workgroup keeps a
+//     window of WB bytes of every row of one checkpoint, double buffered.  The windows follow each
+//     other in "phases" (pass, checkpoint, window).  The window of phase g + 1 is copied
+//     asynchronously during phase g, each wavefront its share; before the one barrier per phase a
+//     wavefront waits for its own share only (vector memory operations complete in order, so it
+//     waits until at most the ring copies it issued later are outstanding: nothing is drained).
+//     Rows are WB bytes apart, chunk c of row r at position c ^ (r % 8).
+//   * Lane (row l, half h) takes chunks 2 c + h, c = 0, 1, of a slice on both operands; dword j of
+//     a chunk is K step 4 c + j.
+// More than 64 validation vectors are handled by one launch per chunk of 64 (the train codes are
+// streamed again), later launches combining their row maxima with the score already there.
+// ------------------------------------------------------------------------------------------
+constexpr int kStream32Val = 64;               // validation vectors per launch
+constexpr int kStream32Waves = 8;
+
+__device__ inline void wait_vmcnt_upto(int n) {    // n wave-uniform, 0 <= n; waits for less when n > 24
+    switch (n) {
+    case 0: wait_vmcnt<0>(); break;   case 1: wait_vmcnt<1>(); break;   case 2: wait_vmcnt<2>(); break;
+    case 3: wait_vmcnt<3>(); break;   case 4: wait_vmcnt<4>(); break;   case 5: wait_vmcnt<5>(); break;
+    case 6: wait_vmcnt<6>(); break;   case 7: wait_vmcnt<7>(); break;   case 8: wait_vmcnt<8>(); break;
+    case 9: wait_vmcnt<9>(); break;   case 10: wait_vmcnt<10>(); break; case 11: wait_vmcnt<11>(); break;
+    case 12: wait_vmcnt<12>(); break; case 13: wait_vmcnt<13>(); break; case 14: wait_vmcnt<14>(); break;
+    case 15: wait_vmcnt<15>(); break; case 16: wait_vmcnt<16>(); break; case 17: wait_vmcnt<17>(); break;
+    case 18: wait_vmcnt<18>(); break; case 19: wait_vmcnt<19>(); break; case 20: wait_vmcnt<20>(); break;
+    case 21: wait_vmcnt<21>(); break; case 22: wait_vmcnt<22>(); break; case 23: wait_vmcnt<23>(); break;
+    default: wait_vmcnt<24>(); break;
+    }
+}
+
+// One ring slot (64-byte slice of NPAN panels of 32 train rows) against VB blocks of 32 validation
+// rows: 8 K steps.  sb: the slot; vwin: the validation window; vcol: chunk index of the slice's
+// first chunk inside the window; wb: bytes per window row.
+template <int VB, int NPAN>
+__device__ inline void stream32_slice(const unsigned char *sb, const unsigned char *vwin, int vcol, int wb,
+                                      int l32, int half, uint32_t ones, f32x16 (&acc)[2][VB]) {
+    // K step ks = 4 c + j uses dword j of chunk 2 c + half.  The operands of step ks + 1 are expanded
+    // between the matrix-core instructions of step ks (one instruction, then one operand's 7 vector
+    // ALU operations; scheduling barriers keep that order), so the matrix pipe is not left waiting
+    // for a burst of expansions and the vector ALU is not blocked behind queued matrix instructions.
+    uint4 tw[2][NPAN], vw[2][VB];
+    auto load_words = [&](int c) {
+        const int chunk = 2 * c + half;
+#pragma unroll
+        for (int p = 0; p < NPAN; ++p) {
+            const int r = 32 * p + l32, rr = r & 15;
+            tw[c][p] = *(const uint4 *)(sb + (r >> 4) * 1024 + rr * 64 + ((chunk ^ ((rr >> 1) & 3)) << 4));
+        }
+#pragma unroll
+        for (int vb = 0; vb < VB; ++vb)
+            vw[c][vb] = *(const uint4 *)(vwin + (size_t)(32 * vb + l32) * wb + (((vcol + chunk) ^ (l32 & 7)) << 4));
+    };
+    auto word = [](const uint4 &w, int j) { return j == 0 ? w.x : j == 1 ? w.y : j == 2 ? w.z : w.w; };
+    load_words(0);
+    i32x8 tv[NPAN], vv[VB];
+#pragma unroll
+    for (int vb = 0; vb < VB; ++vb) vv[vb] = fp4_codes<1>(word(vw[0][vb], 0), 0u, ones);
+#pragma unroll
+    for (int p = 0; p < NPAN; ++p) tv[p] = fp4_codes<1>(word(tw[0][p], 0), 0u, ones);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        if (ks == 1) load_words(1);
+        const int cn = (ks + 1) >> 2, jn = (ks + 1) & 3;       // next step's chunk and dword
+        i32x8 tvn[NPAN], vvn[VB];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int p = 0; p < NPAN; ++p)
+#pragma unroll
+            for (int vb = 0; vb < VB; ++vb) {
+                acc[p][vb] = mfma_fp4(vv[vb], tv[p], acc[p][vb]);
+                const int slot = p * VB + vb;                   // this instruction's share of the expansions
+                if (ks < 7) {
+                    if (slot < VB) vvn[slot] = fp4_codes<1>(word(vw[cn][slot], jn), 0u, ones);
+                    else if (slot < VB + NPAN) tvn[slot - VB] = fp4_codes<1>(word(tw[cn][slot - VB], jn), 0u, ones);
+                    if (NPAN * VB < NPAN + VB && slot == NPAN * VB - 1) {   // fewer instructions than operands
+#pragma unroll
+                        for (int e = NPAN * VB; e < NPAN + VB; ++e) {
+                            if (e < VB) vvn[e] = fp4_codes<1>(word(vw[cn][e], jn), 0u, ones);
+                            else tvn[e - VB] = fp4_codes<1>(word(tw[cn][e - VB], jn), 0u, ones);
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        if (ks < 7) {
+#pragma unroll
+            for (int vb = 0; vb < VB; ++vb) vv[vb] = vvn[vb];
+#pragma unroll
+            for (int p = 0; p < NPAN; ++p) tv[p] = tvn[p];
+        }
+    }
+}
+
+// VB = 1 or 2 validation blocks of 32 (chunk of mc <= 32 VB vectors starting at m0); wb: window
+// bytes per validation row, a power of two >= 128 that divides k / 8; npass: passes of the longest
+// row range (workgroup-uniform)
+template <int VB>
+__global__ void __launch_bounds__(64 * kStream32Waves, 2)
+score_stream_mfma32_kernel(ScoreArgs a, int32_t m0, int32_t mc, int64_t rb_each, int64_t rb_extra, int npass,
+                           int wb, int nb, unsigned ring_off) {
+    constexpr int NW = kStream32Waves;
+    constexpr int SLOT = 4096;                  // 64 rows x 64 bytes
+    // LDS: 2 x [32 VB][wb] validation windows | [C][32 VB] weights | rings
+    extern __shared__ __attribute__((aligned(16))) unsigned char vlds[];
+    const int lane = threadIdx.x & 63;
+    const int cpos = lane & 3, crow = lane >> 2;   // copy role: position and row inside a 1 KB copy
+    const int l32 = lane & 31, half = lane >> 5;   // matrix role
+    const int wv_id = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t wave = (int64_t)wv_id * gridDim.x + blockIdx.x;
+    const int64_t rb0 = wave * rb_each + (wave < rb_extra ? wave : rb_extra);
+    const int64_t rb1 = rb0 + rb_each + (wave < rb_extra ? 1 : 0);
+    const int cb = a.k / 8;                     // bytes per row, a multiple of 64 here
+    const int nsl = cb / 64;                    // 64-byte slices per row
+    const int nwin = cb / wb, spw = wb / 64;    // windows per row, slices per window
+    const int wbytes = 32 * VB * wb;            // one window buffer
+    float *wlds = (float *)(vlds + (size_t)2 * wbytes);
+    unsigned char *ring = vlds + ring_off + (size_t)wv_id * nb * SLOT;
+    const unsigned ring_lds = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)ring);
+    const unsigned vlds_lds = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)vlds);
+    const uint32_t ones = fp4_ones();
+
+    for (int i = threadIdx.x; i < a.C * 32 * VB; i += 64 * NW) {
+        const int j = i % (32 * VB), ci = i / (32 * VB);
+        wlds[i] = __fmul_rn(a.eta[ci], a.vr[ci][m0 + (j < mc ? j : mc - 1)]);
+    }
+    int64_t r_end = rb1 * 8;
+    if (r_end > a.N) r_end = a.N;
+    const int64_t r_begin = rb0 * 8;
+    const int64_t my_rows = r_end > r_begin ? r_end - r_begin : 0;
+    const int my_pass = (int)((my_rows + 63) / 64);          // passes in which this wavefront has rows
+    const int T = a.C * nsl;                                 // ring slots of a pass
+    const int S = my_pass * T;                               // ring slots of this wavefront
+
+    // ---- train ring: slot s is (pass s / T, checkpoint (s % T) / nsl, slice s % nsl)
+    int f_ps = 0, f_ci = 0, f_sl = 0, f_pos = 0, f_it = 0;
+    auto fetch = [&]() {
+        const int64_t rp = r_begin + (int64_t)f_ps * 64;
+        const int lastr = (int)(r_end - rp < 64 ? r_end - rp : 64) - 1;
+        const int off = f_sl * 64 + ((cpos ^ ((crow >> 1) & 3)) << 4);
+        const unsigned char *base = a.tc[f_ci] + rp * cb;                   // wave-uniform
+        const unsigned slot = ring_lds + (unsigned)f_pos * (unsigned)SLOT;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            int rl = q * 16 + crow;
+            if (rl > lastr) rl = lastr;                                      // clamped; masked at the output
+            global_to_lds16(base, (unsigned)(rl * cb + off), slot + (unsigned)q * 1024u);
+        }
+        ++f_it;
+        if (++f_pos == nb) f_pos = 0;
+        if (++f_sl == nsl) { f_sl = 0; if (++f_ci == a.C) { f_ci = 0; ++f_ps; } }
+    };
+    // ---- validation windows: phase g is (pass g / (C nwin), checkpoint, window); buffer g % 2.
+    // A window buffer is 32 VB wb / 1024 copies of 1 KB = 1024 / wb rows each; copy q belongs to
+    // wavefront q % NW.  Rows past the chunk repeat its last one.
+    const int nph = a.C * nwin, G = npass * nph;
+    const int ncopy = wbytes / 1024, lpr = wb / 16;          // copies per window; lanes per row
+    int v_cnt = 0;                                           // copies of the last request of this wavefront
+    int v_at = 0;                                            // ring slots issued before that request
+    auto fetch_window = [&](int g) {
+        const int ph = g % nph, ci = ph / nwin, win = ph - ci * nwin;
+        const unsigned buf = vlds_lds + (unsigned)((g & 1) * wbytes);
+        v_cnt = 0;
+        for (int q = wv_id; q < ncopy; q += NW) {
+            const int row = q * (1024 / wb) + lane / lpr, pos = lane % lpr;
+            const int jc = m0 + (row < mc ? row : mc - 1);
+            const unsigned char *src = a.vc[ci] + (int64_t)jc * cb + win * wb + ((pos ^ (row & 7)) << 4);
+            global_to_lds16(src, buf + (unsigned)q * 1024u);
+            ++v_cnt;
+        }
+        v_at = f_it;
+    };
+
+    fetch_window(0);
+    for (int i = 0; i < nb - 1 && i < S; ++i) fetch();
+    int it = 0, pos = 0;
+    for (int ps = 0; ps < npass; ++ps) {                                     // workgroup-uniform counts
+        const int64_t rp = r_begin + (int64_t)ps * 64;
+        const int rows = ps < my_pass ? (r_end - rp < 64 ? (int)(r_end - rp) : 64) : 0;   // wave-uniform
+        const int last = rows - 1;
+        f32x16 acc[2][VB];
+        float facc[2][VB][16];
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+#pragma unroll
+            for (int vb = 0; vb < VB; ++vb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) { acc[p][vb][v] = 0.0f; facc[p][vb][v] = 0.0f; }
+        for (int ci = 0; ci < a.C; ++ci) {
+            for (int win = 0; win < nwin; ++win) {
+                const int g = (ps * a.C + ci) * nwin + win;
+                // this wavefront's share of window g has landed once at most the ring copies issued
+                // after it are outstanding; the barrier makes every share visible and tells that
+                // all wavefronts are done with window g - 1, whose buffer the next request reuses
+                wait_vmcnt_upto(4 * (f_it - v_at));
+                __syncthreads();
+                if (g + 1 < G) fetch_window(g + 1);
+                if (rows > 0) {
+                    const unsigned char *vwin = vlds + (size_t)(g & 1) * wbytes;
+                    for (int s4 = 0; s4 < spw; ++s4) {
+                        // operations issued after this slot's copies: the younger slots and, if it
+                        // came later, the last window request
+                        wait_vmcnt_upto(4 * (f_it - 1 - it) + (it < v_at ? v_cnt : 0));
+                        if (f_it < S) fetch();
+                        const unsigned char *sb = ring + (size_t)pos * SLOT;
+                        if (rows > 32) stream32_slice<VB, 2>(sb, vwin, 4 * s4, wb, l32, half, ones, acc);
+                        else stream32_slice<VB, 1>(sb, vwin, 4 * s4, wb, l32, half, ones, acc);
+                        ++it;
+                        if (++pos == nb) pos = 0;
+                    }
+                }
+            }
+            if (rows > 0) {
+                // checkpoint epilogue: accumulator v of lane (train row l32, half) is validation row
+                // 8 (v / 4) + 4 half + v % 4 of its block
+#pragma unroll
+                for (int p = 0; p < 2; ++p) {
+                    if (p == 1 && rows <= 32) continue;
+                    const float rt = a.tr[ci][rp + (32 * p + l32 < rows ? 32 * p + l32 : last)];
+#pragma unroll
+                    for (int vb = 0; vb < VB; ++vb)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const float wv = wlds[ci * 32 * VB + 32 * vb + 8 * (v >> 2) + 4 * half + (v & 3)];
+                            const float t = __fmul_rn(__fmul_rn(acc[p][vb][v], rt), wv);   // acc holds the integer D exactly
+                            facc[p][vb][v] = __fadd_rn(facc[p][vb][v], t);
+                            acc[p][vb][v] = 0.0f;
+                        }
+                }
+            }
+        }
+        if (rows > 0) {
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                if (p == 1 && rows <= 32) continue;
+                const bool live = 32 * p + l32 < rows;
+                const int64_t r = rp + 32 * p + l32;
+                float m = neg_inf();
+#pragma unroll
+                for (int vb = 0; vb < VB; ++vb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int j = 32 * vb + 8 * (v >> 2) + 4 * half + (v & 3);
+                        if (j < mc) {
+                            m = fmaxf(m, facc[p][vb][v]);
+                            if (a.full && live) a.full[r * a.M + m0 + j] = facc[p][vb][v];
+                        }
+                    }
+                m = fmaxf(m, __shfl_xor(m, 32));
+                if (a.score && live && half == 0) a.score[r] = m0 > 0 ? fmaxf(a.score[r], m) : m;
+            }
+        }
+    }
+}
+
 // Shape of the NW waves of a workgroup: WX waves across the val tile, NW / WX down the train
 // rows; each wave owns WR x WC accumulators of 32 x 32.  Train tile height MT = 32 WR NW / WX, val
 // tile width VT = 32 WC WX:
@@ -1087,6 +1352,57 @@ static qless_status launch_stream_mfma(const ScoreArgs &a, int bits, const Strea
     return launch_status();
 }
 
+// LDS plan of score_stream_mfma32_kernel: two validation windows of wb bytes per row, weights,
+// 8 rings of nb slots (nb = 0: does not fit).  Narrower windows cost more barriers, deeper rings
+// hide more memory latency: the widest window that leaves room for three slots, else for two.
+#ifndef QLESS_STREAM32_MAX_M
+#define QLESS_STREAM32_MAX_M 320
+#endif
+constexpr int kStream32MaxVal = QLESS_STREAM32_MAX_M;                // beyond this the tile kernel takes over
+struct Stream32Plan { int wb, nb; size_t val_bytes, lds; };
+static Stream32Plan stream_mfma32_plan(int vb, int32_t k, int C) {
+    Stream32Plan best{};
+    const int cb = k / 8;
+    for (int want = 3; want >= 2 && best.nb == 0; --want)
+        for (int wb = 1024; wb >= 128; wb >>= 1) {
+            if (cb % wb) continue;
+            const size_t val = (((size_t)2 * 32 * vb * wb + (size_t)C * 32 * vb * 4) + 1023) & ~(size_t)1023;
+            if (val + (size_t)kStream32Waves * want * 4096 > kLdsPerCU) continue;
+            best.wb = wb; best.nb = want; best.val_bytes = val;
+            best.lds = val + (size_t)kStream32Waves * want * 4096;
+            break;
+        }
+    return best;
+}
+static qless_status launch_stream_mfma32(const ScoreArgs &a, hipStream_t st) {
+    constexpr int NW = kStream32Waves;
+    static bool allowed = false;                                     // LDS above 64 KB has to be allowed per kernel
+    if (!allowed) {
+        const void *fns[2] = {(const void *)score_stream_mfma32_kernel<1>, (const void *)score_stream_mfma32_kernel<2>};
+        for (const void *f : fns)
+            if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU) != hipSuccess)
+                return QLESS_ERR_DEVICE;
+        allowed = true;
+    }
+    // at most one workgroup per compute unit; the 8-row blocks are dealt out evenly over all wavefronts
+    const int64_t total_rb = (a.N + 7) / 8;
+    int64_t groups = compute_units();
+    if (groups * NW > total_rb) groups = (total_rb + NW - 1) / NW;
+    const int64_t waves = groups * NW;
+    const int64_t each = total_rb / waves, extra = total_rb % waves;
+    const int npass = (int)(((each + (extra > 0 ? 1 : 0)) * 8 + 63) / 64);
+    const dim3 grid((unsigned)groups), block(64 * NW);
+    for (int32_t m0 = 0; m0 < a.M; m0 += kStream32Val) {
+        const int32_t mc = a.M - m0 < kStream32Val ? a.M - m0 : kStream32Val;
+        const int vb = mc > 32 ? 2 : 1;
+        const Stream32Plan sp = stream_mfma32_plan(vb, a.k, a.C);
+        const unsigned ro = (unsigned)sp.val_bytes;
+        if (vb == 1) hipLaunchKernelGGL((score_stream_mfma32_kernel<1>), grid, block, sp.lds, st, a, m0, mc, each, extra, npass, sp.wb, sp.nb, ro);
+        else hipLaunchKernelGGL((score_stream_mfma32_kernel<2>), grid, block, sp.lds, st, a, m0, mc, each, extra, npass, sp.wb, sp.nb, ro);
+    }
+    return launch_status();
+}
+
 template <int BITS, int RT, int CT, int TY, int TX>
 static void launch_popcount(const ScoreArgs &a, hipStream_t st) {
     constexpr int TN = RT * TY, TM = CT * TX, SW = BITS * 16 + 4, RSTEP = 256 / (8 * BITS);
@@ -1129,6 +1445,8 @@ extern "C" qless_status qless_score(const void *const *train_codes, const float 
         const StreamMfmaPlan sp = stream_mfma_plan(M, k, bits, C);
         if (sp.nb >= 2) return launch_stream_mfma(a, bits, sp, st);
     }
+    if (bits == 1 && M <= kStream32MaxVal && k % 512 == 0 && stream_mfma32_plan(2, k, C).nb >= 2)
+        return launch_stream_mfma32(a, st);
     if (use_mfma_path(bits, M, k)) {
         const size_t need = mfma_plan(N, M, k, bits, C).total;
         if (!ws || ws_bytes < need) return QLESS_ERR_WORKSPACE;

@@ -199,11 +199,12 @@ def test_config2_multi_bit_sweep_pipeline():
             assert hit >= 0.95 * n_pl, (b, hit)
 
 
+@pytest.mark.parametrize("M,k", [(11, 256), (40, 512), (100, 512)])
 @pytest.mark.parametrize("bits", [2, 1])
-def test_streaming_wavefronts_take_several_passes(bits):
+def test_streaming_wavefronts_take_several_passes(bits, M, k):
     """More train rows than one pass of every wavefront of the few-validation-vector bit-plane
-    kernel covers (Eq. (6), (7) on a large, short-vector datastore): whole output bit-exact."""
-    N, M, k, C = 400000, 11, 256, 2
+    kernels covers (Eq. (6), (7) on a large, short-vector datastore): whole output bit-exact."""
+    N, C = 400000, 2
     _say("several passes per wavefront: score %d-bit N=%d M=%d k=%d C=%d" % (bits, N, M, k, C))
     rng = np.random.default_rng(77 + bits)
     t0 = oracle.quantize(rng.standard_normal((N, k), dtype=np.float32), bits)

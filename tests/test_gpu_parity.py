@@ -196,7 +196,9 @@ def _datastore(n, k, bits, C, seed):
                                      (260, 16, 128, 1), (40, 300, 384, 5), (600, 257, 192, 3),
                                      (513, 512, 640, 1), (1025, 129, 1152, 4), (1000, 5, 256, 3),
                                      (4100, 8, 384, 2), (70, 3, 8192, 4), (2000, 16, 1152, 3),
-                                     (333, 12, 128, 2), (161, 9, 2048, 4), (50, 2, 8192, 4), (7, 6, 640, 1)])
+                                     (333, 12, 128, 2), (161, 9, 2048, 4), (50, 2, 8192, 4), (7, 6, 640, 1),
+                                     (500, 40, 1024, 3), (1000, 64, 512, 2), (333, 100, 1024, 2), (129, 17, 8192, 4),
+                                     (4100, 33, 512, 1), (64, 320, 1024, 2), (2000, 129, 2048, 3)])
 def test_score_bit_exact(bits, N, M, k, C):
     _say("score bits=%d N=%d M=%d k=%d C=%d" % (bits, N, M, k, C))
     tc, tr = _datastore(N, k, bits, C, 1000 + bits)
