@@ -3,8 +3,11 @@
 //
 // Every example gets a 64-bit key  (order-preserving image of the fp32 score) << 32 | (2^32-1 - index);
 // keys are distinct and "larger key" is exactly "selected earlier".  Steps:
-//   1. build keys;  2. radix-select the k_sel-th largest key, 8 passes of 8 bits (histogram +
-//   one-workgroup digit pick);  3. compact all keys >= threshold (exactly k_sel of them);
+//   1. build keys;  2. radix-select the k_sel-th largest key, up to 8 passes of 8 bits (histogram +
+//   one-workgroup digit pick); the passes turn into empty launches as soon as the bucket that
+//   holds the k_sel-th key is selected as a whole (without ties at the threshold that is after
+//   the four digits of the score);  3. compact all keys >= threshold (exactly k_sel of them; one
+//   atomic per wavefront);
 //   4. sort them descending with a bitonic network (LDS for spans up to 4096, global steps
 //   above);  5. decode indices and gather the scores.
 #include "common.h"
@@ -36,7 +39,7 @@ struct SelectState {
     unsigned long long prefix;     // high digits of the threshold found so far
     unsigned long long remaining;  // rank still to locate inside the current prefix bucket
     unsigned int count;            // compaction cursor
-    unsigned int pad;
+    unsigned int done;             // the threshold is final: later passes return at once
 };
 
 __device__ inline uint32_t order_key(float f) {
@@ -48,7 +51,7 @@ __device__ inline uint32_t order_key(float f) {
 __global__ void topk_keys_kernel(const float *score, int64_t N, unsigned long long *keys,
                                  unsigned int *hist, SelectState *state, unsigned long long k_sel) {
     const int64_t i0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i0 == 0) { state->prefix = 0; state->remaining = k_sel; state->count = 0; }
+    if (i0 == 0) { state->prefix = 0; state->remaining = k_sel; state->count = 0; state->done = 0; }
     if (i0 < 256) hist[i0] = 0;
     for (int64_t i = i0; i < N; i += (int64_t)gridDim.x * blockDim.x)
         keys[i] = ((unsigned long long)order_key(score[i]) << 32) | (0xFFFFFFFFull - (unsigned long long)i);
@@ -59,6 +62,7 @@ __global__ void __launch_bounds__(256)
 topk_hist_kernel(const unsigned long long *keys, int64_t N, int pass, const SelectState *state,
                  unsigned int *hist) {
     __shared__ unsigned int h[256];
+    if (state->done) return;                        // uniform: written by an earlier launch
     h[threadIdx.x] = 0;
     __syncthreads();
     const unsigned long long prefix = state->prefix;
@@ -75,49 +79,56 @@ topk_hist_kernel(const unsigned long long *keys, int64_t N, int pass, const Sele
     if (h[threadIdx.x]) atomicAdd(&hist[threadIdx.x], h[threadIdx.x]);
 }
 
-// one workgroup: walk the 256 bins from the top, find the digit holding the remaining rank
+// one workgroup: the digit that holds the remaining rank, walking the 256 bins from the top
 __global__ void __launch_bounds__(256)
 topk_pick_kernel(int pass, SelectState *state, unsigned int *hist) {
-    __shared__ unsigned int h[256];
-    h[threadIdx.x] = hist[threadIdx.x];
-    __syncthreads();
+    __shared__ unsigned long long above[257];      // above[d] = counted keys with digit >= d
+    if (state->done) return;
+    const unsigned int mine = hist[threadIdx.x];
     hist[threadIdx.x] = 0;                          // ready for the next pass
-    if (threadIdx.x == 0) {
-        unsigned long long rem = state->remaining;
-        const int shift = 56 - 8 * pass;
-        int d = 255;
-        if (rem > 0) {
-            for (; d > 0; --d) {
-                if (h[d] >= rem) break;
-                rem -= h[d];
-            }
-        }
-        state->prefix |= (unsigned long long)d << shift;
-        state->remaining = rem;
+    above[threadIdx.x] = mine;
+    if (threadIdx.x == 0) above[256] = 0;
+    __syncthreads();
+    for (int step = 1; step < 256; step <<= 1) {    // suffix sums over the 256 bins (Hillis-Steele)
+        const unsigned long long add = threadIdx.x + step < 256 ? above[threadIdx.x + step] : 0ull;
+        __syncthreads();
+        above[threadIdx.x] += add;
+        __syncthreads();
+    }
+    const unsigned long long rem = state->remaining;
+    const int d = (int)threadIdx.x;
+    // the digit is the largest d with above[d] >= rem; if no bin reaches the rank it is 0
+    const bool here = (above[d] >= rem && above[d + 1] < rem) || (d == 0 && above[0] < rem);
+    if (here) {
+        const unsigned long long left = rem - above[d + 1];
+        state->prefix |= (unsigned long long)d << (56 - 8 * pass);
+        state->remaining = left;
+        // the whole bucket is selected: the prefix with zeros below is the threshold
+        if (left == (unsigned long long)mine) state->done = 1;
     }
 }
 
+// Keys >= threshold (exactly k_sel of them) are gathered in any order; the slots from k_sel to
+// padded are cleared.  One atomic per wavefront: its selected lanes take consecutive positions.
 __global__ void topk_compact_kernel(const unsigned long long *keys, int64_t N, SelectState *state,
                                     unsigned long long *sel, int64_t k_sel, int64_t padded) {
     const unsigned long long thr = state->prefix;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < padded;
+    const int lane = threadIdx.x & 63;
+    const int64_t span = N > padded ? N : padded;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < span;
          i += (int64_t)gridDim.x * blockDim.x) {
-        if (i >= k_sel) sel[i] = 0;                 // padding sorts last (real keys are > 0)
-        if (i < N) {
-            const unsigned long long key = keys[i];
-            if (k_sel > 0 && key >= thr) {
-                const unsigned int pos = atomicAdd(&state->count, 1u);
-                if ((int64_t)pos < k_sel) sel[pos] = key;
-            }
-        }
-    }
-    // keys beyond `padded` (N > padded) are visited by a second loop
-    for (int64_t i = padded + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        const unsigned long long key = keys[i];
-        if (k_sel > 0 && key >= thr) {
-            const unsigned int pos = atomicAdd(&state->count, 1u);
-            if ((int64_t)pos < k_sel) sel[pos] = key;
+        if (i >= k_sel && i < padded) sel[i] = 0;   // padding sorts last (real keys are > 0)
+        unsigned long long key = 0;
+        bool take = false;
+        if (i < N) { key = keys[i]; take = key >= thr; }
+        const unsigned long long mask = __ballot(take);
+        if (mask) {
+            const int leader = __ffsll((long long)mask) - 1;
+            unsigned int base = 0;
+            if (lane == leader) base = atomicAdd(&state->count, (unsigned int)__popcll(mask));
+            base = __shfl(base, leader);
+            const unsigned int pos = base + (unsigned int)__popcll(mask & ((1ull << lane) - 1ull));
+            if (take && (int64_t)pos < k_sel) sel[pos] = key;
         }
     }
 }

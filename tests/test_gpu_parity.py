@@ -272,6 +272,20 @@ def test_topk_identical_with_ties(N, k_sel):
     np.testing.assert_array_equal(val.cpu().numpy().view(np.uint32), ref_v.view(np.uint32))
 
 
+@pytest.mark.parametrize("N,k_sel", [(270000, 13500), (100000, 1), (4096, 4096), (70000, 33000), (1, 1)])
+def test_topk_identical_without_ties(N, k_sel):
+    """Distinct scores (the selection can stop after the digits of the score) and a few equal ones."""
+    _say("topk distinct N=%d k_sel=%d" % (N, k_sel))
+    rng = np.random.default_rng(N + 7 * k_sel)
+    s = rng.permutation(N).astype(np.float32) * np.float32(0.37) - np.float32(1000.0)
+    if N > 10:
+        s[N // 3] = s[N // 2]                                                # one tie somewhere
+    ref_i, ref_v = oracle.topk(s, k_sel)
+    idx, val = Q.topk(torch.from_numpy(s).to(DEV), k_sel)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ref_i)
+    np.testing.assert_array_equal(val.cpu().numpy().view(np.uint32), ref_v.view(np.uint32))
+
+
 # --------------------------------------------------------------------------------- end to end
 def test_config1_end_to_end_planted_recovery():
     _say("config 1 end to end on the GPU: project -> quantize(8) -> score -> top-50")
