@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--d-log2", type=int, default=27, help="gradient dimension 2^x (27 = the metric's shape)")
     ap.add_argument("--skip-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--skip-scoring", action="store_true", help="skip the scoring-only leg")
+    ap.add_argument("--sweep", action="store_true",
+                    help="scoring leg over all four code widths and the validation-set sizes 8 ... 1024")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for profiler byte counters)")
     args = ap.parse_args()
@@ -154,13 +156,14 @@ def main():
         del train_codes, train_rnorm
         N4 = 270000
         oracle_sample = None
-        for sb in (1, 8):
+        for sb in ((1, 2, 4, 8) if args.sweep else (1, 8)):
             cbb = Q.code_bytes(k, sb)
             tc4, tr4 = synthetic_store(N4, 40, sb)
             vc4f, vr4f = synthetic_store(1024, 50, sb)
             sc4 = torch.empty(N4, dtype=torch.float32, device=dev)
             ws4 = torch.empty(max(Q.topk_workspace(N4, 13500), 16), dtype=torch.uint8, device=dev)
-            for M4 in (1024, 64, 8):          # M = 1024: matrix-core bound; M = 8: HBM bound
+            # M = 1024: matrix-core bound; M = 8: HBM bound; 9 / 81 / 285: few-shot validation sets (Sec. 4.1)
+            for M4 in ((1024, 285, 81, 64, 32, 16, 9, 8) if args.sweep else (1024, 64, 8)):
                 vc4, vr4 = [v[:M4] for v in vc4f], [v[:M4] for v in vr4f]
                 wss = torch.empty(max(Q.score_workspace(N4, M4, k, sb, C), 16), dtype=torch.uint8, device=dev)
                 Q.score(tc4, tr4, vc4, vr4, eta, k, sb, score_out=sc4, ws=wss)

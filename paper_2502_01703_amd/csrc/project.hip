@@ -107,13 +107,14 @@ __device__ inline uint4 load_chunk(const ProjectArgs &a, int64_t row, int64_t co
     return out;
 }
 
-union Frag { bf16x8 v; bf16x2 p[4]; uint4 u; uint32_t w[4]; };
+union Frag { bf16x8 v; bf16x2 p[4]; uint4 u; uint32_t w[4]; uint16_t h[8]; };
 
 // DIRECT: gradient tiles go global -> LDS asynchronously (no VGPR staging) into a ring of kRing
 // unpadded, XOR-swizzled stage buffers, three stages ahead of the MFMAs.  It needs bf16 input,
 // 16-byte aligned rows and a gradient length that is a multiple of the stage width; every other
 // case stages through registers into two padded buffers.
 constexpr int kRing = 4;
+constexpr int kGaussCopies = 32;                // copies of the Gaussian table in LDS
 constexpr int kDirectStageBytes = kTileRows * kStageD * 2;
 
 template <bool IN_F32, bool ALIGNED, bool GAUSS, bool DIRECT>
@@ -141,7 +142,12 @@ project_kernel(ProjectArgs a, GaussTable gt) {
     const int nstages = (int)((c_end - c_begin + kStageD - 1) / kStageD);
 
     uint16_t *gtab = (uint16_t *)(smem + (DIRECT ? kRing * kDirectStageBytes : 2 * kStageBytes));
-    if (GAUSS && tid < 256) { gtab[tid] = gt.v[tid]; }
+    // Gaussian table in LDS, 32 copies side by side: entry i for lane l at halfword 32 i + l % 32, so
+    // the 32 lanes that look up together use 16 different banks whatever their indices are (a single
+    // copy makes them collide on the 128 dwords of the table)
+    if (GAUSS) {
+        for (int i = tid; i < 256 * kGaussCopies; i += kWaves * 64) gtab[i] = gt.v[i / kGaussCopies];
+    }
 
     // row keys of this lane's four 32-row blocks
     const int mbase = kt * kTileCols + wave * kWaveCols;
@@ -233,6 +239,7 @@ project_kernel(ProjectArgs a, GaussTable gt) {
         __syncthreads();
     }
 
+    const uint16_t *gl = gtab + (lane & (kGaussCopies - 1));   // this lane's copy of the table
     uint32_t fp4_one = 0x22222222u;                // eight FP4 codes of +1.0
     asm volatile("" : "+v"(fp4_one));              // keep it in a vector register
     for (int s = 0; s < nstages; ++s) {
@@ -284,10 +291,10 @@ project_kernel(ProjectArgs a, GaussTable gt) {
                         const uint32_t h0 = key_word(key[kb], (w4 + 2u * ks) * kGold + kSaltStride);
                         const uint32_t h1 = key_word(key[kb], (w4 + 2u * ks + 1u) * kGold + kSaltStride);
                         Frag bf;
-                        bf.w[0] = (uint32_t)gtab[h0 & 0xFF] | ((uint32_t)gtab[(h0 >> 8) & 0xFF] << 16);
-                        bf.w[1] = (uint32_t)gtab[(h0 >> 16) & 0xFF] | ((uint32_t)gtab[h0 >> 24] << 16);
-                        bf.w[2] = (uint32_t)gtab[h1 & 0xFF] | ((uint32_t)gtab[(h1 >> 8) & 0xFF] << 16);
-                        bf.w[3] = (uint32_t)gtab[(h1 >> 16) & 0xFF] | ((uint32_t)gtab[h1 >> 24] << 16);
+                        bf.h[0] = gl[(h0 & 0xFF) * kGaussCopies];         bf.h[1] = gl[((h0 >> 8) & 0xFF) * kGaussCopies];
+                        bf.h[2] = gl[((h0 >> 16) & 0xFF) * kGaussCopies]; bf.h[3] = gl[(h0 >> 24) * kGaussCopies];
+                        bf.h[4] = gl[(h1 & 0xFF) * kGaussCopies];         bf.h[5] = gl[((h1 >> 8) & 0xFF) * kGaussCopies];
+                        bf.h[6] = gl[((h1 >> 16) & 0xFF) * kGaussCopies]; bf.h[7] = gl[(h1 >> 24) * kGaussCopies];
                         acc[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[0][ks].v, bf.v, acc[0][kb], 0, 0, 0);
                         acc[1][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][ks].v, bf.v, acc[1][kb], 0, 0, 0);
                     }
@@ -381,7 +388,8 @@ static qless_status project_partials(const void *G, qless_dtype dt, int64_t n, i
     const size_t esz = dt == QLESS_F32 ? 4 : 2;
     const bool aligned = ((uintptr_t)G % 16 == 0) && ((ldG * esz) % 16 == 0);
     const bool direct = dt == QLESS_BF16 && aligned && d_len % kStageD == 0;
-    const size_t lds = (direct ? (size_t)kRing * kDirectStageBytes : (size_t)2 * kStageBytes) + 512;
+    const size_t lds = (direct ? (size_t)kRing * kDirectStageBytes : (size_t)2 * kStageBytes) +
+                       (gauss ? (size_t)256 * kGaussCopies * 2 : 0);
     dim3 grid((unsigned)plan.grid), block(kWaves * 64);
     // more than 64 KB of dynamic LDS has to be allowed per kernel (host-side attribute, no device work)
 #define QLESS_LAUNCH(F32, AL, GA, DI) do { \

@@ -216,6 +216,34 @@ def test_score_bit_exact(bits, N, M, k, C):
     assert torch.equal(only, s)
 
 
+def _random_score_shapes():
+    rng = np.random.default_rng(20250201)
+    out = []
+    for _ in range(48):
+        bits = int(rng.choice([1, 1, 2, 4, 8]))
+        k = int(rng.choice([64, 128, 192, 512, 1024, 1536, 2048, 4096]))
+        M = int(rng.choice([1, 3, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64, 65, 100, 129, 321]))
+        N = int(rng.integers(1, 2500))
+        C = int(rng.integers(1, 6))
+        out.append((bits, N, M, k, C))
+    return out
+
+
+@pytest.mark.parametrize("bits,N,M,k,C", _random_score_shapes())
+def test_score_random_shapes(bits, N, M, k, C):
+    """Seeded random shapes around the limits at which qless_score changes kernels (validation
+    vectors 8 / 16 / 64 / 320, vector lengths that are or are not multiples of 128 and 512)."""
+    _say("score random shape bits=%d N=%d M=%d k=%d C=%d" % (bits, N, M, k, C))
+    tc, tr = _datastore(N, k, bits, C, 3000 + N)
+    vc, vr = _datastore(M, k, bits, C, 4000 + M)
+    eta = [0.9, 0.7, 0.5, 0.3, 0.1][:C]
+    ref_s, ref_f = oracle.score(tc, tr, vc, vr, eta, k, bits, want_full=True)
+    dev = lambda arrs: [torch.from_numpy(a).to(DEV) for a in arrs]
+    s, f = Q.score(dev(tc), dev(tr), dev(vc), dev(vr), eta, k, bits, want_full=True)
+    np.testing.assert_array_equal(f.cpu().numpy().view(np.uint32), ref_f.view(np.uint32))
+    np.testing.assert_array_equal(s.cpu().numpy().view(np.uint32), ref_s.view(np.uint32))
+
+
 # -------------------------------------------------------------------------------------- top-k
 # ------------------------------------------------------------------------- 16-bit LESS comparator
 @pytest.mark.parametrize("n,k", [(33, 576), (4, 64), (7, 8192), (300, 1024)])
