@@ -266,9 +266,14 @@ __device__ inline int val_source_element(int p) {
         const int d = i >> 2, b = i & 3;               // dword d, byte b
         return base + 8 * (d >> 1) + 2 * b + (d & 1);
     }
-    // FP4 codes (1- and 2-bit): K step g (64 elements), half h, dword j, nibble n <- bit 4 n + 3 - j of the lane's word
+    // FP4 codes (1- and 2-bit), stages of 512 elements = 16 words of 32 codes per row.  K step ks of a
+    // stage (64 positions), half h: the train lane reads the 16-byte chunk 2 (ks / 4) + h and uses its
+    // dword ks % 4, i.e. word 4 (2 (ks / 4) + h) + ks % 4 of the stage; FP4 dword j, nibble n of the
+    // expansion is bit 4 n + 3 - j of that word.
     const int g = p >> 6, h = (p >> 5) & 1, j = (p >> 3) & 3, n = p & 7;
-    return 64 * g + 32 * h + 4 * n + 3 - j;
+    const int stage = g >> 3, ks = g & 7;
+    const int word = 16 * stage + 4 * (2 * (ks >> 2) + h) + (ks & 3);
+    return 32 * word + 4 * n + 3 - j;
 }
 
 template <int BITS, bool F16 = false>        // F16: rows are bfloat16 bytes, no code norms (see score_mfma_kernel)
@@ -285,9 +290,8 @@ score_prepare_kernel(ScoreArgs a, ScorePrep w) {
             unsigned byte = 0;
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                const int pos = 2 * bi + e;
-                if (live && pos < a.k) {
-                    const int m = val_source_element<BITS>(pos);
+                const int m = val_source_element<BITS>(2 * bi + e);      // source elements past k: code 0
+                if (live && m < a.k) {
                     unsigned nz = 1u, neg;
                     if (BITS == 2) {
                         nz = (src[m >> 3] >> (m & 7)) & 1u;
@@ -992,7 +996,8 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
         const int sw = (l32 >> TSH) & (TCPR - 1);       // trow + 32 b is a multiple of 32: the key is l32's
         if (BITS == 8) a_base[b] = R * TB + (sw >> 1) * 32 + ((half ^ (sw & 1)) * 16);
         else if (BITS == 4) a_base[b] = R * TB + sw * 16 + half * 8;
-        else a_base[b] = R * TB + sw * 16 + half * 4;   // bit planes: 4-byte reads, chunk chosen by XOR below
+        else if (Sh::VPACKED) a_base[b] = R * TB + sw * 16 + half * 4;   // 4-byte reads, chunk chosen by XOR below
+        else a_base[b] = R * TB + ((sw ^ half) << 4);   // bit planes: 16-byte reads of chunk 2 q + half, q by XOR below
     }
 #pragma unroll
     for (int c = 0; c < WC; ++c) {
@@ -1054,15 +1059,49 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
             __syncthreads();                         // stage g visible to all; buffer of stage g-1 free
             if (g + NBUF - 1 < total) issue(g + NBUF - 1);
             const unsigned char *sb = smem + (g % NBUF) * BUF;
-            if constexpr (BITS == 1) {
-                // sign codes as FP4: one 64-element K step per matrix-core instruction.  A lane's word
-                // (32 signs of its row) becomes four dwords of FP4 codes, dword j = bits 3 - j of every
-                // nibble: ((w << j) & 0x88888888) | 0x22222222 -> 0x2 = +1.0, 0xA = -1.0.
-                // K steps of the last stage that start past the end of the vectors are skipped (k % 64 == 0)
+            if constexpr (BITS == 1 && !Sh::VPACKED) {
+                // sign codes as FP4: one 64-element K step per matrix-core instruction.  A lane reads 16
+                // bytes of its row (chunk 2 q + half: four words of 32 signs) per four K steps; word j
+                // becomes four dwords of FP4 codes, dword jd = bits 3 - jd of every nibble:
+                // ((w << jd) & 0x88888888) | 0x22222222 -> 0x2 = +1.0, 0xA = -1.0.  The pre-expanded
+                // validation rows follow the same order and are zero past the end of the vectors.
+#pragma unroll
+                for (int q = 0; q < KE / 256; ++q) {
+                    i32x4 wq[WR];
+#pragma unroll
+                    for (int b = 0; b < WR; ++b) wq[b] = *(const i32x4 *)(sb + (a_base[b] ^ (q << 5)));
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int ks = 4 * q + j;
+                        i32x8 af[WR], bf[WC];
+#pragma unroll
+                        for (int b = 0; b < WR; ++b) {
+                            const unsigned int wd = (unsigned int)wq[b][j];
+#pragma unroll
+                            for (int jd = 0; jd < 4; ++jd) af[b][jd] = (int)sign_bits_or(wd << jd, ones);
+#pragma unroll
+                            for (int jd = 4; jd < 8; ++jd) af[b][jd] = 0;
+                        }
+#pragma unroll
+                        for (int c = 0; c < WC; ++c) {
+                            const i32x4 lo = *(const i32x4 *)(sb + (b_base[c] ^ (ks << 5)));
+                            bf[c] = i32x8{lo[0], lo[1], lo[2], lo[3], 0, 0, 0, 0};
+                        }
+#pragma unroll
+                        for (int b = 0; b < WR; ++b)
+#pragma unroll
+                            for (int c = 0; c < WC; ++c)
+                                acc[b][c] = mfma_fp4(af[b], bf[c], acc[b][c]);
+                    }
+                }
+            } else if constexpr (BITS == 1) {
+                // few validation vectors: both operands are packed rows, read as 4-byte words (K step ks:
+                // word 2 ks + half) and expanded in registers.  K steps of the last stage that start past
+                // the end of the vectors are skipped (k % 64 == 0).
                 const int ksteps = (a.k - s * KE) / 64 < KE / 64 ? (a.k - s * KE) / 64 : KE / 64;
 #pragma unroll
                 for (int ks = 0; ks < KE / 64; ++ks) {
-                    if (Sh::VPACKED && ks >= ksteps) break;    // (pre-expanded validation rows are zero there)
+                    if (ks >= ksteps) break;
                     i32x8 af[WR], bf[WC];
 #pragma unroll
                     for (int b = 0; b < WR; ++b) {
@@ -1074,16 +1113,11 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
                     }
 #pragma unroll
                     for (int c = 0; c < WC; ++c) {
-                        if (Sh::VPACKED) {
-                            const unsigned int wd = *(const unsigned int *)(sb + (b_base[c] ^ ((ks >> 1) << 4)) + 8 * (ks & 1));
+                        const unsigned int wd = *(const unsigned int *)(sb + (b_base[c] ^ ((ks >> 1) << 4)) + 8 * (ks & 1));
 #pragma unroll
-                            for (int jd = 0; jd < 4; ++jd) bf[c][jd] = (int)sign_bits_or(wd << jd, ones);
+                        for (int jd = 0; jd < 4; ++jd) bf[c][jd] = (int)sign_bits_or(wd << jd, ones);
 #pragma unroll
-                            for (int jd = 4; jd < 8; ++jd) bf[c][jd] = 0;
-                        } else {
-                            const i32x4 lo = *(const i32x4 *)(sb + (b_base[c] ^ (ks << 5)));
-                            bf[c] = i32x8{lo[0], lo[1], lo[2], lo[3], 0, 0, 0, 0};
-                        }
+                        for (int jd = 4; jd < 8; ++jd) bf[c][jd] = 0;
                     }
 #pragma unroll
                     for (int b = 0; b < WR; ++b)
@@ -1093,32 +1127,42 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
                 }
             } else if constexpr (BITS == 2) {
                 // ternary codes as FP4 {-1.0, 0, +1.0}: nibble bit 3 <- "negative" plane, bit 1 <- "non-zero"
-                // plane (0xA, 0x0, 0x2); dword j takes bits 4 n + 3 - j of the lane's two plane words
+                // plane (0xA, 0x0, 0x2); 16-byte reads of both planes per four K steps, dword jd of the
+                // expansion takes bits 4 n + 3 - jd of the two plane words
 #pragma unroll
-                for (int ks = 0; ks < KE / 64; ++ks) {
-                    i32x8 af[WR], bf[WC];
+                for (int q = 0; q < KE / 256; ++q) {
+                    i32x4 wnq[WR], wgq[WR];
 #pragma unroll
                     for (int b = 0; b < WR; ++b) {
-                        const unsigned int wn = *(const unsigned int *)(sb + (a_base[b] ^ ((ks >> 1) << 4)) + 8 * (ks & 1));
-                        const unsigned int wg = *(const unsigned int *)(sb + (a_base[b] ^ ((PCH + (ks >> 1)) << 4)) + 8 * (ks & 1));
+                        wnq[b] = *(const i32x4 *)(sb + (a_base[b] ^ (q << 5)));
+                        wgq[b] = *(const i32x4 *)(sb + (a_base[b] ^ (q << 5) ^ (PCH << 4)));
+                    }
 #pragma unroll
-                        for (int jd = 0; jd < 4; ++jd) {
-                            const unsigned int zs = jd >= 2 ? wn << (jd - 2) : wn >> (2 - jd);
-                            af[b][jd] = (int)sign_bits_or(wg << jd, zs & 0x22222222u);
+                    for (int j = 0; j < 4; ++j) {
+                        const int ks = 4 * q + j;
+                        i32x8 af[WR], bf[WC];
+#pragma unroll
+                        for (int b = 0; b < WR; ++b) {
+                            const unsigned int wn = (unsigned int)wnq[b][j], wg = (unsigned int)wgq[b][j];
+#pragma unroll
+                            for (int jd = 0; jd < 4; ++jd) {
+                                const unsigned int zs = jd >= 2 ? wn << (jd - 2) : wn >> (2 - jd);
+                                af[b][jd] = (int)sign_bits_or(wg << jd, zs & 0x22222222u);
+                            }
+#pragma unroll
+                            for (int jd = 4; jd < 8; ++jd) af[b][jd] = 0;
                         }
 #pragma unroll
-                        for (int jd = 4; jd < 8; ++jd) af[b][jd] = 0;
+                        for (int c = 0; c < WC; ++c) {
+                            const i32x4 lo = *(const i32x4 *)(sb + (b_base[c] ^ (ks << 5)));
+                            bf[c] = i32x8{lo[0], lo[1], lo[2], lo[3], 0, 0, 0, 0};
+                        }
+#pragma unroll
+                        for (int b = 0; b < WR; ++b)
+#pragma unroll
+                            for (int c = 0; c < WC; ++c)
+                                acc[b][c] = mfma_fp4(af[b], bf[c], acc[b][c]);
                     }
-#pragma unroll
-                    for (int c = 0; c < WC; ++c) {
-                        const i32x4 lo = *(const i32x4 *)(sb + (b_base[c] ^ (ks << 5)));
-                        bf[c] = i32x8{lo[0], lo[1], lo[2], lo[3], 0, 0, 0, 0};
-                    }
-#pragma unroll
-                    for (int b = 0; b < WR; ++b)
-#pragma unroll
-                        for (int c = 0; c < WC; ++c)
-                            acc[b][c] = mfma_fp4(af[b], bf[c], acc[b][c]);
                 }
             } else {
 #pragma unroll
