@@ -1065,34 +1065,42 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
                 // becomes four dwords of FP4 codes, dword jd = bits 3 - jd of every nibble:
                 // ((w << jd) & 0x88888888) | 0x22222222 -> 0x2 = +1.0, 0xA = -1.0.  The pre-expanded
                 // validation rows follow the same order and are zero past the end of the vectors.
+                // The validation fragments of K step ks + 1 and the train words of the next four steps are
+                // requested before the matrix instructions of step ks (scheduling barriers keep that
+                // order), so a wave waits for LDS once per stage instead of once per step.
+                i32x4 wq[KE / 256][WR], bq[WC], bn[WC];
 #pragma unroll
-                for (int q = 0; q < KE / 256; ++q) {
-                    i32x4 wq[WR];
+                for (int b = 0; b < WR; ++b) wq[0][b] = *(const i32x4 *)(sb + a_base[b]);
 #pragma unroll
-                    for (int b = 0; b < WR; ++b) wq[b] = *(const i32x4 *)(sb + (a_base[b] ^ (q << 5)));
+                for (int c = 0; c < WC; ++c) bq[c] = *(const i32x4 *)(sb + b_base[c]);
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int ks = 4 * q + j;
-                        i32x8 af[WR], bf[WC];
+                for (int ks = 0; ks < KE / 64; ++ks) {
+                    const int q = ks >> 2, j = ks & 3;
+                    if (ks + 1 < KE / 64) {
 #pragma unroll
-                        for (int b = 0; b < WR; ++b) {
-                            const unsigned int wd = (unsigned int)wq[b][j];
-#pragma unroll
-                            for (int jd = 0; jd < 4; ++jd) af[b][jd] = (int)sign_bits_or(wd << jd, ones);
-#pragma unroll
-                            for (int jd = 4; jd < 8; ++jd) af[b][jd] = 0;
-                        }
-#pragma unroll
-                        for (int c = 0; c < WC; ++c) {
-                            const i32x4 lo = *(const i32x4 *)(sb + (b_base[c] ^ (ks << 5)));
-                            bf[c] = i32x8{lo[0], lo[1], lo[2], lo[3], 0, 0, 0, 0};
-                        }
-#pragma unroll
-                        for (int b = 0; b < WR; ++b)
-#pragma unroll
-                            for (int c = 0; c < WC; ++c)
-                                acc[b][c] = mfma_fp4(af[b], bf[c], acc[b][c]);
+                        for (int c = 0; c < WC; ++c) bn[c] = *(const i32x4 *)(sb + (b_base[c] ^ ((ks + 1) << 5)));
                     }
+                    if (j == 1 && q + 1 < KE / 256) {
+#pragma unroll
+                        for (int b = 0; b < WR; ++b) wq[q + 1][b] = *(const i32x4 *)(sb + (a_base[b] ^ ((q + 1) << 5)));
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    i32x8 af[WR], bf[WC];
+#pragma unroll
+                    for (int c = 0; c < WC; ++c) bf[c] = i32x8{bq[c][0], bq[c][1], bq[c][2], bq[c][3], 0, 0, 0, 0};
+#pragma unroll
+                    for (int b = 0; b < WR; ++b) {
+                        const unsigned int wd = (unsigned int)wq[q][b][j];
+#pragma unroll
+                        for (int jd = 0; jd < 4; ++jd) af[b][jd] = (int)sign_bits_or(wd << jd, ones);
+#pragma unroll
+                        for (int jd = 4; jd < 8; ++jd) af[b][jd] = 0;
+#pragma unroll
+                        for (int c = 0; c < WC; ++c) acc[b][c] = mfma_fp4(af[b], bf[c], acc[b][c]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int c = 0; c < WC; ++c) bq[c] = bn[c];
                 }
             } else if constexpr (BITS == 1) {
                 // few validation vectors: both operands are packed rows, read as 4-byte words (K step ks:
