@@ -1172,6 +1172,52 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
                                 acc[b][c] = mfma_fp4(af[b], bf[c], acc[b][c]);
                     }
                 }
+            } else if constexpr (!Sh::NARROW) {
+                // int8 (or bfloat16) operands, wide tiles: the fragments of K step ks + 1 are requested before the
+                // matrix instructions of step ks (scheduling barriers keep that order)
+                i32x4 aq[WR], bq[WC], an[WR], bn[WC];
+                auto load_step = [&](int ks, i32x4 (&fa)[WR], i32x4 (&fb)[WC]) {
+#pragma unroll
+                    for (int b = 0; b < WR; ++b) {
+                        if (BITS == 8) {
+                            fa[b] = *(const i32x4 *)(sb + (a_base[b] ^ (ks << 5)));
+                        } else {
+                            const uint2 pa = *(const uint2 *)(sb + (a_base[b] ^ (ks << 4)));
+                            fa[b] = i32x4{(int)pa.x, (int)pa.y, 0, 0};
+                        }
+                    }
+#pragma unroll
+                    for (int c = 0; c < WC; ++c) fb[c] = *(const i32x4 *)(sb + (b_base[c] ^ (ks << 5)));
+                };
+                load_step(0, aq, bq);
+#pragma unroll
+                for (int ks = 0; ks < KE / 32; ++ks) {
+                    if (ks + 1 < KE / 32) load_step(ks + 1, an, bn);
+                    __builtin_amdgcn_sched_barrier(0);
+                    i32x4 af[WR];
+#pragma unroll
+                    for (int b = 0; b < WR; ++b) {
+                        if (BITS == 8) {
+                            af[b] = aq[b];
+                        } else {
+                            const unsigned int px = (unsigned int)aq[b][0], py = (unsigned int)aq[b][1];
+                            af[b][0] = (int)((px << 4) & 0xF0F0F0F0u); af[b][1] = (int)(px & 0xF0F0F0F0u);
+                            af[b][2] = (int)((py << 4) & 0xF0F0F0F0u); af[b][3] = (int)(py & 0xF0F0F0F0u);
+                        }
+                    }
+#pragma unroll
+                    for (int b = 0; b < WR; ++b)
+#pragma unroll
+                        for (int c = 0; c < WC; ++c)
+                            acc[b][c] = mfma_step<F16>(af[b], bq[c], acc[b][c]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (ks + 1 < KE / 32) {
+#pragma unroll
+                        for (int b = 0; b < WR; ++b) aq[b] = an[b];
+#pragma unroll
+                        for (int c = 0; c < WC; ++c) bq[c] = bn[c];
+                    }
+                }
             } else {
 #pragma unroll
                 for (int ks = 0; ks < KE / 32; ++ks) {
