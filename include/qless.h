@@ -138,8 +138,11 @@ qless_status qless_project_quantize(const void *G, qless_dtype dt, int64_t n, in
  *   full       device, N x M fp32 row-major receiving acc, or NULL (at least one of the two)
  *   ws         device workspace, 16-byte aligned, of at least qless_score_workspace(N, M, k, bits, C)
  *              bytes (0 for the configurations that need none).  It holds the validation codes
- *              expanded to int8 for the matrix-core path and the running row maxima.
- * N == 0 is valid; M >= 1.
+ *              expanded for the tiled matrix-core path and the running row maxima; the paths that
+ *              stream the train codes once (bit-plane codes, few validation vectors) leave it untouched.
+ * N == 0 is valid; M >= 1.  Whichever kernels a shape selects, the results are the same bits.  With
+ * more than 64 validation vectors a call may consist of several launches that update score in
+ * place: score and full are complete once the stream has run the whole call.
  * ------------------------------------------------------------------------------------------- */
 size_t qless_score_workspace(int64_t N, int32_t M, int32_t k, int bits, int C);
 qless_status qless_score(const void *const *train_codes, const float *const *train_rnorm,

@@ -15,6 +15,7 @@
 // of +-1.0 for K-step s; V_CVT_SCALEF32_PK_BF16_FP4 expands them to packed bf16 +-1.0, two
 // elements per instruction.
 #include "common.h"
+#include <atomic>
 
 namespace qless {
 
@@ -393,7 +394,7 @@ static qless_status project_partials(const void *G, qless_dtype dt, int64_t n, i
     dim3 grid((unsigned)plan.grid), block(kWaves * 64);
     // more than 64 KB of dynamic LDS has to be allowed per kernel (host-side attribute, no device work)
 #define QLESS_LAUNCH(F32, AL, GA, DI) do { \
-        static bool once = false; \
+        static std::atomic<bool> once{false}; \
         if (!once) { \
             if (hipFuncSetAttribute((const void *)project_kernel<F32, AL, GA, DI>, \
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \

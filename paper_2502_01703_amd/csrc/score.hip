@@ -19,6 +19,7 @@
 // tiles with the running row maximum in registers; the MFMA kernel gives every (train tile, val
 // tile) pair its own workgroup and combines the row maxima with an exact integer atomicMax.
 #include "common.h"
+#include <atomic>
 
 namespace qless {
 
@@ -1339,7 +1340,7 @@ static qless_status launch_mfma_shape(const ScoreArgs &a, const ScorePrep &w, in
         const size_t share = ((size_t)kLdsPerCU / per_cu - kStaticLds) & ~(size_t)511;
         if (share > lds) lds = share;
     }
-    static size_t allowed = 0;
+    static std::atomic<size_t> allowed{0};            // two host threads may race here: both then set the attribute
     if (lds > allowed) {
         if (hipFuncSetAttribute((const void *)score_mfma_kernel<BITS, WR, WC, WX, NW, F16>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
@@ -1426,7 +1427,7 @@ static StreamMfmaPlan stream_mfma_plan(int32_t M, int32_t k, int bits, int C) {
 }
 static qless_status launch_stream_mfma(const ScoreArgs &a, int bits, const StreamMfmaPlan &sp, hipStream_t st) {
     constexpr int NW = kStreamWaves;
-    static bool allowed = false;                                     // LDS above 64 KB has to be allowed per kernel
+    static std::atomic<bool> allowed{false};                         // LDS above 64 KB has to be allowed per kernel
     if (!allowed) {
         const void *fns[4] = {(const void *)score_stream_mfma_kernel<1, 8, NW, 2>, (const void *)score_stream_mfma_kernel<1, 16, NW, 2>,
                               (const void *)score_stream_mfma_kernel<2, 8, NW, 1>, (const void *)score_stream_mfma_kernel<2, 16, NW, 1>};
@@ -1474,7 +1475,7 @@ static Stream32Plan stream_mfma32_plan(int vb, int32_t k, int C) {
 }
 static qless_status launch_stream_mfma32(const ScoreArgs &a, hipStream_t st) {
     constexpr int NW = kStream32Waves;
-    static bool allowed = false;                                     // LDS above 64 KB has to be allowed per kernel
+    static std::atomic<bool> allowed{false};                         // LDS above 64 KB has to be allowed per kernel
     if (!allowed) {
         const void *fns[2] = {(const void *)score_stream_mfma32_kernel<1>, (const void *)score_stream_mfma32_kernel<2>};
         for (const void *f : fns)
