@@ -1327,8 +1327,9 @@ static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int bits, int C) {
     return p;
 }
 // The bit planes are copied in 16-byte chunks: k must be a multiple of 128 for the 1-/2-bit codes.
-// With at most 8 validation vectors those codes are bandwidth-bound and their 16-byte stages are
-// too fine for the copy pipeline; the popcount streaming kernel serves them.
+// With at most 8 validation vectors those codes never take this path (and never need its
+// workspace): the streaming kernel serves them, or the popcount kernel if their validation codes
+// do not fit in LDS.
 static bool use_mfma_path(int bits, int32_t M, int32_t k) { return bits >= 4 || (k % 128 == 0 && M > kStreamVal); }
 
 // per_cu > 0 asks for exactly that many workgroups per compute unit (by padding the LDS request).
