@@ -138,17 +138,25 @@ __device__ inline void cmpswap_desc(unsigned long long &x, unsigned long long &y
     if ((x < y) == desc) { const unsigned long long t = x; x = y; y = t; }
 }
 
-// all steps with jj < kSortBlock for stages kk_from..kk_to inside LDS
+// all steps with jj < kSortBlock for stages kk_from..kk_to inside LDS.  Thread t handles the pairs t
+// and t + 1024 of a step; for a partner distance jj <= 64 both pairs of every thread of a wavefront lie
+// inside two 128-element segments that only this wavefront touches, so consecutive steps with
+// jj <= 64 need no workgroup barrier (LDS operations of a wavefront complete in order).
 __global__ void __launch_bounds__(1024)
 topk_bitonic_local_kernel(unsigned long long *data, int64_t kk_from, int64_t kk_to) {
     __shared__ unsigned long long s[kSortBlock];
     const int64_t base = (int64_t)blockIdx.x * kSortBlock;
     for (int t = threadIdx.x; t < kSortBlock; t += 1024) s[t] = data[base + t];
     __syncthreads();
+    bool wide_before = true;                           // the previous step crossed wavefront segments
     for (int64_t kk = kk_from; kk <= kk_to; kk <<= 1) {
         int64_t jj = kk >> 1;
         if (jj >= kSortBlock) jj = kSortBlock >> 1;
         for (; jj > 0; jj >>= 1) {
+            const bool wide = jj > 64;
+            if (wide || wide_before) __syncthreads();
+            else { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); __builtin_amdgcn_wave_barrier(); }
+            wide_before = wide;
             for (int t = threadIdx.x; t < kSortBlock / 2; t += 1024) {
                 const int lo = (int)(((int64_t)t / jj) * 2 * jj + ((int64_t)t % jj));
                 const int hi = lo + (int)jj;
@@ -157,9 +165,9 @@ topk_bitonic_local_kernel(unsigned long long *data, int64_t kk_from, int64_t kk_
                 cmpswap_desc(x, y, desc);
                 s[lo] = x; s[hi] = y;
             }
-            __syncthreads();
         }
     }
+    __syncthreads();
     for (int t = threadIdx.x; t < kSortBlock; t += 1024) data[base + t] = s[t];
 }
 
