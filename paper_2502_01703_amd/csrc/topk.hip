@@ -3,22 +3,25 @@
 //
 // Every example gets a 64-bit key  (order-preserving image of the fp32 score) << 32 | (2^32-1 - index);
 // keys are distinct and "larger key" is exactly "selected earlier".  Steps:
-//   1. build keys;  2. radix-select the k_sel-th largest key, up to 8 passes of 8 bits (histogram +
-//   one-workgroup digit pick); the passes turn into empty launches as soon as the bucket that
-//   holds the k_sel-th key is selected as a whole (without ties at the threshold that is after
-//   the four digits of the score);  3. compact all keys >= threshold (exactly k_sel of them; one
-//   atomic per wavefront);
-//   4. sort them descending with a bitonic network (LDS for spans up to 4096, global steps
-//   above);  5. decode indices and gather the scores.
+//   1. radix-select the k_sel-th largest key, up to 8 passes of 8 bits (keys are formed on the fly
+//   from the scores); the passes stop as soon as the bucket that holds the k_sel-th key is selected
+//   as a whole (without ties at the threshold that is after the four digits of the score).  Up to
+//   32768 scores one workgroup does all passes in a single launch (a launch costs more than such a
+//   pass; beyond that size the ~50 instructions per key and pass are too many for one compute
+//   unit); above that, a histogram launch and a one-workgroup digit pick per pass;  2. compact all keys >= threshold (exactly k_sel of them; one atomic per
+//   wavefront);
+//   3. sort them descending with a bitonic network (LDS for spans up to 4096, global steps
+//   above);  4. decode indices and gather the scores.
 #include "common.h"
 
 namespace qless {
 
 constexpr int kSortBlock = 4096;   // keys sorted per workgroup in LDS (32 KB)
+constexpr int64_t kSelectSmallMax = 32768;   // scores one workgroup selects from in a single launch
 
 struct TopkPlan {
     int64_t padded;                // power of two >= k_sel (>= kSortBlock)
-    size_t off_keys, off_sel, off_hist, off_state, total;
+    size_t off_sel, off_hist, off_state, total;
 };
 
 static TopkPlan topk_plan(int64_t N, int64_t k_sel) {
@@ -27,7 +30,6 @@ static TopkPlan topk_plan(int64_t N, int64_t k_sel) {
     while (pad < k_sel) pad <<= 1;
     p.padded = pad;
     size_t o = 0;
-    p.off_keys = o;  o += (size_t)(N > 0 ? N : 1) * 8;
     p.off_sel = o;   o += (size_t)pad * 8;
     p.off_hist = o;  o += 256 * 4;
     p.off_state = o; o += 64;
@@ -48,18 +50,106 @@ __device__ inline uint32_t order_key(float f) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-__global__ void topk_keys_kernel(const float *score, int64_t N, unsigned long long *keys,
-                                 unsigned int *hist, SelectState *state, unsigned long long k_sel) {
-    const int64_t i0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i0 == 0) { state->prefix = 0; state->remaining = k_sel; state->count = 0; state->done = 0; }
-    if (i0 < 256) hist[i0] = 0;
-    for (int64_t i = i0; i < N; i += (int64_t)gridDim.x * blockDim.x)
-        keys[i] = ((unsigned long long)order_key(score[i]) << 32) | (0xFFFFFFFFull - (unsigned long long)i);
+__device__ inline unsigned long long make_key(float sc, int64_t i) {
+    return ((unsigned long long)order_key(sc) << 32) | (0xFFFFFFFFull - (unsigned long long)i);
+}
+
+__global__ void __launch_bounds__(256) topk_init_kernel(unsigned int *hist, SelectState *state, unsigned long long k_sel) {
+    if (threadIdx.x == 0) { state->prefix = 0; state->remaining = k_sel; state->count = 0; state->done = 0; }
+    hist[threadIdx.x] = 0;
+}
+
+// Suffix sums over 256 bins and the digit that holds the remaining rank `rem` (walking from the top):
+// thread d < 256 passes its bin count; the thread of the chosen digit returns true, with the rank
+// left inside that bin in `left`.  `above` is LDS scratch of 257 entries.  All threads of the
+// workgroup call it (barriers inside).
+__device__ inline bool pick_digit(unsigned long long *above, unsigned int mine, unsigned long long rem,
+                                  unsigned long long &left) {
+    const int d = (int)threadIdx.x;
+    if (d < 256) above[d] = mine;
+    if (d == 0) above[256] = 0;
+    __syncthreads();
+    for (int step = 1; step < 256; step <<= 1) {    // Hillis-Steele
+        const unsigned long long add = (d < 256 && d + step < 256) ? above[d + step] : 0ull;
+        __syncthreads();
+        if (d < 256) above[d] += add;
+        __syncthreads();
+    }
+    // the digit is the largest d with above[d] >= rem; if no bin reaches the rank it is 0
+    bool here = false;
+    if (d < 256) {
+        here = (above[d] >= rem && above[d + 1] < rem) || (d == 0 && above[0] < rem);
+        if (here) left = rem - above[d + 1];
+    }
+    return here;
+}
+
+// All passes of the selection in one workgroup (small N).  A wavefront adds the digit of its first
+// matching lane once for all lanes that share it (the leading digits of scores are few), the other
+// lanes add their own.
+__global__ void __launch_bounds__(1024)
+topk_select_small_kernel(const float *score, int64_t N, unsigned long long k_sel, SelectState *state) {
+    __shared__ unsigned int h[256];
+    __shared__ unsigned long long above[257];
+    __shared__ unsigned long long sh_prefix, sh_rem;
+    __shared__ int sh_done;
+    const int lane = threadIdx.x & 63;
+    unsigned long long prefix = 0, rem = k_sel;
+    constexpr int kU = 8;
+    const int64_t n_up = (N + 1024 * kU - 1) / (1024 * kU) * (1024 * kU);
+    for (int pass = 0; pass < 8; ++pass) {
+        if (threadIdx.x < 256) h[threadIdx.x] = 0;
+        if (threadIdx.x == 0) sh_done = 0;
+        __syncthreads();
+        const int shift = 56 - 8 * pass;
+        const unsigned long long himask = pass == 0 ? 0ull : (~0ull << (shift + 8));
+        for (int64_t base = 0; base < n_up; base += 1024 * kU) {  // same trip count for all lanes
+            float v[kU];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {                         // kU loads in flight per thread
+                const int64_t i = base + u * 1024 + threadIdx.x;
+                v[u] = i < N ? score[i] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                const int64_t i = base + u * 1024 + threadIdx.x;
+                bool match = false;
+                unsigned int d = 0;
+                if (i < N) {
+                    const unsigned long long key = make_key(v[u], i);
+                    match = ((key ^ prefix) & himask) == 0;
+                    d = (unsigned int)(key >> shift) & 0xFFu;
+                }
+                const unsigned long long act = __ballot(match);
+                if (act) {
+                    const int leader = __ffsll((long long)act) - 1;
+                    const unsigned int d0 = (unsigned int)__builtin_amdgcn_readlane((int)d, leader);
+                    const unsigned long long same = __ballot(match && d == d0);
+                    if (lane == leader) atomicAdd(&h[d0], (unsigned int)__popcll(same));
+                    if (match && d != d0) atomicAdd(&h[d], 1u);
+                }
+            }
+        }
+        __syncthreads();
+        const unsigned int mine = threadIdx.x < 256 ? h[threadIdx.x] : 0u;
+        unsigned long long left = 0;
+        if (pick_digit(above, mine, rem, left)) {
+            sh_prefix = prefix | ((unsigned long long)threadIdx.x << shift);
+            sh_rem = left;
+            sh_done = left == (unsigned long long)mine;             // the whole bucket is selected
+        }
+        __syncthreads();
+        prefix = sh_prefix; rem = sh_rem;
+        const int done = sh_done;
+        __syncthreads();
+        if (done) break;
+    }
+    if (threadIdx.x == 0) { state->prefix = prefix; state->remaining = rem; state->count = 0; state->done = 1; }
 }
 
 // histogram of digit `pass` (0 = most significant byte) over keys whose higher digits equal prefix
 __global__ void __launch_bounds__(256)
-topk_hist_kernel(const unsigned long long *keys, int64_t N, int pass, const SelectState *state,
+topk_hist_kernel(const float *score, int64_t N, int pass, const SelectState *state,
                  unsigned int *hist) {
     __shared__ unsigned int h[256];
     if (state->done) return;                        // uniform: written by an earlier launch
@@ -71,7 +161,7 @@ topk_hist_kernel(const unsigned long long *keys, int64_t N, int pass, const Sele
     const unsigned long long himask = pass == 0 ? 0ull : (~0ull << (shift + 8));
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N;
          i += (int64_t)gridDim.x * blockDim.x) {
-        const unsigned long long key = keys[i];
+        const unsigned long long key = make_key(score[i], i);
         const bool match = ((key ^ prefix) & himask) == 0;
         if (match) atomicAdd(&h[(key >> shift) & 0xFF], 1u);
     }
@@ -86,22 +176,9 @@ topk_pick_kernel(int pass, SelectState *state, unsigned int *hist) {
     if (state->done) return;
     const unsigned int mine = hist[threadIdx.x];
     hist[threadIdx.x] = 0;                          // ready for the next pass
-    above[threadIdx.x] = mine;
-    if (threadIdx.x == 0) above[256] = 0;
-    __syncthreads();
-    for (int step = 1; step < 256; step <<= 1) {    // suffix sums over the 256 bins (Hillis-Steele)
-        const unsigned long long add = threadIdx.x + step < 256 ? above[threadIdx.x + step] : 0ull;
-        __syncthreads();
-        above[threadIdx.x] += add;
-        __syncthreads();
-    }
-    const unsigned long long rem = state->remaining;
-    const int d = (int)threadIdx.x;
-    // the digit is the largest d with above[d] >= rem; if no bin reaches the rank it is 0
-    const bool here = (above[d] >= rem && above[d + 1] < rem) || (d == 0 && above[0] < rem);
-    if (here) {
-        const unsigned long long left = rem - above[d + 1];
-        state->prefix |= (unsigned long long)d << (56 - 8 * pass);
+    unsigned long long left = 0;
+    if (pick_digit(above, mine, state->remaining, left)) {
+        state->prefix |= (unsigned long long)threadIdx.x << (56 - 8 * pass);
         state->remaining = left;
         // the whole bucket is selected: the prefix with zeros below is the threshold
         if (left == (unsigned long long)mine) state->done = 1;
@@ -110,7 +187,7 @@ topk_pick_kernel(int pass, SelectState *state, unsigned int *hist) {
 
 // Keys >= threshold (exactly k_sel of them) are gathered in any order; the slots from k_sel to
 // padded are cleared.  One atomic per wavefront: its selected lanes take consecutive positions.
-__global__ void topk_compact_kernel(const unsigned long long *keys, int64_t N, SelectState *state,
+__global__ void topk_compact_kernel(const float *score, int64_t N, SelectState *state,
                                     unsigned long long *sel, int64_t k_sel, int64_t padded) {
     const unsigned long long thr = state->prefix;
     const int lane = threadIdx.x & 63;
@@ -120,7 +197,7 @@ __global__ void topk_compact_kernel(const unsigned long long *keys, int64_t N, S
         if (i >= k_sel && i < padded) sel[i] = 0;   // padding sorts last (real keys are > 0)
         unsigned long long key = 0;
         bool take = false;
-        if (i < N) { key = keys[i]; take = key >= thr; }
+        if (i < N) { key = make_key(score[i], i); take = key >= thr; }
         const unsigned long long mask = __ballot(take);
         if (mask) {
             const int leader = __ffsll((long long)mask) - 1;
@@ -212,20 +289,22 @@ extern "C" qless_status qless_topk(const float *score, int64_t N, int64_t k_sel,
     if ((uintptr_t)ws % 8) return QLESS_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
     unsigned char *w = (unsigned char *)ws;
-    unsigned long long *keys = (unsigned long long *)(w + p.off_keys);
     unsigned long long *sel = (unsigned long long *)(w + p.off_sel);
     unsigned int *hist = (unsigned int *)(w + p.off_hist);
     SelectState *state = (SelectState *)(w + p.off_state);
 
     auto blocks_for = [](int64_t n) { int64_t b = (n + 255) / 256; if (b < 1) b = 1; if (b > 2048) b = 2048; return (unsigned)b; };
-    hipLaunchKernelGGL(topk_keys_kernel, dim3(blocks_for(N)), dim3(256), 0, st, score, N, keys, hist, state,
-                       (unsigned long long)k_sel);
-    for (int pass = 0; pass < 8; ++pass) {
-        hipLaunchKernelGGL(topk_hist_kernel, dim3(blocks_for(N)), dim3(256), 0, st, keys, N, pass, state, hist);
-        hipLaunchKernelGGL(topk_pick_kernel, dim3(1), dim3(256), 0, st, pass, state, hist);
+    if (N <= kSelectSmallMax) {
+        hipLaunchKernelGGL(topk_select_small_kernel, dim3(1), dim3(1024), 0, st, score, N, (unsigned long long)k_sel, state);
+    } else {
+        hipLaunchKernelGGL(topk_init_kernel, dim3(1), dim3(256), 0, st, hist, state, (unsigned long long)k_sel);
+        for (int pass = 0; pass < 8; ++pass) {
+            hipLaunchKernelGGL(topk_hist_kernel, dim3(blocks_for(N)), dim3(256), 0, st, score, N, pass, state, hist);
+            hipLaunchKernelGGL(topk_pick_kernel, dim3(1), dim3(256), 0, st, pass, state, hist);
+        }
     }
     const int64_t span = N > p.padded ? N : p.padded;
-    hipLaunchKernelGGL(topk_compact_kernel, dim3(blocks_for(span)), dim3(256), 0, st, keys, N, state, sel, k_sel, p.padded);
+    hipLaunchKernelGGL(topk_compact_kernel, dim3(blocks_for(span)), dim3(256), 0, st, score, N, state, sel, k_sel, p.padded);
     // sort the selected keys, descending
     const unsigned nblk = (unsigned)(p.padded / kSortBlock);
     hipLaunchKernelGGL(topk_bitonic_local_kernel, dim3(nblk), dim3(1024), 0, st, sel, (int64_t)2, (int64_t)kSortBlock);

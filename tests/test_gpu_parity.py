@@ -287,7 +287,7 @@ def test_score16_matches_oracle_from_the_same_store(N, M, k, C):
 
 
 @pytest.mark.parametrize("N,k_sel", [(1000, 50), (100000, 5000), (100000, 20000), (5000, 5000),
-                                     (4097, 4097), (7, 0), (1, 1), (270000, 13500)])
+                                     (4097, 4097), (7, 0), (1, 1), (270000, 13500), (1048576, 9), (1300000, 70000)])
 def test_topk_identical_with_ties(N, k_sel):
     _say("topk N=%d k_sel=%d" % (N, k_sel))
     rng = np.random.default_rng(N + k_sel)
@@ -300,7 +300,7 @@ def test_topk_identical_with_ties(N, k_sel):
     np.testing.assert_array_equal(val.cpu().numpy().view(np.uint32), ref_v.view(np.uint32))
 
 
-@pytest.mark.parametrize("N,k_sel", [(270000, 13500), (100000, 1), (4096, 4096), (70000, 33000), (1, 1)])
+@pytest.mark.parametrize("N,k_sel", [(270000, 13500), (100000, 1), (4096, 4096), (70000, 33000), (1, 1), (1048577, 5000)])
 def test_topk_identical_without_ties(N, k_sel):
     """Distinct scores (the selection can stop after the digits of the score) and a few equal ones."""
     _say("topk distinct N=%d k_sel=%d" % (N, k_sel))
