@@ -1,4 +1,4 @@
-"""Parity at the benchmark's full sizes, in the launch configurations bench.py times.  The oracle
+"""Parity at the full sizes of the benchmark configurations, in the launch configurations bench.py times.  The oracle
 cannot run these sizes end to end, so it computes sampled outputs one by one (each projected
 coordinate, each code row and each train row's scores are independent of the others) and the
 tests add properties that hold at any size (determinism, planted recovery, exact top-k of the
