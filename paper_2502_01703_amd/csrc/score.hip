@@ -875,11 +875,16 @@ score_stream_mfma32_kernel(ScoreArgs a, int32_t m0, int32_t mc, int64_t rb_each,
 // tile width VT = 32 WC WX:
 //   M > 64: <2, 2, 2, 8> (64 x 64 per wave, 256 x 128 per workgroup);  M <= 64: <1, 2, 1, 8> (256 x 64);
 //   M <= 32: <1, 1, 1, 8> (256 x 32) or <1, 1, 1, 4> (128 x 32), whichever fills the chip more evenly.
-template <int BITS, int WR, int WC, int WX, int NW>
+template <int BITS, int WR, int WC, int WX, int NW, bool VH = false>
 struct MfmaShape {
     static constexpr int WY = NW / WX;
     static constexpr int MT = 32 * WR * WY;
     static constexpr int VT = 32 * WC * WX;
+    // VH (one 32-wide val block, at most 16 validation vectors): only 16 validation rows are staged
+    // (lanes 16..31 of the val operand re-read them; their results are masked), which leaves room for
+    // one more workgroup per compute unit
+    static constexpr int VROWS = VH ? 16 : VT;
+    static_assert(!VH || (WC == 1 && WX == 1), "half val tiles exist for the 32-wide shape only");
     // Code elements per stage: a stage should bring 128 bytes of every train row (whole cache lines
     // when the codes are streamed from HBM) as far as the expanded validation rows leave room in LDS:
     // the shapes for few validation vectors take 256 elements (4- and 2-bit) or 512 (1-bit).
@@ -895,8 +900,8 @@ struct MfmaShape {
     static constexpr int VCPR = VROWB / 16;              // 16-byte chunks per expanded val row
     // rows whose chunks share a bank group are 16 / CPR apart: the swizzle key is (row >> SH) % CPR
     static constexpr int TSH = log2c(16 / TCPR), VSH = log2c(16 / VCPR);
-    static constexpr int TRAIN_BYTES = MT * TB, VAL_BYTES = VT * VROWB;
-    static constexpr int TCH = MT * TCPR, VCH = VT * VCPR;
+    static constexpr int TRAIN_BYTES = MT * TB, VAL_BYTES = VROWS * VROWB;
+    static constexpr int TCH = MT * TCPR, VCH = VROWS * VCPR;
     static constexpr int NINST = (TCH + VCH) / 64;       // wavefront-wide copies per stage
     static constexpr int LPW = (NINST + NW - 1) / NW;    // per wave
     static constexpr int BUF = TRAIN_BYTES + VAL_BYTES + 1024;   // + 1 KB landing zone for padding copies
@@ -915,11 +920,11 @@ struct MfmaShape {
 // to the matrix core are eight bfloat16 values for v_mfma_f32_32x32x16_bf16 (same bytes, same
 // addresses as the int8 operands), the accumulator is fp32 and the epilogue is acc += eta * D:
 // the 16-bit LESS comparator (Eq.(2),(3)) on pre-normalised rows.
-template <int BITS, int WR, int WC, int WX, int NW, bool F16 = false>
+template <int BITS, int WR, int WC, int WX, int NW, bool F16 = false, bool VH = false>
 __global__ void __launch_bounds__(64 * NW, (WR == 1 ? 4 : 2))
 score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     static_assert(!F16 || BITS == 8, "bfloat16 rows use the byte geometry of the 8-bit codes");
-    using Sh = MfmaShape<BITS, WR, WC, WX, NW>;
+    using Sh = MfmaShape<BITS, WR, WC, WX, NW, VH>;
     constexpr int kMT = Sh::MT;
     constexpr int KE = Sh::KE, TB = Sh::TB, TCPR = Sh::TCPR, VCPR = Sh::VCPR, TSH = Sh::TSH, VSH = Sh::VSH, VT = Sh::VT;
     constexpr int TRAIN_BYTES = Sh::TRAIN_BYTES, VAL_BYTES = Sh::VAL_BYTES, TCH = Sh::TCH;
@@ -1002,8 +1007,9 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     }
 #pragma unroll
     for (int c = 0; c < WC; ++c) {
-        const int Rv = vcol + 32 * c + l32;
-        const int sw = (l32 >> VSH) & (VCPR - 1);
+        const int lv = VH ? (l32 & 15) : l32;           // row of the staged val tile this lane reads
+        const int Rv = vcol + 32 * c + lv;
+        const int sw = (lv >> VSH) & (VCPR - 1);
         if (Sh::VPACKED) b_base[c] = TRAIN_BYTES + Rv * Sh::VROWB + sw * 16 + half * 4;  // 4-byte reads, chunk chosen by XOR
         else b_base[c] = TRAIN_BYTES + Rv * Sh::VROWB + (sw >> 1) * 32 + ((half ^ (sw & 1)) * 16);
     }
@@ -1333,9 +1339,9 @@ static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int bits, int C) {
 static bool use_mfma_path(int bits, int32_t M, int32_t k) { return bits >= 4 || (k % 128 == 0 && M > kStreamVal); }
 
 // per_cu > 0 asks for exactly that many workgroups per compute unit (by padding the LDS request).
-template <int BITS, int WR, int WC, int WX, int NW, bool F16 = false>
+template <int BITS, int WR, int WC, int WX, int NW, bool F16 = false, bool VH = false>
 static qless_status launch_mfma_shape(const ScoreArgs &a, const ScorePrep &w, int per_cu, hipStream_t st) {
-    using Sh = MfmaShape<BITS, WR, WC, WX, NW>;
+    using Sh = MfmaShape<BITS, WR, WC, WX, NW, VH>;
     size_t lds = (size_t)Sh::NBUF * Sh::BUF;
     if (per_cu > 0) {
         const size_t share = ((size_t)kLdsPerCU / per_cu - kStaticLds) & ~(size_t)511;
@@ -1343,7 +1349,7 @@ static qless_status launch_mfma_shape(const ScoreArgs &a, const ScorePrep &w, in
     }
     static std::atomic<size_t> allowed{0};            // two host threads may race here: both then set the attribute
     if (lds > allowed) {
-        if (hipFuncSetAttribute((const void *)score_mfma_kernel<BITS, WR, WC, WX, NW, F16>,
+        if (hipFuncSetAttribute((const void *)score_mfma_kernel<BITS, WR, WC, WX, NW, F16, VH>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return QLESS_ERR_DEVICE;
         allowed = lds;
@@ -1352,7 +1358,7 @@ static qless_status launch_mfma_shape(const ScoreArgs &a, const ScorePrep &w, in
     const int vtiles = w.Mp / Sh::VT;
     const int64_t grid = 8 * (int64_t)vtiles * ((ttiles + 7) / 8);
     if (grid > 0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((score_mfma_kernel<BITS, WR, WC, WX, NW, F16>), dim3((unsigned)grid), dim3(64 * NW), lds, st, a, w,
+    hipLaunchKernelGGL((score_mfma_kernel<BITS, WR, WC, WX, NW, F16, VH>), dim3((unsigned)grid), dim3(64 * NW), lds, st, a, w,
                        (int)ttiles, vtiles);
     return QLESS_OK;
 }
@@ -1361,14 +1367,14 @@ static qless_status launch_mfma_shape(const ScoreArgs &a, const ScorePrep &w, in
 // takes ceil(tiles / slots) rounds of equal length.  Pick the tile height (256 or 128 rows) and the
 // number of workgroups per compute unit whose last round is fullest.
 struct NarrowChoice { int nw, per_cu; };
-template <int BITS, int WC>
+template <int BITS, int WC, bool VH = false>
 static NarrowChoice choose_narrow(int64_t N) {
     const int cus = compute_units();
     NarrowChoice best{8, 2};
     double best_eff = -1.0;
     for (int nw = 8; nw >= 4; nw -= 4) {
-        const size_t need = nw == 8 ? (size_t)MfmaShape<BITS, 1, WC, 1, 8>::NBUF * MfmaShape<BITS, 1, WC, 1, 8>::BUF
-                                    : (size_t)MfmaShape<BITS, 1, WC, 1, 4>::NBUF * MfmaShape<BITS, 1, WC, 1, 4>::BUF;
+        const size_t need = nw == 8 ? (size_t)MfmaShape<BITS, 1, WC, 1, 8, VH>::NBUF * MfmaShape<BITS, 1, WC, 1, 8, VH>::BUF
+                                    : (size_t)MfmaShape<BITS, 1, WC, 1, 4, VH>::NBUF * MfmaShape<BITS, 1, WC, 1, 4, VH>::BUF;
         const int64_t tiles = (N + 32 * nw - 1) / (32 * nw);
         int cap = (int)(kLdsPerCU / (need + kStaticLds));
         if (cap > 16 / nw) cap = 16 / nw;                 // at most 16 wavefronts per compute unit
@@ -1398,6 +1404,11 @@ static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st) {
         const NarrowChoice c = choose_narrow<BITS, 2>(a.N);
         if (c.nw == 8) rc = launch_mfma_shape<BITS, 1, 2, 1, 8, F16>(a, w, c.per_cu, st);
         else rc = launch_mfma_shape<BITS, 1, 2, 1, 4, F16>(a, w, c.per_cu, st);
+    } else if ((BITS == 2 || BITS == 4) && a.M <= 16) {
+        // the expanded validation rows of these widths are large next to the train rows of a stage
+        const NarrowChoice c = choose_narrow<BITS, 1, true>(a.N);
+        if (c.nw == 8) rc = launch_mfma_shape<BITS, 1, 1, 1, 8, F16, true>(a, w, c.per_cu, st);
+        else rc = launch_mfma_shape<BITS, 1, 1, 1, 4, F16, true>(a, w, c.per_cu, st);
     } else {
         const NarrowChoice c = choose_narrow<BITS, 1>(a.N);
         if (c.nw == 8) rc = launch_mfma_shape<BITS, 1, 1, 1, 8, F16>(a, w, c.per_cu, st);
