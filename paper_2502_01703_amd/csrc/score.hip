@@ -709,16 +709,70 @@ __device__ inline void stream32_slice(const unsigned char *sb, const unsigned ch
     }
 }
 
-// VB = 1 or 2 validation blocks of 32 (chunk of mc <= 32 VB vectors starting at m0); wb: window
-// bytes per validation row, a power of two >= 128 that divides k / 8; npass: passes of the longest
-// row range (workgroup-uniform)
-template <int VB>
+// The same slot for 4- or 8-bit codes on the int8 matrix cores (v_mfma_i32_32x32x32_i8, 32 codes per
+// instruction).  8 bits: a lane's 16-byte chunk 2 c + half is one K step of both operands.  4 bits:
+// the chunk holds 32 train codes = two K steps; dwords 2 j, 2 j + 1 are unpacked as 16 q (bytes
+// (w << 4) & 0xF0.. and w & 0xF0..: the even, then the odd nibbles), and the validation rows come
+// int8-expanded in that order from the pre-pass (16 bytes per K step), so the accumulator holds 16 D.
+template <int BITS, int VB, int VR, int NPAN, int NPMAX>
+__device__ inline void stream32_slice_i8(const unsigned char *sb, const unsigned char *vwin, int slice, int wbv,
+                                         int l32, int half, i32x16 (&acc)[NPMAX][VB]) {
+    const int lv = VR < 32 ? (l32 & (VR - 1)) : l32;       // staged validation row of this lane (block 0)
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int chunk = 2 * c + half;
+        i32x4 tw[NPAN];
+#pragma unroll
+        for (int p = 0; p < NPAN; ++p) {
+            // the third panel has 16 staged rows: its lanes 16..31 re-read them (masked results)
+            const int r = p == 2 ? 64 + (l32 & 15) : 32 * p + l32, rr = r & 15;
+            tw[p] = *(const i32x4 *)(sb + (r >> 4) * 1024 + rr * 64 + ((chunk ^ ((rr >> 1) & 3)) << 4));
+        }
+        constexpr int STEPS = BITS == 4 ? 2 : 1;            // K steps per chunk
+#pragma unroll
+        for (int j = 0; j < STEPS; ++j) {
+            const int vchunk = (BITS == 4 ? 8 * slice + 2 * chunk + j : 4 * slice + chunk);
+            i32x4 vv[VB];
+#pragma unroll
+            for (int vb = 0; vb < VB; ++vb)
+                vv[vb] = *(const i32x4 *)(vwin + (size_t)(32 * vb + lv) * wbv + ((vchunk ^ (lv & 7)) << 4));
+#pragma unroll
+            for (int p = 0; p < NPAN; ++p) {
+                i32x4 tv;
+                if (BITS == 8) {
+                    tv = tw[p];
+                } else {
+                    const unsigned int px = (unsigned int)tw[p][2 * j], py = (unsigned int)tw[p][2 * j + 1];
+                    tv[0] = (int)((px << 4) & 0xF0F0F0F0u); tv[1] = (int)(px & 0xF0F0F0F0u);
+                    tv[2] = (int)((py << 4) & 0xF0F0F0F0u); tv[3] = (int)(py & 0xF0F0F0F0u);
+                }
+#pragma unroll
+                for (int vb = 0; vb < VB; ++vb) acc[p][vb] = mfma_step<false>(vv[vb], tv, acc[p][vb]);
+            }
+        }
+    }
+}
+
+// BITS = 1 (FP4 products), 4 or 8 (int8 products).  VB = 1 or 2 validation blocks of 32 (chunk of
+// mc <= 32 VB vectors starting at m0); VR validation rows are staged (8, 16 or 32 VB: lanes past VR
+// re-read the staged rows, their results are masked).  wb: train bytes per window, a power of two
+// >= 128 that divides the row; the validation window of the same codes is wbv bytes per row (twice
+// wb for the int8-expanded rows `vexp` of the 4-bit codes, else wb bytes of the codes themselves).
+// npass: passes of the longest row range (workgroup-uniform)
+template <int BITS, int VB, int VR>
 __global__ void __launch_bounds__(64 * kStream32Waves, 2)
-score_stream_mfma32_kernel(ScoreArgs a, int32_t m0, int32_t mc, int64_t rb_each, int64_t rb_extra, int npass,
-                           int wb, int nb, unsigned ring_off) {
+score_stream_mfma32_kernel(ScoreArgs a, const int8_t *vexp, int32_t Mp, int32_t vrow, int32_t m0, int32_t mc,
+                           int64_t rb_each, int64_t rb_extra, int npass, int wb, int nb, unsigned ring_off) {
+    static_assert(VR == 32 * VB || (VB == 1 && (VR == 8 || VR == 16)), "staged validation rows");
     constexpr int NW = kStream32Waves;
-    constexpr int SLOT = 4096;                  // 64 rows x 64 bytes
-    // LDS: 2 x [32 VB][wb] validation windows | [C][32 VB] weights | rings
+    // Rows of a pass: two panels of 32; the int8 shapes with one validation block have registers for
+    // a third panel of 16 rows, which saves a whole pass over K when a wavefront's range is a little
+    // more than two tiles (136 rows of 270 000 on 2048 wavefronts).
+    constexpr int NPMAX = (BITS != 1 && VB == 1) ? 3 : 2;
+    constexpr int PASS = NPMAX == 3 ? 80 : 64;
+    constexpr int NQ = PASS / 16;               // 1 KB copies per slot
+    constexpr int SLOT = NQ * 1024;             // PASS rows x 64 bytes
+    // LDS: 2 x [VR][wbv] validation windows | [C][32 VB] weights | rings
     extern __shared__ __attribute__((aligned(16))) unsigned char vlds[];
     const int lane = threadIdx.x & 63;
     const int cpos = lane & 3, crow = lane >> 2;   // copy role: position and row inside a 1 KB copy
@@ -727,10 +781,11 @@ score_stream_mfma32_kernel(ScoreArgs a, int32_t m0, int32_t mc, int64_t rb_each,
     const int64_t wave = (int64_t)wv_id * gridDim.x + blockIdx.x;
     const int64_t rb0 = wave * rb_each + (wave < rb_extra ? wave : rb_extra);
     const int64_t rb1 = rb0 + rb_each + (wave < rb_extra ? 1 : 0);
-    const int cb = a.k / 8;                     // bytes per row, a multiple of 64 here
+    const int cb = a.k * BITS / 8;              // bytes per row, a multiple of 64 here
     const int nsl = cb / 64;                    // 64-byte slices per row
     const int nwin = cb / wb, spw = wb / 64;    // windows per row, slices per window
-    const int wbytes = 32 * VB * wb;            // one window buffer
+    const int wbv = BITS == 4 ? 2 * wb : wb;    // validation bytes per window row
+    const int wbytes = VR * wbv;                // one window buffer
     float *wlds = (float *)(vlds + (size_t)2 * wbytes);
     unsigned char *ring = vlds + ring_off + (size_t)wv_id * nb * SLOT;
     const unsigned ring_lds = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)ring);
@@ -745,20 +800,20 @@ score_stream_mfma32_kernel(ScoreArgs a, int32_t m0, int32_t mc, int64_t rb_each,
     if (r_end > a.N) r_end = a.N;
     const int64_t r_begin = rb0 * 8;
     const int64_t my_rows = r_end > r_begin ? r_end - r_begin : 0;
-    const int my_pass = (int)((my_rows + 63) / 64);          // passes in which this wavefront has rows
+    const int my_pass = (int)((my_rows + PASS - 1) / PASS);  // passes in which this wavefront has rows
     const int T = a.C * nsl;                                 // ring slots of a pass
     const int S = my_pass * T;                               // ring slots of this wavefront
 
     // ---- train ring: slot s is (pass s / T, checkpoint (s % T) / nsl, slice s % nsl)
     int f_ps = 0, f_ci = 0, f_sl = 0, f_pos = 0, f_it = 0;
     auto fetch = [&]() {
-        const int64_t rp = r_begin + (int64_t)f_ps * 64;
-        const int lastr = (int)(r_end - rp < 64 ? r_end - rp : 64) - 1;
+        const int64_t rp = r_begin + (int64_t)f_ps * PASS;
+        const int lastr = (int)(r_end - rp < PASS ? r_end - rp : PASS) - 1;
         const int off = f_sl * 64 + ((cpos ^ ((crow >> 1) & 3)) << 4);
         const unsigned char *base = a.tc[f_ci] + rp * cb;                   // wave-uniform
         const unsigned slot = ring_lds + (unsigned)f_pos * (unsigned)SLOT;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < NQ; ++q) {
             int rl = q * 16 + crow;
             if (rl > lastr) rl = lastr;                                      // clamped; masked at the output
             global_to_lds16(base, (unsigned)(rl * cb + off), slot + (unsigned)q * 1024u);
@@ -771,7 +826,7 @@ score_stream_mfma32_kernel(ScoreArgs a, int32_t m0, int32_t mc, int64_t rb_each,
     // A window buffer is 32 VB wb / 1024 copies of 1 KB = 1024 / wb rows each; copy q belongs to
     // wavefront q % NW.  Rows past the chunk repeat its last one.
     const int nph = a.C * nwin, G = npass * nph;
-    const int ncopy = wbytes / 1024, lpr = wb / 16;          // copies per window; lanes per row
+    const int ncopy = wbytes / 1024, lpr = wbv / 16;         // copies per window; 16-byte chunks per row
     int v_cnt = 0;                                           // copies of the last request of this wavefront
     int v_at = 0;                                            // ring slots issued before that request
     auto fetch_window = [&](int g) {
@@ -779,10 +834,15 @@ score_stream_mfma32_kernel(ScoreArgs a, int32_t m0, int32_t mc, int64_t rb_each,
         const unsigned buf = vlds_lds + (unsigned)((g & 1) * wbytes);
         v_cnt = 0;
         for (int q = wv_id; q < ncopy; q += NW) {
-            const int row = q * (1024 / wb) + lane / lpr, pos = lane % lpr;
-            const int jc = m0 + (row < mc ? row : mc - 1);
-            const unsigned char *src = a.vc[ci] + (int64_t)jc * cb + win * wb + ((pos ^ (row & 7)) << 4);
-            global_to_lds16(src, buf + (unsigned)q * 1024u);
+            const int g = q * 64 + lane, row = g / lpr, pos = g % lpr;      // chunk `pos` of staged row `row`
+            const unsigned char *src;
+            if (BITS == 4) {        // expanded rows, zero past M
+                src = (const unsigned char *)vexp + ((size_t)ci * Mp + m0 + row) * (size_t)vrow + (size_t)win * wbv;
+            } else {
+                const int jc = m0 + (row < mc ? row : mc - 1);
+                src = a.vc[ci] + (int64_t)jc * cb + (int64_t)win * wb;
+            }
+            global_to_lds16(src + ((pos ^ (row & 7)) << 4), buf + (unsigned)q * 1024u);
             ++v_cnt;
         }
         v_at = f_it;
@@ -792,24 +852,24 @@ score_stream_mfma32_kernel(ScoreArgs a, int32_t m0, int32_t mc, int64_t rb_each,
     for (int i = 0; i < nb - 1 && i < S; ++i) fetch();
     int it = 0, pos = 0;
     for (int ps = 0; ps < npass; ++ps) {                                     // workgroup-uniform counts
-        const int64_t rp = r_begin + (int64_t)ps * 64;
-        const int rows = ps < my_pass ? (r_end - rp < 64 ? (int)(r_end - rp) : 64) : 0;   // wave-uniform
+        const int64_t rp = r_begin + (int64_t)ps * PASS;
+        const int rows = ps < my_pass ? (r_end - rp < PASS ? (int)(r_end - rp) : PASS) : 0;   // wave-uniform
         const int last = rows - 1;
-        f32x16 acc[2][VB];
-        float facc[2][VB][16];
+        typename AccType<BITS == 1>::type acc[NPMAX][VB];
+        float facc[NPMAX][VB][16];
 #pragma unroll
-        for (int p = 0; p < 2; ++p)
+        for (int p = 0; p < NPMAX; ++p)
 #pragma unroll
             for (int vb = 0; vb < VB; ++vb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) { acc[p][vb][v] = 0.0f; facc[p][vb][v] = 0.0f; }
+                for (int v = 0; v < 16; ++v) { acc[p][vb][v] = 0; facc[p][vb][v] = 0.0f; }
         for (int ci = 0; ci < a.C; ++ci) {
             for (int win = 0; win < nwin; ++win) {
                 const int g = (ps * a.C + ci) * nwin + win;
                 // this wavefront's share of window g has landed once at most the ring copies issued
                 // after it are outstanding; the barrier makes every share visible and tells that
                 // all wavefronts are done with window g - 1, whose buffer the next request reuses
-                wait_vmcnt_upto(4 * (f_it - v_at));
+                wait_vmcnt_upto(NQ * (f_it - v_at));
                 __syncthreads();
                 if (g + 1 < G) fetch_window(g + 1);
                 if (rows > 0) {
@@ -817,11 +877,17 @@ score_stream_mfma32_kernel(ScoreArgs a, int32_t m0, int32_t mc, int64_t rb_each,
                     for (int s4 = 0; s4 < spw; ++s4) {
                         // operations issued after this slot's copies: the younger slots and, if it
                         // came later, the last window request
-                        wait_vmcnt_upto(4 * (f_it - 1 - it) + (it < v_at ? v_cnt : 0));
+                        wait_vmcnt_upto(NQ * (f_it - 1 - it) + (it < v_at ? v_cnt : 0));
                         if (f_it < S) fetch();
                         const unsigned char *sb = ring + (size_t)pos * SLOT;
-                        if (rows > 32) stream32_slice<VB, 2>(sb, vwin, 4 * s4, wb, l32, half, ones, acc);
-                        else stream32_slice<VB, 1>(sb, vwin, 4 * s4, wb, l32, half, ones, acc);
+                        if constexpr (BITS == 1) {
+                            if (rows > 32) stream32_slice<VB, 2>(sb, vwin, 4 * s4, wb, l32, half, ones, acc);
+                            else stream32_slice<VB, 1>(sb, vwin, 4 * s4, wb, l32, half, ones, acc);
+                        } else {
+                            if (NPMAX == 3 && rows > 64) stream32_slice_i8<BITS, VB, VR, NPMAX, NPMAX>(sb, vwin, s4, wbv, l32, half, acc);
+                            else if (rows > 32) stream32_slice_i8<BITS, VB, VR, 2, NPMAX>(sb, vwin, s4, wbv, l32, half, acc);
+                            else stream32_slice_i8<BITS, VB, VR, 1, NPMAX>(sb, vwin, s4, wbv, l32, half, acc);
+                        }
                         ++it;
                         if (++pos == nb) pos = 0;
                     }
@@ -831,25 +897,27 @@ score_stream_mfma32_kernel(ScoreArgs a, int32_t m0, int32_t mc, int64_t rb_each,
                 // checkpoint epilogue: accumulator v of lane (train row l32, half) is validation row
                 // 8 (v / 4) + 4 half + v % 4 of its block
 #pragma unroll
-                for (int p = 0; p < 2; ++p) {
-                    if (p == 1 && rows <= 32) continue;
+                for (int p = 0; p < NPMAX; ++p) {
+                    if (32 * p >= rows) continue;                            // wave-uniform
                     const float rt = a.tr[ci][rp + (32 * p + l32 < rows ? 32 * p + l32 : last)];
 #pragma unroll
                     for (int vb = 0; vb < VB; ++vb)
 #pragma unroll
                         for (int v = 0; v < 16; ++v) {
                             const float wv = wlds[ci * 32 * VB + 32 * vb + 8 * (v >> 2) + 4 * half + (v & 3)];
-                            const float t = __fmul_rn(__fmul_rn(acc[p][vb][v], rt), wv);   // acc holds the integer D exactly
+                            // 1-bit: acc holds the integer D exactly in fp32; 4-bit: 16 D (train codes scaled)
+                            const float D = BITS == 1 ? (float)acc[p][vb][v] : (float)(BITS == 4 ? ((int)acc[p][vb][v] >> 4) : (int)acc[p][vb][v]);
+                            const float t = __fmul_rn(__fmul_rn(D, rt), wv);
                             facc[p][vb][v] = __fadd_rn(facc[p][vb][v], t);
-                            acc[p][vb][v] = 0.0f;
+                            acc[p][vb][v] = 0;
                         }
                 }
             }
         }
         if (rows > 0) {
 #pragma unroll
-            for (int p = 0; p < 2; ++p) {
-                if (p == 1 && rows <= 32) continue;
+            for (int p = 0; p < NPMAX; ++p) {
+                if (32 * p >= rows) continue;
                 const bool live = 32 * p + l32 < rows;
                 const int64_t r = rp + 32 * p + l32;
                 float m = neg_inf();
@@ -1463,36 +1531,40 @@ static qless_status launch_stream_mfma(const ScoreArgs &a, int bits, const Strea
     return launch_status();
 }
 
-// LDS plan of score_stream_mfma32_kernel: two validation windows of wb bytes per row, weights,
+// LDS plan of score_stream_mfma32_kernel: two validation windows (vr rows of wbv bytes), weights,
 // 8 rings of nb slots (nb = 0: does not fit).  Narrower windows cost more barriers, deeper rings
 // hide more memory latency: the widest window that leaves room for three slots, else for two.
 #ifndef QLESS_STREAM32_MAX_M
 #define QLESS_STREAM32_MAX_M 320
 #endif
-constexpr int kStream32MaxVal = QLESS_STREAM32_MAX_M;                // beyond this the tile kernel takes over
+constexpr int kStream32MaxVal = QLESS_STREAM32_MAX_M;                // 1-bit: beyond this the tile kernel takes over
 struct Stream32Plan { int wb, nb; size_t val_bytes, lds; };
-static Stream32Plan stream_mfma32_plan(int vb, int32_t k, int C) {
+static Stream32Plan stream_mfma32_plan(int bits, int vb, int vr, int32_t k, int C) {
     Stream32Plan best{};
-    const int cb = k / 8;
+    const int cb = k * bits / 8;
+    const size_t slot = (bits != 1 && vb == 1) ? 5120 : 4096;       // 80 or 64 rows x 64 bytes
     for (int want = 3; want >= 2 && best.nb == 0; --want)
-        for (int wb = 1024; wb >= 128; wb >>= 1) {
+        for (int wb = 2048; wb >= 128; wb >>= 1) {
             if (cb % wb) continue;
-            const size_t val = (((size_t)2 * 32 * vb * wb + (size_t)C * 32 * vb * 4) + 1023) & ~(size_t)1023;
-            if (val + (size_t)kStream32Waves * want * 4096 > kLdsPerCU) continue;
+            const int wbv = bits == 4 ? 2 * wb : wb;
+            const size_t val = (((size_t)2 * vr * wbv + (size_t)C * 32 * vb * 4) + 1023) & ~(size_t)1023;
+            if (val + (size_t)kStream32Waves * want * slot > kLdsPerCU) continue;
             best.wb = wb; best.nb = want; best.val_bytes = val;
-            best.lds = val + (size_t)kStream32Waves * want * 4096;
+            best.lds = val + (size_t)kStream32Waves * want * slot;
             break;
         }
     return best;
 }
-static qless_status launch_stream_mfma32(const ScoreArgs &a, hipStream_t st) {
+static int stream32_rows(int32_t mc) { return mc <= 8 ? 8 : (mc <= 16 ? 16 : (mc <= 32 ? 32 : 64)); }
+
+template <int BITS, int VB, int VR>
+static qless_status launch_stream32_shape(const ScoreArgs &a, const ScorePrep &w, int32_t m0, int32_t mc, hipStream_t st) {
     constexpr int NW = kStream32Waves;
     static std::atomic<bool> allowed{false};                         // LDS above 64 KB has to be allowed per kernel
     if (!allowed) {
-        const void *fns[2] = {(const void *)score_stream_mfma32_kernel<1>, (const void *)score_stream_mfma32_kernel<2>};
-        for (const void *f : fns)
-            if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU) != hipSuccess)
-                return QLESS_ERR_DEVICE;
+        if (hipFuncSetAttribute((const void *)score_stream_mfma32_kernel<BITS, VB, VR>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU) != hipSuccess)
+            return QLESS_ERR_DEVICE;
         allowed = true;
     }
     // at most one workgroup per compute unit; the 8-row blocks are dealt out evenly over all wavefronts
@@ -1501,17 +1573,51 @@ static qless_status launch_stream_mfma32(const ScoreArgs &a, hipStream_t st) {
     if (groups * NW > total_rb) groups = (total_rb + NW - 1) / NW;
     const int64_t waves = groups * NW;
     const int64_t each = total_rb / waves, extra = total_rb % waves;
-    const int npass = (int)(((each + (extra > 0 ? 1 : 0)) * 8 + 63) / 64);
-    const dim3 grid((unsigned)groups), block(64 * NW);
+    constexpr int kPass = (BITS != 1 && VB == 1) ? 80 : 64;          // rows of a pass, as in the kernel
+    const int npass = (int)(((each + (extra > 0 ? 1 : 0)) * 8 + kPass - 1) / kPass);
+    const Stream32Plan sp = stream_mfma32_plan(BITS, VB, VR, a.k, a.C);
+    hipLaunchKernelGGL((score_stream_mfma32_kernel<BITS, VB, VR>), dim3((unsigned)groups), dim3(64 * NW), sp.lds, st, a,
+                       (const int8_t *)w.vexp, w.Mp, w.vrow, m0, mc, each, extra, npass, sp.wb, sp.nb, (unsigned)sp.val_bytes);
+    return QLESS_OK;
+}
+
+// 1-bit codes: one launch per chunk of 64 validation vectors
+static qless_status launch_stream_mfma32(const ScoreArgs &a, hipStream_t st) {
+    const ScorePrep none{};
     for (int32_t m0 = 0; m0 < a.M; m0 += kStream32Val) {
         const int32_t mc = a.M - m0 < kStream32Val ? a.M - m0 : kStream32Val;
-        const int vb = mc > 32 ? 2 : 1;
-        const Stream32Plan sp = stream_mfma32_plan(vb, a.k, a.C);
-        const unsigned ro = (unsigned)sp.val_bytes;
-        if (vb == 1) hipLaunchKernelGGL((score_stream_mfma32_kernel<1>), grid, block, sp.lds, st, a, m0, mc, each, extra, npass, sp.wb, sp.nb, ro);
-        else hipLaunchKernelGGL((score_stream_mfma32_kernel<2>), grid, block, sp.lds, st, a, m0, mc, each, extra, npass, sp.wb, sp.nb, ro);
+        const qless_status rc = mc > 32 ? launch_stream32_shape<1, 2, 64>(a, none, m0, mc, st)
+                                        : launch_stream32_shape<1, 1, 32>(a, none, m0, mc, st);
+        if (rc != QLESS_OK) return rc;
     }
     return launch_status();
+}
+
+// 4- and 8-bit codes against at most 64 validation vectors: one launch; the 4-bit validation rows are
+// int8-expanded by the pre-pass into the workspace first
+static bool use_stream_i8(int bits, int32_t M, int32_t k, int C) {
+    // measured against the tile kernel at N = 270 000: ahead up to 64 validation vectors at 4 bits, up to 32 at 8
+    if (bits < 4 || M > (bits == 4 ? 64 : 32) || (k * bits / 8) % 128 != 0) return false;
+    const int vr = stream32_rows(M);
+    return stream_mfma32_plan(bits, vr > 32 ? 2 : 1, vr, k, C).nb >= 2;
+}
+template <int BITS>
+static qless_status launch_stream_i8(const ScoreArgs &a, void *ws, hipStream_t st) {
+    ScorePrep w{};
+    if (BITS == 4) {
+        const MfmaPlan p = mfma_plan(a.N, a.M, a.k, BITS, a.C);
+        unsigned char *base = (unsigned char *)ws;
+        w.vexp = (int8_t *)base; w.vw = (float *)(base + p.off_vw);
+        w.smax = (unsigned int *)(base + p.off_smax); w.Mp = p.Mp; w.kp = p.kp; w.vrow = p.kp;
+        hipLaunchKernelGGL((score_prepare_kernel<BITS, false>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
+    }
+    const int vr = stream32_rows(a.M);
+    qless_status rc;
+    if (vr == 8) rc = launch_stream32_shape<BITS, 1, 8>(a, w, 0, a.M, st);
+    else if (vr == 16) rc = launch_stream32_shape<BITS, 1, 16>(a, w, 0, a.M, st);
+    else if (vr == 32) rc = launch_stream32_shape<BITS, 1, 32>(a, w, 0, a.M, st);
+    else rc = launch_stream32_shape<BITS, 2, 64>(a, w, 0, a.M, st);
+    return rc != QLESS_OK ? rc : launch_status();
 }
 
 template <int BITS, int RT, int CT, int TY, int TX>
@@ -1556,13 +1662,14 @@ extern "C" qless_status qless_score(const void *const *train_codes, const float 
         const StreamMfmaPlan sp = stream_mfma_plan(M, k, bits, C);
         if (sp.nb >= 2) return launch_stream_mfma(a, bits, sp, st);
     }
-    if (bits == 1 && M <= kStream32MaxVal && k % 512 == 0 && stream_mfma32_plan(2, k, C).nb >= 2)
+    if (bits == 1 && M <= kStream32MaxVal && k % 512 == 0 && stream_mfma32_plan(1, 2, 64, k, C).nb >= 2)
         return launch_stream_mfma32(a, st);
     if (use_mfma_path(bits, M, k)) {
         const size_t need = mfma_plan(N, M, k, bits, C).total;
         if (!ws || ws_bytes < need) return QLESS_ERR_WORKSPACE;
         if ((uintptr_t)ws % 16) return QLESS_ERR_INVALID_ARG;
         if (N > (int64_t)0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
+        if (use_stream_i8(bits, M, k, C)) return bits == 8 ? launch_stream_i8<8>(a, ws, st) : launch_stream_i8<4>(a, ws, st);
         if (bits == 8) return launch_mfma<8>(a, ws, st);
         if (bits == 4) return launch_mfma<4>(a, ws, st);
         if (bits == 2) return launch_mfma<2>(a, ws, st);
