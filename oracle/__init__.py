@@ -59,6 +59,8 @@ def lib():
                                    _vp, _vp]
         L.oracle_topk.restype = _c.c_int
         L.oracle_topk.argtypes = [_vp, _i64, _i64, _vp, _vp]
+        L.oracle_aggregate.restype = _c.c_int
+        L.oracle_aggregate.argtypes = [_vp, _i64, _c.c_int32, _vp, _c.c_int, _c.c_int, _vp]
         L.oracle_less_cosine.restype = _c.c_int
         L.oracle_less_cosine.argtypes = [_vp, _vp, _vp, _c.c_int, _i64, _i32, _i32, _vp]
         L.oracle_less16_store.restype = _c.c_int
@@ -227,6 +229,15 @@ def topk(score_vec, k_sel):
     val = np.zeros(k_sel, dtype=np.float32)
     _check(lib().oracle_topk(_ptr(s), s.size, k_sel, _ptr(idx), _ptr(val)), "topk")
     return idx, val
+
+
+def aggregate(full, group_end, mode):
+    """Maximum (mode 0) or fp32 mean (mode 1) of full[N, M] over the column groups ending at group_end."""
+    f = np.ascontiguousarray(full, dtype=np.float32)
+    ge = np.ascontiguousarray(group_end, dtype=np.int32)
+    out = np.zeros((f.shape[0], ge.size), dtype=np.float32)
+    _check(lib().oracle_aggregate(_ptr(f), f.shape[0], f.shape[1], _ptr(ge), ge.size, mode, _ptr(out)), "aggregate")
+    return out
 
 
 def less_cosine(train_P, val_P, eta):

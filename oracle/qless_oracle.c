@@ -13,6 +13,8 @@
  *   oracle_score        Eq.(6),(7), Sec. 3.2: cosine of the quantised vectors, learning-rate
  *                       weighted sum over checkpoints; then max over validation vectors.
  *   oracle_topk         Sec. 4.1 ("select the top 5 %"): largest scores, ties by smaller index.
+ *   oracle_aggregate    maximum / mean of the pairwise influences over groups of validation examples
+ *                       (no formula in the paper: parity unpinned)
  *   oracle_less_cosine  Eq.(2),(3), Sec. 2.2: the un-quantised LESS influence (comparator only).
  *   oracle_less16_*     the same comparator from a stored 16-bit (bfloat16) datastore (Table 1 baseline).
  *
@@ -409,6 +411,38 @@ int oracle_topk(const float *score, int64_t N, int64_t k_sel, int64_t *idx, floa
     qsort(a, (size_t)N, sizeof(sc_t), cmp_sc);   /* total order on (s, i): result is unique */
     for (int64_t t = 0; t < k_sel; ++t) { idx[t] = a[t].i; if (val) val[t] = a[t].s; }
     free(a);
+    return ORACLE_OK;
+}
+
+/* Aggregation of the pairwise influences over groups of validation examples (Sec. 4.1 selects by
+ * "cumulative influence scores" and its benchmarks have sub-tasks, but the paper gives no formula:
+ * parity unpinned against the paper; the benchmark spec fixes the maximum over all validation examples).
+ * Group t is the columns [group_end[t-1], group_end[t]) of full (group_end[-1] = 0).
+ *   mode 0: out[z][t] = the maximum of the group's entries (the first of equal ones, compared with >)
+ *   mode 1: out[z][t] = fl32(s / n), s the fp32 sum of the entries in column order from +0, n their number */
+int oracle_aggregate(const float *full, int64_t N, int32_t M, const int32_t *group_end, int T, int mode,
+                     float *out) {
+    if (!full || !group_end || !out || N < 0 || M < 1 || T < 1 || (mode != 0 && mode != 1)) return ORACLE_BAD_ARG;
+    for (int t = 0; t < T; ++t) {
+        const int32_t g0 = t ? group_end[t - 1] : 0;
+        if (group_end[t] <= g0 || group_end[t] > M) return ORACLE_BAD_ARG;
+    }
+    if (group_end[T - 1] != M) return ORACLE_BAD_ARG;
+    for (int64_t z = 0; z < N; ++z)
+        for (int t = 0; t < T; ++t) {
+            const int32_t g0 = t ? group_end[t - 1] : 0, g1 = group_end[t];
+            const float *row = full + z * (int64_t)M;
+            if (mode == 0) {
+                float m = row[g0];
+                for (int32_t j = g0 + 1; j < g1; ++j) if (row[j] > m) m = row[j];
+                out[z * (int64_t)T + t] = m;
+            } else {
+                volatile float s = 0.0f;               /* one fp32 rounding per addition */
+                for (int32_t j = g0; j < g1; ++j) s = s + row[j];
+                const volatile float n = (float)(g1 - g0);
+                out[z * (int64_t)T + t] = s / n;
+            }
+        }
     return ORACLE_OK;
 }
 
