@@ -8,6 +8,7 @@
  *   qless_score     Eq.(6),(7)    normalised quantised cosine, learning-rate weighted over
  *                                 checkpoints, reduced by max over validation examples
  *   qless_topk      Sec. 4.1      selection of the highest-scoring training examples
+ *   qless_aggregate Sec. 4.1      maximum / mean of the influences over groups of validation examples
  *
  * Conventions common to every call
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
@@ -183,6 +184,24 @@ qless_status qless_score16(const void *const *train16, const void *const *val16,
 size_t qless_topk_workspace(int64_t N, int64_t k_sel);
 qless_status qless_topk(const float *score, int64_t N, int64_t k_sel, int64_t *idx, float *val,
                         void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Aggregation of pairwise influences over groups of validation examples (Sec. 4.1 selects by
+ * "cumulative influence scores" and evaluates on benchmarks with sub-tasks, without a formula for
+ * combining validation examples; qless_score reduces by the maximum over all of them).  From the
+ * full matrix of qless_score / qless_score16:
+ *   QLESS_AGG_MAX   out[z][t] = max of full[z][j] over group t (the first of equal values)
+ *   QLESS_AGG_MEAN  out[z][t] = fl32(s / n), s = the fp32 sum of the group's entries in column order
+ *                   starting from +0 (one rounding per addition), n = their number
+ * Group t is the columns [group_end[t-1], group_end[t]) with group_end[-1] = 0.
+ *
+ *   full       device, N x M fp32 row-major          out   device, N x T fp32 row-major
+ *   group_end  host, T strictly increasing column ends, group_end[T-1] == M;  1 <= T <= QLESS_MAX_GROUPS
+ * ------------------------------------------------------------------------------------------- */
+#define QLESS_MAX_GROUPS 64
+typedef enum { QLESS_AGG_MAX = 0, QLESS_AGG_MEAN = 1 } qless_agg;
+qless_status qless_aggregate(const float *full, int64_t N, int32_t M, const int32_t *group_end, int T,
+                             qless_agg mode, float *out, void *stream);
 
 #ifdef __cplusplus
 }

@@ -40,6 +40,7 @@ EXPORTS = {
     "qless_score16": (_c.c_int, [_vp, _vp, _vp, _c.c_int, _i64, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
     "qless_topk_workspace": (_sz, [_i64, _i64]),
     "qless_topk": (_c.c_int, [_vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
+    "qless_aggregate": (_c.c_int, [_vp, _i64, _i32, _vp, _c.c_int, _c.c_int, _vp, _vp]),
 }
 
 
@@ -253,3 +254,18 @@ def topk(score_vec, k_sel, want_val=True, ws=None):
                             _vp(val.data_ptr()) if want_val else None, _vp(w.data_ptr()), w.numel(),
                             _stream()), "qless_topk")
     return (idx, val) if want_val else idx
+
+
+AGG_MAX, AGG_MEAN = 0, 1
+
+
+def aggregate(full, group_end, mode=AGG_MAX, out=None):
+    """qless_aggregate: full [N, M] fp32 -> [N, T] maximum or mean over the column groups ending at group_end."""
+    assert full.is_cuda and full.dtype == torch.float32 and full.is_contiguous() and full.dim() == 2
+    N, M = full.shape
+    ge = (_c.c_int32 * len(group_end))(*[int(g) for g in group_end])
+    if out is None:
+        out = torch.empty(N, len(group_end), dtype=torch.float32, device=full.device)
+    _check(lib().qless_aggregate(_vp(full.data_ptr()), N, M, _c.cast(ge, _vp), len(group_end), mode,
+                                 _vp(out.data_ptr()), _stream()), "qless_aggregate")
+    return out

@@ -1,4 +1,5 @@
-// Status strings and the host-side Gaussian quantile table of the projection
+// Status strings, the aggregation over groups of validation examples, and the host-side Gaussian
+// quantile table of the projection
 // (paper Sec. 2.4 allows a Gaussian random matrix; entries are the 256 standard-normal
 // quantiles Phi^-1((i + 1/2)/256), each rounded to the nearest bfloat16).
 #include "common.h"
@@ -42,7 +43,54 @@ const uint16_t *gaussian_table_bf16() {
     return table;
 }
 
+struct GroupEnds { int32_t end[QLESS_MAX_GROUPS]; };
+
+// one thread per (train example, group): the group's entries are visited in column order, so the
+// mean is the same sequence of fp32 additions for every launch shape
+__global__ void __launch_bounds__(256)
+aggregate_kernel(const float *full, int64_t N, int32_t M, GroupEnds ge, int T, int mean, float *out) {
+    const int64_t total = N * (int64_t)T;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t z = i / T;
+        const int t = (int)(i - z * T);
+        const int32_t g0 = t ? ge.end[t - 1] : 0, g1 = ge.end[t];
+        const float *row = full + z * (int64_t)M;
+        float r;
+        if (mean) {
+            float s = 0.0f;
+            for (int32_t j = g0; j < g1; ++j) s = __fadd_rn(s, row[j]);
+            r = __fdiv_rn(s, (float)(g1 - g0));
+        } else {
+            r = row[g0];
+            for (int32_t j = g0 + 1; j < g1; ++j) { const float v = row[j]; if (v > r) r = v; }
+        }
+        out[i] = r;
+    }
+}
+
 }  // namespace qless
+
+extern "C" qless_status qless_aggregate(const float *full, int64_t N, int32_t M, const int32_t *group_end, int T,
+                                        qless_agg mode, float *out, void *stream) {
+    if (N < 0 || M < 1 || !group_end || T < 1) return QLESS_ERR_INVALID_ARG;
+    if (mode != QLESS_AGG_MAX && mode != QLESS_AGG_MEAN) return QLESS_ERR_UNSUPPORTED;
+    if (T > QLESS_MAX_GROUPS) return QLESS_ERR_UNSUPPORTED;
+    qless::GroupEnds ge{};
+    for (int t = 0; t < T; ++t) {
+        const int32_t g0 = t ? group_end[t - 1] : 0;
+        if (group_end[t] <= g0 || group_end[t] > M) return QLESS_ERR_INVALID_ARG;
+        ge.end[t] = group_end[t];
+    }
+    if (group_end[T - 1] != M) return QLESS_ERR_INVALID_ARG;
+    if (N == 0) return QLESS_OK;
+    if (!full || !out) return QLESS_ERR_INVALID_ARG;
+    int64_t blocks = (N * (int64_t)T + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(qless::aggregate_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, full, N, M, ge, T,
+                       mode == QLESS_AGG_MEAN ? 1 : 0, out);
+    return qless::launch_status();
+}
 
 extern "C" const char *qless_status_string(qless_status s) {
     switch (s) {

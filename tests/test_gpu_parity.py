@@ -314,6 +314,19 @@ def test_topk_identical_without_ties(N, k_sel):
     np.testing.assert_array_equal(val.cpu().numpy().view(np.uint32), ref_v.view(np.uint32))
 
 
+@pytest.mark.parametrize("mode", [Q.AGG_MAX, Q.AGG_MEAN])
+@pytest.mark.parametrize("N,ends", [(1000, [57]), (333, [1, 2, 9, 20, 29]), (5000, list(range(1, 65))), (1, [3])])
+def test_aggregate_over_validation_groups_bit_exact(mode, N, ends):
+    _say("aggregate mode=%d N=%d groups=%d" % (mode, N, len(ends)))
+    rng = np.random.default_rng(N + len(ends))
+    full = (rng.standard_normal((N, ends[-1])) * 10 ** rng.uniform(-3, 3, size=(N, 1))).astype(np.float32)
+    full[0, :] = 0.0
+    full[N // 2, 0] = -0.0
+    ref = oracle.aggregate(full, ends, mode)
+    got = Q.aggregate(torch.from_numpy(full).to(DEV), ends, mode)
+    np.testing.assert_array_equal(got.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+
+
 # --------------------------------------------------------------------------------- end to end
 def test_config1_end_to_end_planted_recovery():
     _say("config 1 end to end on the GPU: project -> quantize(8) -> score -> top-50")

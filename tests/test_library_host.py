@@ -115,6 +115,14 @@ def test_quantize_score_topk_argument_validation():
     assert t(one, 10, 5, one, None, one, 8, None) == WORKSPACE
     assert t(one, 10, 0, None, None, None, 0, None) == OK
     assert L.qless_topk_workspace(270000, 13500) >= 16384 * 8 + 256 * 4      # selected keys (padded) + histogram
+    ag = L.qless_aggregate
+    ends = lambda *e: ctypes.cast((ctypes.c_int32 * len(e))(*e), ctypes.c_void_p)
+    assert ag(one, 0, 5, ends(2, 5), 2, 0, one, None) == OK
+    assert ag(one, 0, 5, ends(2, 4), 2, 0, one, None) == INVALID               # last end != M
+    assert ag(one, 0, 5, ends(3, 3, 5), 3, 1, one, None) == INVALID            # empty group
+    assert ag(one, 0, 5, ends(5), 1, 2, one, None) == UNSUPPORTED              # unknown mode
+    assert ag(one, 0, 5, None, 1, 0, one, None) == INVALID
+    assert ag(one, 0, 100, ends(*range(1, 66)), 65, 0, one, None) == UNSUPPORTED   # more than QLESS_MAX_GROUPS
 
 
 def test_gaussian_table_matches_the_oracle_table():
