@@ -198,7 +198,8 @@ def _datastore(n, k, bits, C, seed):
                                      (4100, 8, 384, 2), (70, 3, 8192, 4), (2000, 16, 1152, 3),
                                      (333, 12, 128, 2), (161, 9, 2048, 4), (50, 2, 8192, 4), (7, 6, 640, 1),
                                      (500, 40, 1024, 3), (1000, 64, 512, 2), (333, 100, 1024, 2), (129, 17, 8192, 4),
-                                     (4100, 33, 512, 1), (64, 320, 1024, 2), (2000, 129, 2048, 3)])
+                                     (4100, 33, 512, 1), (64, 320, 1024, 2), (2000, 129, 2048, 3),
+                                     (600, 513, 192, 3), (300, 1024, 576, 4), (520, 700, 64, 1), (257, 600, 8192, 2)])
 def test_score_bit_exact(bits, N, M, k, C):
     _say("score bits=%d N=%d M=%d k=%d C=%d" % (bits, N, M, k, C))
     tc, tr = _datastore(N, k, bits, C, 1000 + bits)
@@ -263,7 +264,7 @@ def test_normalize16_matches_oracle_store(n, k):
 
 
 @pytest.mark.parametrize("N,M,k,C", [(300, 70, 576, 3), (129, 8, 1024, 2), (64, 33, 8192, 2), (1000, 130, 2048, 2),
-                                     (515, 300, 320, 4)])
+                                     (515, 300, 320, 4), (515, 600, 320, 4), (300, 1030, 576, 2)])
 def test_score16_matches_oracle_from_the_same_store(N, M, k, C):
     """Eq.(2),(3) from bfloat16 stores: products exact, fp32 sums on the matrix cores (order unspecified):
     |acc_gpu - acc_fp64| <= C * 2^-17 (k terms of magnitude <= 1/k-ish, partial sums <= 1)."""
