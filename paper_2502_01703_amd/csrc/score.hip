@@ -237,7 +237,7 @@ constexpr int kKE = 128;                       // code elements per pipeline sta
 constexpr int narrow_stage_elements(int bits, int vt) {
     return bits == 1 ? 512                               // sign codes: 64 bytes per train row and stage
          : bits == 2 ? 512                               // two planes of 64 bytes
-                     : ((vt > 64 || bits == 8) ? kKE : 256);
+                     : (bits == 8 ? kKE : 256);     // whole 128-byte lines of every train row per stage
 }
 constexpr int log2c(int x) { return x <= 1 ? 0 : 1 + log2c(x / 2); }
 
