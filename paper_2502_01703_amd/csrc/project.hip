@@ -2,11 +2,13 @@
 // as a bf16 MFMA GEMM whose B operand (the random matrix) is generated in registers.
 //
 // Shape of the problem: M-dimension = batch rows n (small), N-dimension = k projected
-// coordinates, contraction over the gradient dimension d (huge).  One workgroup of 4 waves
-// owns a 64 (rows) x 512 (coordinates) output tile for one slice of d; each wave owns
-// 64 x 128 of it as 2 x 4 MFMA 32x32 accumulators.  The gradient tile is staged through LDS
-// (double buffered); partial tiles of the d-slices go to the workspace and are summed in a
-// fixed order by a second kernel, so results are run-to-run identical.
+// coordinates, contraction over the gradient dimension d (huge).  One workgroup of 8 waves
+// owns a 64 (rows) x 1024 (coordinates) output tile for one slice of d; each wave owns
+// 64 x 128 of it as 2 x 4 MFMA 32x32 accumulators.  Gaussian projections of batches that
+// fill 128-row tiles take 128 x 512 tiles instead (4 x 2 accumulators per wave): every
+// generated fragment of the random operand then feeds four matrix instructions instead of two.  The gradient tile is staged through LDS; partial tiles of
+// the d-slices go to the workspace and are summed in a fixed order by a second kernel, so
+// results are run-to-run identical.
 //
 // Random operand: lanes 0..31 of a wave take one 32-column word of R for their row m, lanes
 // 32..63 the next word; the 32 sign bits of a word feed four MFMA K-steps of 8 columns each.
@@ -23,21 +25,36 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int kTileRows = 64;                  // batch rows per workgroup
 constexpr int kWaves = 8;
-constexpr int kWaveCols = 128;                 // projected coordinates per wave
-constexpr int kTileCols = kWaves * kWaveCols;  // 512 per workgroup
 constexpr int kStageD = 128;                   // gradient columns per LDS stage
 constexpr int kLdsStride = kStageD * 2 + 16;   // bytes per staged row (+16: conflict-free b128 reads)
-constexpr int kStageBytes = kTileRows * kLdsStride;
+// NB = 32-row blocks per workgroup tile (2 or 4); a wave owns NB x (8 / NB) accumulators
+template <int NB> struct ProjShape {
+    static_assert(NB == 2 || NB == 4, "64- or 128-row tiles");
+    static constexpr int KB = 8 / NB;                   // 32-coordinate blocks per wave
+    static constexpr int kTileRows = 32 * NB;           // batch rows per workgroup
+    static constexpr int kWaveCols = 32 * KB;           // projected coordinates per wave
+    static constexpr int kTileCols = kWaves * kWaveCols;   // 1024 or 512 per workgroup
+    static constexpr int kStageBytes = kTileRows * kLdsStride;
+    static constexpr int kDirectStageBytes = kTileRows * kStageD * 2;
+};
+// 128-row tiles for the Gaussian family (whose operand generation, one table look-up per element,
+// is what bounds the kernel) when they cover the batch with no more padding rows than 64-row tiles
+// would.  The Rademacher kernel gains nothing from them: it already runs at the matrix-core rate the
+// chip sustains.
+static int tile_row_blocks(int64_t n, bool gauss) {
+    return (gauss && n > 64 && (n + 127) / 128 * 128 <= (n + 63) / 64 * 64) ? 4 : 2;
+}
 
 struct ProjectPlan {
     int64_t ntiles, ktiles, nsplit, stages_per_split, slices, grid;
     size_t ws_bytes;
 };
 
-static ProjectPlan make_plan(int64_t n, int64_t d_len, int32_t k) {
+static ProjectPlan make_plan(int64_t n, int64_t d_len, int32_t k, bool gauss) {
     ProjectPlan p{};
+    const int nb = tile_row_blocks(n, gauss);
+    const int kTileRows = 32 * nb, kTileCols = kWaves * 32 * (8 / nb);
     p.ntiles = (n + kTileRows - 1) / kTileRows;
     p.ktiles = (k + kTileCols - 1) / kTileCols;
     int64_t stages = (d_len + kStageD - 1) / kStageD;
@@ -116,12 +133,14 @@ union Frag { bf16x8 v; bf16x2 p[4]; uint4 u; uint32_t w[4]; uint16_t h[8]; };
 // case stages through registers into two padded buffers.
 constexpr int kRing = 4;
 constexpr int kGaussCopies = 32;                // copies of the Gaussian table in LDS
-constexpr int kDirectStageBytes = kTileRows * kStageD * 2;
 
-template <bool IN_F32, bool ALIGNED, bool GAUSS, bool DIRECT>
+template <bool IN_F32, bool ALIGNED, bool GAUSS, bool DIRECT, int NB>
 __global__ void __launch_bounds__(kWaves * 64, 2)
 project_kernel(ProjectArgs a, GaussTable gt) {
     static_assert(!DIRECT || (!IN_F32 && ALIGNED), "direct LDS copies move bf16 rows as they are");
+    using Sh = ProjShape<NB>;
+    constexpr int KB = Sh::KB, kTileRows = Sh::kTileRows, kWaveCols = Sh::kWaveCols, kTileCols = Sh::kTileCols;
+    constexpr int kStageBytes = Sh::kStageBytes, kDirectStageBytes = Sh::kDirectStageBytes;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // XCD-aware decode: consecutive workgroup ids land on different XCDs, so the ktiles
     // workgroups that share one gradient slice are given ids 8 apart (same XCD, same L2).
@@ -150,27 +169,27 @@ project_kernel(ProjectArgs a, GaussTable gt) {
         for (int i = tid; i < 256 * kGaussCopies; i += kWaves * 64) gtab[i] = gt.v[i / kGaussCopies];
     }
 
-    // row keys of this lane's four 32-row blocks
+    // row keys of this lane's KB 32-row blocks of the random matrix
     const int mbase = kt * kTileCols + wave * kWaveCols;
-    RowKey key[4];
-    bool live[4];
+    RowKey key[KB];
+    bool live[KB];
 #pragma unroll
-    for (int kb = 0; kb < 4; ++kb) {
+    for (int kb = 0; kb < KB; ++kb) {
         int m = mbase + 32 * kb + l32;
         live[kb] = (mbase + 32 * kb) < a.k;            // wave-uniform (k is a multiple of 64)
         key[kb] = row_key(a.sk, (uint32_t)m);
         if (!GAUSS) key[kb].a += (uint32_t)half * kGold;   // upper half-wave reads the next word
     }
 
-    f32x16 acc[2][4];
+    f32x16 acc[NB][KB];
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb)
+        for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[nb][kb][v] = 0.0f;
 
-    // staging (register path): 64 rows x 16 chunks of 8 columns; thread handles chunks tid + kThreads*i
+    // staging (register path): kTileRows rows x 16 chunks of 8 columns; thread handles chunks tid + kThreads*i
     constexpr int kThreads = kWaves * 64;
     constexpr int kChunksPerThread = kTileRows * (kStageD / 8) / kThreads;
     uint4 stage_regs[DIRECT ? 1 : kChunksPerThread];
@@ -192,8 +211,8 @@ project_kernel(ProjectArgs a, GaussTable gt) {
         }
     };
 
-    // staging (direct path): a stage is 64 rows x 256 bytes = 16 wavefront copies of 1 KB, two per
-    // wave.  Copy q fills LDS chunks 64 q .. 64 q + 63 (rows 4 q .. 4 q + 3); chunk `pos` of row r
+    // staging (direct path): a stage is kTileRows rows x 256 bytes = 16 or 32 wavefront copies of 1 KB,
+    // two or four per wave.  Copy q fills LDS chunks 64 q .. 64 q + 63 (rows 4 q .. 4 q + 3); chunk `pos` of row r
     // holds gradient chunk pos ^ (r & 15), so 16 consecutive rows read the same gradient chunk
     // from 16 different bank groups.  Rows past n re-read row n-1 (never stored).
     constexpr int kCopies = kDirectStageBytes / 1024 / kWaves;
@@ -258,15 +277,15 @@ project_kernel(ProjectArgs a, GaussTable gt) {
 #pragma unroll
         for (int bp = 0; bp < 2; ++bp) {
             // A fragments: rows 32*nb + l32, columns 64*bp + 32*half + 8*ks .. +7
-            Frag af[2][4];
+            Frag af[NB][4];
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
+            for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
                     af[nb][ks].u = read_a(buf, nb, bp, ks);
             const uint32_t wpair = wstage + 2u * bp;             // word index of lanes 0..31
 #pragma unroll
-            for (int kb = 0; kb < 4; ++kb) {
+            for (int kb = 0; kb < KB; ++kb) {
                 // row blocks past k (last k-tile only) are computed and dropped in the epilogue
                 if (!GAUSS) {
                     const uint32_t h = key_word(key[kb], wpair * kGold);
@@ -281,8 +300,9 @@ project_kernel(ProjectArgs a, GaussTable gt) {
                         bf.p[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(x, 1.0f, 1);
                         bf.p[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(x, 1.0f, 2);
                         bf.p[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(x, 1.0f, 3);
-                        acc[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[0][ks].v, bf.v, acc[0][kb], 0, 0, 0);
-                        acc[1][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][ks].v, bf.v, acc[1][kb], 0, 0, 0);
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            acc[nb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[nb][ks].v, bf.v, acc[nb][kb], 0, 0, 0);
                     }
                 } else {
                     // Gaussian-like entries: 4 columns per word, one table byte per column
@@ -296,8 +316,9 @@ project_kernel(ProjectArgs a, GaussTable gt) {
                         bf.h[2] = gl[((h0 >> 16) & 0xFF) * kGaussCopies]; bf.h[3] = gl[(h0 >> 24) * kGaussCopies];
                         bf.h[4] = gl[(h1 & 0xFF) * kGaussCopies];         bf.h[5] = gl[((h1 >> 8) & 0xFF) * kGaussCopies];
                         bf.h[6] = gl[((h1 >> 16) & 0xFF) * kGaussCopies]; bf.h[7] = gl[(h1 >> 24) * kGaussCopies];
-                        acc[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[0][ks].v, bf.v, acc[0][kb], 0, 0, 0);
-                        acc[1][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][ks].v, bf.v, acc[1][kb], 0, 0, 0);
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            acc[nb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[nb][ks].v, bf.v, acc[nb][kb], 0, 0, 0);
                     }
                 }
             }
@@ -311,9 +332,9 @@ project_kernel(ProjectArgs a, GaussTable gt) {
     // partial tile -> workspace [split][n][k];  D[i][j]: j = lane%32, i = 8*(v/4) + 4*(lane/32) + v%4
     float *wsp = a.ws + (size_t)split * (size_t)a.n * (size_t)a.k;
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
+        for (int kb = 0; kb < KB; ++kb) {
             if (!live[kb]) continue;
             const int m = mbase + 32 * kb + l32;
 #pragma unroll
@@ -356,7 +377,9 @@ using namespace qless;
 
 extern "C" size_t qless_project_workspace(int64_t n, int64_t d_len, int32_t k) {
     if (n <= 0 || d_len <= 0 || k <= 0) return 0;
-    return make_plan(n, d_len, k).ws_bytes;
+    // enough for either matrix family (their tile shapes, hence their d-splits, may differ)
+    const size_t r = make_plan(n, d_len, k, false).ws_bytes, g = make_plan(n, d_len, k, true).ws_bytes;
+    return r > g ? r : g;
 }
 
 // Validates the projection arguments shared by both entry points and launches the split-d
@@ -373,7 +396,7 @@ static qless_status project_partials(const void *G, qless_dtype dt, int64_t n, i
     if (d_offset + d_len > ((int64_t)1 << 36)) return QLESS_ERR_UNSUPPORTED;
     if (n > ((int64_t)1 << 31)) return QLESS_ERR_UNSUPPORTED;
     if (n == 0) return QLESS_OK;
-    ProjectPlan plan = make_plan(n, d_len, k);
+    ProjectPlan plan = make_plan(n, d_len, k, kind == QLESS_GAUSSIAN);
     if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return QLESS_ERR_WORKSPACE;
     if (plan.grid > 0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
     if (plan.nsplit == 0) return QLESS_OK;
@@ -389,19 +412,22 @@ static qless_status project_partials(const void *G, qless_dtype dt, int64_t n, i
     const size_t esz = dt == QLESS_F32 ? 4 : 2;
     const bool aligned = ((uintptr_t)G % 16 == 0) && ((ldG * esz) % 16 == 0);
     const bool direct = dt == QLESS_BF16 && aligned && d_len % kStageD == 0;
-    const size_t lds = (direct ? (size_t)kRing * kDirectStageBytes : (size_t)2 * kStageBytes) +
+    const int nb = tile_row_blocks(n, gauss);
+    const size_t lds = (direct ? (size_t)kRing * (32 * nb) * kStageD * 2 : (size_t)2 * (32 * nb) * kLdsStride) +
                        (gauss ? (size_t)256 * kGaussCopies * 2 : 0);
     dim3 grid((unsigned)plan.grid), block(kWaves * 64);
     // more than 64 KB of dynamic LDS has to be allowed per kernel (host-side attribute, no device work)
-#define QLESS_LAUNCH(F32, AL, GA, DI) do { \
+#define QLESS_LAUNCH_NB(F32, AL, GA, DI, NBLK) do { \
         static std::atomic<bool> once{false}; \
         if (!once) { \
-            if (hipFuncSetAttribute((const void *)project_kernel<F32, AL, GA, DI>, \
+            if (hipFuncSetAttribute((const void *)project_kernel<F32, AL, GA, DI, NBLK>, \
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
                 return QLESS_ERR_DEVICE; \
             once = true; \
         } \
-        hipLaunchKernelGGL((project_kernel<F32, AL, GA, DI>), grid, block, lds, st, a, gt); } while (0)
+        hipLaunchKernelGGL((project_kernel<F32, AL, GA, DI, NBLK>), grid, block, lds, st, a, gt); } while (0)
+#define QLESS_LAUNCH(F32, AL, GA, DI) do { \
+        if (nb == 4) QLESS_LAUNCH_NB(F32, AL, GA, DI, 4); else QLESS_LAUNCH_NB(F32, AL, GA, DI, 2); } while (0)
     if (dt == QLESS_F32) {
         if (aligned) { if (gauss) QLESS_LAUNCH(true, true, true, false); else QLESS_LAUNCH(true, true, false, false); }
         else         { if (gauss) QLESS_LAUNCH(true, false, true, false); else QLESS_LAUNCH(true, false, false, false); }
@@ -412,6 +438,7 @@ static qless_status project_partials(const void *G, qless_dtype dt, int64_t n, i
         else         { if (gauss) QLESS_LAUNCH(false, false, true, false); else QLESS_LAUNCH(false, false, false, false); }
     }
 #undef QLESS_LAUNCH
+#undef QLESS_LAUNCH_NB
     if (launch_status() != QLESS_OK) return QLESS_ERR_DEVICE;
     *nsplit_out = (int)plan.nsplit;
     return QLESS_OK;

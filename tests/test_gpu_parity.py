@@ -50,7 +50,8 @@ def test_generator_words_match_oracle_and_golden_file():
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("kind", [Q.RADEMACHER, Q.GAUSSIAN])
 @pytest.mark.parametrize("n,d,k", [(70, 5000, 576), (3, 333, 64), (130, 4099, 1088), (66, 5120, 576),
-                                   (5, 128, 64), (64, 16384, 2048)])
+                                   (5, 128, 64), (64, 16384, 2048), (128, 5120, 1088), (256, 4099, 576),
+                                   (200, 8192, 512)])
 def test_projection_parity_ragged(dtype, kind, n, d, k):
     _say("project n=%d d=%d k=%d kind=%d %s" % (n, d, k, kind, dtype))
     g = torch.Generator().manual_seed(n * 1000 + d)
@@ -143,7 +144,8 @@ def test_quantize_strided_rows_and_literal_formula_boundary_rate():
 @pytest.mark.parametrize("bits", [8, 4, 2, 1])
 @pytest.mark.parametrize("n,d,k,dtype,kind", [(70, 5000, 576, torch.float32, 0), (64, 16384, 2048, torch.bfloat16, 0),
                                               (3, 333, 64, torch.bfloat16, 1), (9, 40000, 16384, torch.bfloat16, 0),
-                                              (2100, 1024, 128, torch.bfloat16, 0)])
+                                              (2100, 1024, 128, torch.bfloat16, 0), (128, 16384, 2048, torch.bfloat16, 0),
+                                              (250, 5000, 576, torch.float32, 1)])
 def test_fused_project_quantize_matches_the_two_calls_and_the_oracle(bits, n, d, k, dtype, kind):
     """One call for Eq.(1) then Eq.(4),(5): same bits as the two separate calls, and the codes are
     the oracle's codes of the projection the call reports."""
