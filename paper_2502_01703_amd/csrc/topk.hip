@@ -8,20 +8,25 @@
 //   as a whole (without ties at the threshold that is after the four digits of the score).  Up to
 //   32768 scores one workgroup does all passes in a single launch (a launch costs more than such a
 //   pass; beyond that size the ~50 instructions per key and pass are too many for one compute
-//   unit); above that, a histogram launch and a one-workgroup digit pick per pass;  2. compact all keys >= threshold (exactly k_sel of them; one atomic per
-//   wavefront);
-//   3. sort them descending with a bitonic network (LDS for spans up to 4096, global steps
-//   above);  4. decode indices and gather the scores.
+//   unit); above that, one histogram launch per pass, whose workgroups each first pick the digit of
+//   the pass before from its finished histogram (a 256-bin scan, cheaper than a launch of its own);
+//   2. compact all keys >= threshold (exactly k_sel of them; one atomic per wavefront);
+//   3. order them, descending: up to 16384 selected keys by rank (every key counts the larger ones
+//   among all of them, k_sel^2 comparisons spread over the whole chip, and is written to the slot of
+//   its rank: two short launches); above that, a bitonic network (LDS spans of 4096 keys with global
+//   steps in between), then  4. decode indices and gather the scores.
 #include "common.h"
 
 namespace qless {
 
 constexpr int kSortBlock = 4096;   // keys sorted per workgroup in LDS (32 KB)
+constexpr int kSortOne = 16384;    // most (padded) selected keys that are ordered by rank instead of sorted
+constexpr int kPasses = 8;         // 8-bit digits of the 64-bit keys
 constexpr int64_t kSelectSmallMax = 32768;   // scores one workgroup selects from in a single launch
 
 struct TopkPlan {
     int64_t padded;                // power of two >= k_sel (>= kSortBlock)
-    size_t off_sel, off_hist, off_state, total;
+    size_t off_sel, off_hist, off_state, off_rank, total;
 };
 
 static TopkPlan topk_plan(int64_t N, int64_t k_sel) {
@@ -31,8 +36,9 @@ static TopkPlan topk_plan(int64_t N, int64_t k_sel) {
     p.padded = pad;
     size_t o = 0;
     p.off_sel = o;   o += (size_t)pad * 8;
-    p.off_hist = o;  o += 256 * 4;
-    p.off_state = o; o += 64;
+    p.off_hist = o;  o += kPasses * 256 * 4;        // one histogram per pass
+    p.off_state = o; o += (kPasses + 1) * 32 + 32;  // state before each pass and after the last; compaction cursor
+    p.off_rank = o;  o += (size_t)pad * 4;          // ranks of the selected keys
     p.total = o;
     return p;
 }
@@ -40,8 +46,9 @@ static TopkPlan topk_plan(int64_t N, int64_t k_sel) {
 struct SelectState {
     unsigned long long prefix;     // high digits of the threshold found so far
     unsigned long long remaining;  // rank still to locate inside the current prefix bucket
-    unsigned int count;            // compaction cursor
+    unsigned int count;            // compaction cursor (of the last state only)
     unsigned int done;             // the threshold is final: later passes return at once
+    unsigned long long pad_;       // 32 bytes per state
 };
 
 __device__ inline uint32_t order_key(float f) {
@@ -54,9 +61,13 @@ __device__ inline unsigned long long make_key(float sc, int64_t i) {
     return ((unsigned long long)order_key(sc) << 32) | (0xFFFFFFFFull - (unsigned long long)i);
 }
 
+// state[0] = nothing chosen yet; all histograms and the compaction cursor (state[kPasses].count) cleared
 __global__ void __launch_bounds__(256) topk_init_kernel(unsigned int *hist, SelectState *state, unsigned long long k_sel) {
-    if (threadIdx.x == 0) { state->prefix = 0; state->remaining = k_sel; state->count = 0; state->done = 0; }
-    hist[threadIdx.x] = 0;
+    if (threadIdx.x == 0) {
+        state[0].prefix = 0; state[0].remaining = k_sel; state[0].count = 0; state[0].done = 0;
+        state[kPasses].count = 0;
+    }
+    for (int p = 0; p < kPasses; ++p) hist[p * 256 + threadIdx.x] = 0;
 }
 
 // Suffix sums over 256 bins and the digit that holds the remaining rank `rem` (walking from the top):
@@ -144,70 +155,154 @@ topk_select_small_kernel(const float *score, int64_t N, unsigned long long k_sel
         __syncthreads();
         if (done) break;
     }
-    if (threadIdx.x == 0) { state->prefix = prefix; state->remaining = rem; state->count = 0; state->done = 1; }
+    if (threadIdx.x == 0) {
+        state[kPasses].prefix = prefix; state[kPasses].remaining = rem; state[kPasses].count = 0; state[kPasses].done = 1;
+    }
 }
 
-// histogram of digit `pass` (0 = most significant byte) over keys whose higher digits equal prefix
+// The state after the digit pick of pass `pass` (from the state before it and the pass's finished
+// histogram), computed by every thread of a 256-thread workgroup alike; workgroup 0 also records
+// it in state[pass + 1].  `above` and `sh` are LDS scratch.
+__device__ inline SelectState next_state(int pass, SelectState *state, const unsigned int *hist,
+                                         unsigned long long *above, SelectState *sh) {
+    const SelectState before = state[pass];
+    if (before.done) {                              // uniform
+        if (blockIdx.x == 0 && threadIdx.x == 0) { state[pass + 1].prefix = before.prefix; state[pass + 1].remaining = before.remaining; state[pass + 1].done = 1; }
+        return before;
+    }
+    const unsigned int mine = hist[pass * 256 + threadIdx.x];
+    unsigned long long left = 0;
+    if (pick_digit(above, mine, before.remaining, left)) {
+        sh->prefix = before.prefix | ((unsigned long long)threadIdx.x << (56 - 8 * pass));
+        sh->remaining = left;
+        sh->done = left == (unsigned long long)mine;    // the whole bucket is selected: the prefix with zeros below is the threshold
+    }
+    __syncthreads();
+    SelectState after = *sh;
+    after.count = 0;
+    __syncthreads();
+    if (blockIdx.x == 0 && threadIdx.x == 0) { state[pass + 1].prefix = after.prefix; state[pass + 1].remaining = after.remaining; state[pass + 1].done = after.done; }
+    return after;
+}
+
+// histogram of digit `pass` (0 = most significant byte) over keys whose higher digits equal the prefix
+// chosen so far; the pick of the pass before is done here first, by every workgroup for itself
 __global__ void __launch_bounds__(256)
-topk_hist_kernel(const float *score, int64_t N, int pass, const SelectState *state,
-                 unsigned int *hist) {
+topk_hist_kernel(const float *score, int64_t N, int pass, SelectState *state, unsigned int *hist) {
     __shared__ unsigned int h[256];
-    if (state->done) return;                        // uniform: written by an earlier launch
+    __shared__ unsigned long long above[257];
+    __shared__ SelectState sh;
+    const SelectState cur = pass == 0 ? state[0] : next_state(pass - 1, state, hist, above, &sh);
+    if (cur.done) return;                           // uniform
     h[threadIdx.x] = 0;
     __syncthreads();
-    const unsigned long long prefix = state->prefix;
+    const unsigned long long prefix = cur.prefix;
     const int shift = 56 - 8 * pass;
     // bits above the current digit: pass 0 has none (mask 0), later passes compare them all
     const unsigned long long himask = pass == 0 ? 0ull : (~0ull << (shift + 8));
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        const unsigned long long key = make_key(score[i], i);
-        const bool match = ((key ^ prefix) & himask) == 0;
-        if (match) atomicAdd(&h[(key >> shift) & 0xFF], 1u);
+    for (int64_t i0 = (int64_t)blockIdx.x * blockDim.x; i0 < N; i0 += (int64_t)gridDim.x * blockDim.x) {   // uniform per wavefront
+        const int64_t i = i0 + threadIdx.x;
+        const unsigned long long key = i < N ? make_key(score[i], i) : 0ull;
+        const bool match = i < N && ((key ^ prefix) & himask) == 0;
+        const unsigned int d = (unsigned int)(key >> shift) & 0xFFu;
+        // the leading digits of scores are few: the lanes that share the digit of the first matching lane
+        // are added at once, the others one by one
+        const unsigned long long act = __ballot(match);
+        if (act) {
+            const int leader = __ffsll((long long)act) - 1;
+            const unsigned int d0 = (unsigned int)__builtin_amdgcn_readlane((int)d, leader);
+            const unsigned long long same = __ballot(match && d == d0);
+            if ((int)(threadIdx.x & 63) == leader) atomicAdd(&h[d0], (unsigned int)__popcll(same));
+            if (match && d != d0) atomicAdd(&h[d], 1u);
+        }
     }
     __syncthreads();
-    if (h[threadIdx.x]) atomicAdd(&hist[threadIdx.x], h[threadIdx.x]);
-}
-
-// one workgroup: the digit that holds the remaining rank, walking the 256 bins from the top
-__global__ void __launch_bounds__(256)
-topk_pick_kernel(int pass, SelectState *state, unsigned int *hist) {
-    __shared__ unsigned long long above[257];      // above[d] = counted keys with digit >= d
-    if (state->done) return;
-    const unsigned int mine = hist[threadIdx.x];
-    hist[threadIdx.x] = 0;                          // ready for the next pass
-    unsigned long long left = 0;
-    if (pick_digit(above, mine, state->remaining, left)) {
-        state->prefix |= (unsigned long long)threadIdx.x << (56 - 8 * pass);
-        state->remaining = left;
-        // the whole bucket is selected: the prefix with zeros below is the threshold
-        if (left == (unsigned long long)mine) state->done = 1;
-    }
+    if (h[threadIdx.x]) atomicAdd(&hist[pass * 256 + threadIdx.x], h[threadIdx.x]);
 }
 
 // Keys >= threshold (exactly k_sel of them) are gathered in any order; the slots from k_sel to
-// padded are cleared.  One atomic per wavefront: its selected lanes take consecutive positions.
-__global__ void topk_compact_kernel(const float *score, int64_t N, SelectState *state,
-                                    unsigned long long *sel, int64_t k_sel, int64_t padded) {
-    const unsigned long long thr = state->prefix;
-    const int lane = threadIdx.x & 63;
+// padded and the ranks are cleared.  A workgroup takes 1024 consecutive examples at a time and one
+// atomic for all it selects among them.
+// `last_pick`: the digit of the last pass is still to be picked from its histogram (large N).
+constexpr int kCompactPer = 4;                      // examples per thread and round
+__global__ void __launch_bounds__(256)
+topk_compact_kernel(const float *score, int64_t N, SelectState *state, const unsigned int *hist, int last_pick,
+                    unsigned long long *sel, unsigned int *rank, int64_t k_sel, int64_t padded) {
+    __shared__ unsigned long long above[257];
+    __shared__ SelectState sh;
+    __shared__ unsigned int offs[4 * kCompactPer + 1];
+    const unsigned long long thr = last_pick ? next_state(kPasses - 1, state, hist, above, &sh).prefix
+                                             : state[kPasses].prefix;
+    unsigned int *cursor = &state[kPasses].count;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t span = N > padded ? N : padded;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < span;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        if (i >= k_sel && i < padded) sel[i] = 0;   // padding sorts last (real keys are > 0)
-        unsigned long long key = 0;
-        bool take = false;
-        if (i < N) { key = make_key(score[i], i); take = key >= thr; }
-        const unsigned long long mask = __ballot(take);
-        if (mask) {
-            const int leader = __ffsll((long long)mask) - 1;
-            unsigned int base = 0;
-            if (lane == leader) base = atomicAdd(&state->count, (unsigned int)__popcll(mask));
-            base = __shfl(base, leader);
-            const unsigned int pos = base + (unsigned int)__popcll(mask & ((1ull << lane) - 1ull));
-            if (take && (int64_t)pos < k_sel) sel[pos] = key;
+    constexpr int kChunk = 256 * kCompactPer;
+    for (int64_t c0 = (int64_t)blockIdx.x * kChunk; c0 < span; c0 += (int64_t)gridDim.x * kChunk) {   // uniform per workgroup
+        unsigned long long key[kCompactPer], mask[kCompactPer];
+        bool take[kCompactPer];
+#pragma unroll
+        for (int u = 0; u < kCompactPer; ++u) {
+            const int64_t i = c0 + u * 256 + threadIdx.x;
+            if (i >= k_sel && i < padded) sel[i] = 0;   // padding sorts last (real keys are > 0)
+            if (i < padded) rank[i] = 0;
+            key[u] = 0; take[u] = false;
+            if (i < N) { key[u] = make_key(score[i], i); take[u] = key[u] >= thr; }
+            mask[u] = __ballot(take[u]);
+            if (lane == 0) offs[wave * kCompactPer + u] = (unsigned int)__popcll(mask[u]);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {                      // exclusive prefix over the 16 counts, then one atomic
+            unsigned int run = 0;
+            for (int q = 0; q < 4 * kCompactPer; ++q) { const unsigned int v = offs[q]; offs[q] = run; run += v; }
+            offs[4 * kCompactPer] = run ? atomicAdd(cursor, run) : 0u;
+        }
+        __syncthreads();
+        const unsigned int wgbase = offs[4 * kCompactPer];
+#pragma unroll
+        for (int u = 0; u < kCompactPer; ++u) {
+            const unsigned int pos = wgbase + offs[wave * kCompactPer + u] +
+                                     (unsigned int)__popcll(mask[u] & ((1ull << lane) - 1ull));
+            if (take[u] && (int64_t)pos < k_sel) sel[pos] = key[u];
+        }
+        __syncthreads();                             // offs is reused by the next round
+    }
+}
+
+// Rank of every selected key = how many selected keys are larger (keys are distinct): workgroup
+// (x, y) counts, for its 256 keys, the larger ones among keys [y * seg, (y + 1) * seg), staged in LDS 1024
+// at a time and read by all lanes at once (a broadcast).  k_sel^2 comparisons: for k_sel <= kSortOne only.
+__global__ void __launch_bounds__(256)
+topk_rank_kernel(const unsigned long long *sel, int64_t k_sel, int64_t seg, unsigned int *rank) {
+    __shared__ __attribute__((aligned(16))) unsigned long long tile[1024];
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const unsigned long long mine = i < k_sel ? sel[i] : ~0ull;
+    const int64_t j0 = (int64_t)blockIdx.y * seg;
+    const int64_t j1 = j0 + seg < k_sel ? j0 + seg : k_sel;
+    unsigned int cnt = 0;
+    for (int64_t jb = j0; jb < j1; jb += 1024) {
+        __syncthreads();
+        for (int t = threadIdx.x; t < 1024; t += 256) tile[t] = jb + t < j1 ? sel[jb + t] : 0ull;   // 0 is below every key
+        __syncthreads();
+#pragma unroll 8
+        for (int t = 0; t < 1024; t += 2) {
+            const ulonglong2 pr = *(const ulonglong2 *)&tile[t];
+            cnt += (pr.x > mine) + (pr.y > mine);
         }
     }
+    if (i < k_sel && cnt) atomicAdd(&rank[i], cnt);
+}
+
+// idx / val in rank order
+__global__ void __launch_bounds__(256)
+topk_scatter_kernel(const unsigned long long *sel, const unsigned int *rank, int64_t k_sel, const float *score,
+                    int64_t N, int64_t *idx, float *val) {
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= k_sel) return;
+    const int64_t i = (int64_t)(0xFFFFFFFFull - (sel[t] & 0xFFFFFFFFull));
+    const unsigned int r = rank[t];
+    if ((int64_t)r >= k_sel) return;                 // cannot happen with distinct keys
+    idx[r] = i;
+    if (val) val[r] = score[i < N ? i : N - 1];
 }
 
 // Bitonic network, descending.  Stage size kk (sub-sequence length), step jj (partner distance).
@@ -227,16 +322,17 @@ topk_bitonic_local_kernel(unsigned long long *data, int64_t kk_from, int64_t kk_
     __syncthreads();
     bool wide_before = true;                           // the previous step crossed wavefront segments
     for (int64_t kk = kk_from; kk <= kk_to; kk <<= 1) {
-        int64_t jj = kk >> 1;
-        if (jj >= kSortBlock) jj = kSortBlock >> 1;
-        for (; jj > 0; jj >>= 1) {
+        int64_t j0 = kk >> 1;
+        if (j0 >= kSortBlock) j0 = kSortBlock >> 1;
+        for (int lj = 63 - __builtin_clzll((unsigned long long)j0); lj >= 0; --lj) {   // partner distance 2^lj
+            const int jj = 1 << lj;
             const bool wide = jj > 64;
             if (wide || wide_before) __syncthreads();
             else { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); __builtin_amdgcn_wave_barrier(); }
             wide_before = wide;
             for (int t = threadIdx.x; t < kSortBlock / 2; t += 1024) {
-                const int lo = (int)(((int64_t)t / jj) * 2 * jj + ((int64_t)t % jj));
-                const int hi = lo + (int)jj;
+                const int lo = ((t >> lj) << (lj + 1)) | (t & (jj - 1));
+                const int hi = lo + jj;
                 const bool desc = (((base + lo) & kk) == 0);
                 unsigned long long x = s[lo], y = s[hi];
                 cmpswap_desc(x, y, desc);
@@ -292,20 +388,33 @@ extern "C" qless_status qless_topk(const float *score, int64_t N, int64_t k_sel,
     unsigned long long *sel = (unsigned long long *)(w + p.off_sel);
     unsigned int *hist = (unsigned int *)(w + p.off_hist);
     SelectState *state = (SelectState *)(w + p.off_state);
+    unsigned int *rank = (unsigned int *)(w + p.off_rank);
 
     auto blocks_for = [](int64_t n) { int64_t b = (n + 255) / 256; if (b < 1) b = 1; if (b > 2048) b = 2048; return (unsigned)b; };
-    if (N <= kSelectSmallMax) {
+    const bool small = N <= kSelectSmallMax;
+    if (small) {
         hipLaunchKernelGGL(topk_select_small_kernel, dim3(1), dim3(1024), 0, st, score, N, (unsigned long long)k_sel, state);
     } else {
         hipLaunchKernelGGL(topk_init_kernel, dim3(1), dim3(256), 0, st, hist, state, (unsigned long long)k_sel);
-        for (int pass = 0; pass < 8; ++pass) {
+        for (int pass = 0; pass < kPasses; ++pass)
             hipLaunchKernelGGL(topk_hist_kernel, dim3(blocks_for(N)), dim3(256), 0, st, score, N, pass, state, hist);
-            hipLaunchKernelGGL(topk_pick_kernel, dim3(1), dim3(256), 0, st, pass, state, hist);
-        }
     }
     const int64_t span = N > p.padded ? N : p.padded;
-    hipLaunchKernelGGL(topk_compact_kernel, dim3(blocks_for(span)), dim3(256), 0, st, score, N, state, sel, k_sel, p.padded);
-    // sort the selected keys, descending
+    int64_t cblocks = (span + 256 * kCompactPer - 1) / (256 * kCompactPer);
+    if (cblocks > 2048) cblocks = 2048;
+    hipLaunchKernelGGL(topk_compact_kernel, dim3((unsigned)cblocks), dim3(256), 0, st, score, N, state,
+                       (const unsigned int *)hist, small ? 0 : 1, sel, rank, k_sel, p.padded);
+    if (p.padded <= kSortOne) {
+        // few selected keys: rank every key among all of them, then write in rank order
+        const unsigned kb = (unsigned)((k_sel + 255) / 256);
+        const int64_t seg = 1024;
+        hipLaunchKernelGGL(topk_rank_kernel, dim3(kb, (unsigned)((k_sel + seg - 1) / seg)), dim3(256), 0, st,
+                           (const unsigned long long *)sel, k_sel, seg, rank);
+        hipLaunchKernelGGL(topk_scatter_kernel, dim3(kb), dim3(256), 0, st, (const unsigned long long *)sel,
+                           (const unsigned int *)rank, k_sel, score, N, idx, val);
+        return launch_status();
+    }
+    // many selected keys: sort them, descending, with a bitonic network
     const unsigned nblk = (unsigned)(p.padded / kSortBlock);
     hipLaunchKernelGGL(topk_bitonic_local_kernel, dim3(nblk), dim3(1024), 0, st, sel, (int64_t)2, (int64_t)kSortBlock);
     for (int64_t kk = 2 * kSortBlock; kk <= p.padded; kk <<= 1) {
