@@ -3,14 +3,17 @@
 //
 // Every example gets a 64-bit key  (order-preserving image of the fp32 score) << 32 | (2^32-1 - index);
 // keys are distinct and "larger key" is exactly "selected earlier".  Steps:
-//   1. radix-select the k_sel-th largest key, up to 8 passes of 8 bits (keys are formed on the fly
-//   from the scores); the passes stop as soon as the bucket that holds the k_sel-th key is selected
-//   as a whole (without ties at the threshold that is after the four digits of the score).  Up to
-//   32768 scores one workgroup does all passes in a single launch (a launch costs more than such a
-//   pass; beyond that size the ~50 instructions per key and pass are too many for one compute
-//   unit); above that, one histogram launch per pass, whose workgroups each first pick the digit of
-//   the pass before from its finished histogram (a 256-bin scan, cheaper than a launch of its own);
-//   2. compact all keys >= threshold (exactly k_sel of them; one atomic per wavefront);
+//   1. radix-select the k_sel-th largest key in passes of 8 bits (keys are formed on the fly from
+//   the scores); the passes stop as soon as the bucket that holds the k_sel-th key is selected as a
+//   whole.  Up to 32768 scores one workgroup does all (up to 8) passes in a single launch (a launch
+//   costs more than such a pass; beyond that size the ~50 instructions per key and pass are too
+//   many for one compute unit).  Above that, one histogram launch for each of the four digits of
+//   the score, whose workgroups each first pick the digit of the pass before from its finished
+//   histogram (a 256-bin scan, cheaper than a launch of its own); if the threshold score T is then
+//   shared by more examples than are still to be taken, the r with the smallest indices are the
+//   first r in array order: a count of the examples with score T per 1024 examples and an exclusive
+//   scan of these counts give every such example its position among them;
+//   2. compact all selected keys (exactly k_sel of them; one atomic per workgroup and 1024 examples);
 //   3. order them, descending: up to 16384 selected keys by rank (every key counts the larger ones
 //   among all of them, k_sel^2 comparisons spread over the whole chip, and is written to the slot of
 //   its rank: two short launches); above that, a bitonic network (LDS spans of 4096 keys with global
@@ -21,12 +24,13 @@ namespace qless {
 
 constexpr int kSortBlock = 4096;   // keys sorted per workgroup in LDS (32 KB)
 constexpr int kSortOne = 16384;    // most (padded) selected keys that are ordered by rank instead of sorted
-constexpr int kPasses = 8;         // 8-bit digits of the 64-bit keys
+constexpr int kPasses = 4;         // 8-bit digits of the score half of the keys (histogram launches)
 constexpr int64_t kSelectSmallMax = 32768;   // scores one workgroup selects from in a single launch
 
 struct TopkPlan {
     int64_t padded;                // power of two >= k_sel (>= kSortBlock)
-    size_t off_sel, off_hist, off_state, off_rank, total;
+    size_t off_sel, off_hist, off_state, off_rank, off_ties, total;
+    int64_t chunks;                // groups of 1024 examples
 };
 
 static TopkPlan topk_plan(int64_t N, int64_t k_sel) {
@@ -39,6 +43,8 @@ static TopkPlan topk_plan(int64_t N, int64_t k_sel) {
     p.off_hist = o;  o += kPasses * 256 * 4;        // one histogram per pass
     p.off_state = o; o += (kPasses + 1) * 32 + 32;  // state before each pass and after the last; compaction cursor
     p.off_rank = o;  o += (size_t)pad * 4;          // ranks of the selected keys
+    p.chunks = (N + 1023) / 1024;
+    p.off_ties = o;  o += (size_t)(p.chunks + 1) * 4;   // examples at the threshold score per 1024 examples
     p.total = o;
     return p;
 }
@@ -108,7 +114,7 @@ topk_select_small_kernel(const float *score, int64_t N, unsigned long long k_sel
     unsigned long long prefix = 0, rem = k_sel;
     constexpr int kU = 8;
     const int64_t n_up = (N + 1024 * kU - 1) / (1024 * kU) * (1024 * kU);
-    for (int pass = 0; pass < 8; ++pass) {
+    for (int pass = 0; pass < 8; ++pass) {              // all eight digits of the 64-bit keys
         if (threadIdx.x < 256) h[threadIdx.x] = 0;
         if (threadIdx.x == 0) sh_done = 0;
         __syncthreads();
@@ -185,6 +191,7 @@ __device__ inline SelectState next_state(int pass, SelectState *state, const uns
     return after;
 }
 
+constexpr int kHistPer = 8;                         // examples per thread and round of the histogram
 // histogram of digit `pass` (0 = most significant byte) over keys whose higher digits equal the prefix
 // chosen so far; the pick of the pass before is done here first, by every workgroup for itself
 __global__ void __launch_bounds__(256)
@@ -200,53 +207,151 @@ topk_hist_kernel(const float *score, int64_t N, int pass, SelectState *state, un
     const int shift = 56 - 8 * pass;
     // bits above the current digit: pass 0 has none (mask 0), later passes compare them all
     const unsigned long long himask = pass == 0 ? 0ull : (~0ull << (shift + 8));
-    for (int64_t i0 = (int64_t)blockIdx.x * blockDim.x; i0 < N; i0 += (int64_t)gridDim.x * blockDim.x) {   // uniform per wavefront
-        const int64_t i = i0 + threadIdx.x;
-        const unsigned long long key = i < N ? make_key(score[i], i) : 0ull;
-        const bool match = i < N && ((key ^ prefix) & himask) == 0;
-        const unsigned int d = (unsigned int)(key >> shift) & 0xFFu;
-        // the leading digits of scores are few: the lanes that share the digit of the first matching lane
-        // are added at once, the others one by one
-        const unsigned long long act = __ballot(match);
-        if (act) {
-            const int leader = __ffsll((long long)act) - 1;
-            const unsigned int d0 = (unsigned int)__builtin_amdgcn_readlane((int)d, leader);
-            const unsigned long long same = __ballot(match && d == d0);
-            if ((int)(threadIdx.x & 63) == leader) atomicAdd(&h[d0], (unsigned int)__popcll(same));
-            if (match && d != d0) atomicAdd(&h[d], 1u);
+    // a workgroup takes kHistPer * 256 consecutive examples at a time (few workgroups: every one of them ends
+    // with up to 256 atomics on the same global bins), kHistPer loads in flight per thread
+    for (int64_t c0 = (int64_t)blockIdx.x * (256 * kHistPer); c0 < N; c0 += (int64_t)gridDim.x * (256 * kHistPer)) {   // uniform
+        float v[kHistPer];
+#pragma unroll
+        for (int u = 0; u < kHistPer; ++u) {
+            const int64_t i = c0 + u * 256 + threadIdx.x;
+            v[u] = i < N ? score[i] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < kHistPer; ++u) {
+            const int64_t i = c0 + u * 256 + threadIdx.x;
+            const unsigned long long key = make_key(v[u], i);
+            const bool match = i < N && ((key ^ prefix) & himask) == 0;
+            const unsigned int d = (unsigned int)(key >> shift) & 0xFFu;
+            // the leading digits of scores are few: the lanes that share the digit of the first matching
+            // lane are added at once, the others one by one
+            const unsigned long long act = __ballot(match);
+            if (act) {
+                const int leader = __ffsll((long long)act) - 1;
+                const unsigned int d0 = (unsigned int)__builtin_amdgcn_readlane((int)d, leader);
+                const unsigned long long same = __ballot(match && d == d0);
+                if ((int)(threadIdx.x & 63) == leader) atomicAdd(&h[d0], (unsigned int)__popcll(same));
+                if (match && d != d0) atomicAdd(&h[d], 1u);
+            }
         }
     }
     __syncthreads();
     if (h[threadIdx.x]) atomicAdd(&hist[pass * 256 + threadIdx.x], h[threadIdx.x]);
 }
 
-// Keys >= threshold (exactly k_sel of them) are gathered in any order; the slots from k_sel to
-// padded and the ranks are cleared.  A workgroup takes 1024 consecutive examples at a time and one
-// atomic for all it selects among them.
-// `last_pick`: the digit of the last pass is still to be picked from its histogram (large N).
 constexpr int kCompactPer = 4;                      // examples per thread and round
+constexpr int kChunk = 256 * kCompactPer;           // examples per round of a workgroup
+
+// After the last histogram: picks its digit; unless the threshold bucket is taken whole, counts the
+// examples whose score is the threshold score in every group of kChunk examples.
 __global__ void __launch_bounds__(256)
-topk_compact_kernel(const float *score, int64_t N, SelectState *state, const unsigned int *hist, int last_pick,
-                    unsigned long long *sel, unsigned int *rank, int64_t k_sel, int64_t padded) {
+topk_tie_count_kernel(const float *score, int64_t N, SelectState *state, const unsigned int *hist,
+                      unsigned int *ties) {
     __shared__ unsigned long long above[257];
     __shared__ SelectState sh;
+    __shared__ unsigned int cnt;
+    const SelectState fin = next_state(kPasses - 1, state, hist, above, &sh);
+    if (fin.done) return;                           // uniform
+    const uint32_t T = (uint32_t)(fin.prefix >> 32);
+    for (int64_t c0 = (int64_t)blockIdx.x * kChunk; c0 < N; c0 += (int64_t)gridDim.x * kChunk) {
+        if (threadIdx.x == 0) cnt = 0;
+        __syncthreads();
+        unsigned int mine = 0;
+#pragma unroll
+        for (int u = 0; u < kCompactPer; ++u) {
+            const int64_t i = c0 + u * 256 + threadIdx.x;
+            const bool tie = i < N && order_key(score[i]) == T;
+            mine += (unsigned int)__popcll(__ballot(tie));
+        }
+        if ((threadIdx.x & 63) == 0 && mine) atomicAdd(&cnt, mine);
+        __syncthreads();
+        if (threadIdx.x == 0) ties[c0 / kChunk] = cnt;
+        __syncthreads();
+    }
+}
+
+// One workgroup: exclusive scan, in place, of the per-group counts.
+__global__ void __launch_bounds__(1024)
+topk_tie_scan_kernel(const SelectState *state, unsigned int *ties, int64_t chunks) {
+    __shared__ unsigned int part[1024];
+    __shared__ unsigned int carry;
+    if (state[kPasses].done) return;                // written by the launch before
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    for (int64_t b = 0; b < chunks; b += 1024) {
+        const int64_t c = b + threadIdx.x;
+        const unsigned int v = c < chunks ? ties[c] : 0u;
+        part[threadIdx.x] = v;
+        __syncthreads();
+        for (int step = 1; step < 1024; step <<= 1) {   // Hillis-Steele, inclusive
+            const unsigned int add = (int)threadIdx.x >= step ? part[threadIdx.x - step] : 0u;
+            __syncthreads();
+            part[threadIdx.x] += add;
+            __syncthreads();
+        }
+        const unsigned int base = carry;
+        if (c < chunks) ties[c] = base + part[threadIdx.x] - v;
+        __syncthreads();
+        if (threadIdx.x == 1023) carry = base + part[1023];
+        __syncthreads();
+    }
+}
+
+// The selected keys (exactly k_sel of them) are gathered in any order; the slots from k_sel to
+// padded and the ranks are cleared.  A workgroup takes kChunk consecutive examples at a time and one
+// atomic for all it selects among them.  Selected: key >= threshold key when the selection ended
+// with a whole bucket; otherwise score above the threshold score T, or equal to it and among the
+// first `remaining` such examples in array order (`ties` holds how many precede each group).
+__global__ void __launch_bounds__(256)
+topk_compact_kernel(const float *score, int64_t N, SelectState *state, const unsigned int *ties,
+                    unsigned long long *sel, unsigned int *rank, int64_t k_sel, int64_t padded) {
     __shared__ unsigned int offs[4 * kCompactPer + 1];
-    const unsigned long long thr = last_pick ? next_state(kPasses - 1, state, hist, above, &sh).prefix
-                                             : state[kPasses].prefix;
+    __shared__ unsigned int toffs[4 * kCompactPer];
+    const SelectState fin = state[kPasses];
+    const bool by_position = !fin.done;             // uniform
+    const unsigned long long thr = by_position ? (fin.prefix | 0xFFFFFFFFull) + 1ull : fin.prefix;   // T + 1 in the score half
+    const bool none_above = by_position && thr == 0ull;     // T is the largest score key: nothing lies above it
+    const uint32_t T = (uint32_t)(fin.prefix >> 32);
     unsigned int *cursor = &state[kPasses].count;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t span = N > padded ? N : padded;
-    constexpr int kChunk = 256 * kCompactPer;
     for (int64_t c0 = (int64_t)blockIdx.x * kChunk; c0 < span; c0 += (int64_t)gridDim.x * kChunk) {   // uniform per workgroup
-        unsigned long long key[kCompactPer], mask[kCompactPer];
-        bool take[kCompactPer];
+        unsigned long long key[kCompactPer], mask[kCompactPer], tmask[kCompactPer];
+        bool take[kCompactPer], tie[kCompactPer];
 #pragma unroll
         for (int u = 0; u < kCompactPer; ++u) {
             const int64_t i = c0 + u * 256 + threadIdx.x;
             if (i >= k_sel && i < padded) sel[i] = 0;   // padding sorts last (real keys are > 0)
             if (i < padded) rank[i] = 0;
-            key[u] = 0; take[u] = false;
-            if (i < N) { key[u] = make_key(score[i], i); take[u] = key[u] >= thr; }
+            key[u] = 0; take[u] = false; tie[u] = false;
+            if (i < N) {
+                key[u] = make_key(score[i], i);
+                take[u] = !none_above && key[u] >= thr;
+                tie[u] = by_position && (uint32_t)(key[u] >> 32) == T;
+            }
+        }
+        if (by_position) {
+            // position of every example with the threshold score among all of them, in array order
+            // (element u * 256 + 64 * wave + lane of the group: order by u, then wave, then lane)
+#pragma unroll
+            for (int u = 0; u < kCompactPer; ++u) {
+                tmask[u] = __ballot(tie[u]);
+                if (lane == 0) toffs[u * 4 + wave] = (unsigned int)__popcll(tmask[u]);
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                unsigned int run = c0 < N ? ties[c0 / kChunk] : 0u;
+                for (int q = 0; q < 4 * kCompactPer; ++q) { const unsigned int v = toffs[q]; toffs[q] = run; run += v; }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < kCompactPer; ++u) {
+                const unsigned long long pos = (unsigned long long)toffs[u * 4 + wave] +
+                                               (unsigned long long)__popcll(tmask[u] & ((1ull << lane) - 1ull));
+                if (tie[u] && pos < fin.remaining) take[u] = true;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kCompactPer; ++u) {
             mask[u] = __ballot(take[u]);
             if (lane == 0) offs[wave * kCompactPer + u] = (unsigned int)__popcll(mask[u]);
         }
@@ -264,21 +369,28 @@ topk_compact_kernel(const float *score, int64_t N, SelectState *state, const uns
                                      (unsigned int)__popcll(mask[u] & ((1ull << lane) - 1ull));
             if (take[u] && (int64_t)pos < k_sel) sel[pos] = key[u];
         }
-        __syncthreads();                             // offs is reused by the next round
+        __syncthreads();                             // offs and toffs are reused by the next round
     }
 }
 
 // Rank of every selected key = how many selected keys are larger (keys are distinct): workgroup
-// (x, y) counts, for its 256 keys, the larger ones among keys [y * seg, (y + 1) * seg), staged in LDS 1024
-// at a time and read by all lanes at once (a broadcast).  k_sel^2 comparisons: for k_sel <= kSortOne only.
+// (x, y) counts, for its 256 * kRankPer keys, the larger ones among keys [y * seg, (y + 1) * seg),
+// staged in LDS 1024 at a time and read by all lanes at once (a broadcast).  k_sel^2 comparisons: for
+// k_sel <= kSortOne only.
+constexpr int kRankPer = 1;                         // keys per thread (two measured no faster)
 __global__ void __launch_bounds__(256)
 topk_rank_kernel(const unsigned long long *sel, int64_t k_sel, int64_t seg, unsigned int *rank) {
     __shared__ __attribute__((aligned(16))) unsigned long long tile[1024];
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const unsigned long long mine = i < k_sel ? sel[i] : ~0ull;
+    unsigned long long mine[kRankPer];
+    unsigned int cnt[kRankPer];
+#pragma unroll
+    for (int e = 0; e < kRankPer; ++e) {
+        const int64_t i = ((int64_t)blockIdx.x * kRankPer + e) * 256 + threadIdx.x;
+        mine[e] = i < k_sel ? sel[i] : ~0ull;
+        cnt[e] = 0;
+    }
     const int64_t j0 = (int64_t)blockIdx.y * seg;
     const int64_t j1 = j0 + seg < k_sel ? j0 + seg : k_sel;
-    unsigned int cnt = 0;
     for (int64_t jb = j0; jb < j1; jb += 1024) {
         __syncthreads();
         for (int t = threadIdx.x; t < 1024; t += 256) tile[t] = jb + t < j1 ? sel[jb + t] : 0ull;   // 0 is below every key
@@ -286,10 +398,15 @@ topk_rank_kernel(const unsigned long long *sel, int64_t k_sel, int64_t seg, unsi
 #pragma unroll 8
         for (int t = 0; t < 1024; t += 2) {
             const ulonglong2 pr = *(const ulonglong2 *)&tile[t];
-            cnt += (pr.x > mine) + (pr.y > mine);
+#pragma unroll
+            for (int e = 0; e < kRankPer; ++e) cnt[e] += (pr.x > mine[e]) + (pr.y > mine[e]);
         }
     }
-    if (i < k_sel && cnt) atomicAdd(&rank[i], cnt);
+#pragma unroll
+    for (int e = 0; e < kRankPer; ++e) {
+        const int64_t i = ((int64_t)blockIdx.x * kRankPer + e) * 256 + threadIdx.x;
+        if (i < k_sel && cnt[e]) atomicAdd(&rank[i], cnt[e]);
+    }
 }
 
 // idx / val in rank order
@@ -389,6 +506,7 @@ extern "C" qless_status qless_topk(const float *score, int64_t N, int64_t k_sel,
     unsigned int *hist = (unsigned int *)(w + p.off_hist);
     SelectState *state = (SelectState *)(w + p.off_state);
     unsigned int *rank = (unsigned int *)(w + p.off_rank);
+    unsigned int *ties = (unsigned int *)(w + p.off_ties);
 
     auto blocks_for = [](int64_t n) { int64_t b = (n + 255) / 256; if (b < 1) b = 1; if (b > 2048) b = 2048; return (unsigned)b; };
     const bool small = N <= kSelectSmallMax;
@@ -396,19 +514,29 @@ extern "C" qless_status qless_topk(const float *score, int64_t N, int64_t k_sel,
         hipLaunchKernelGGL(topk_select_small_kernel, dim3(1), dim3(1024), 0, st, score, N, (unsigned long long)k_sel, state);
     } else {
         hipLaunchKernelGGL(topk_init_kernel, dim3(1), dim3(256), 0, st, hist, state, (unsigned long long)k_sel);
+        int64_t hblocks = (N + 256 * kHistPer - 1) / (256 * kHistPer);
+        if (hblocks > 2048) hblocks = 2048;
         for (int pass = 0; pass < kPasses; ++pass)
-            hipLaunchKernelGGL(topk_hist_kernel, dim3(blocks_for(N)), dim3(256), 0, st, score, N, pass, state, hist);
+            hipLaunchKernelGGL(topk_hist_kernel, dim3((unsigned)hblocks), dim3(256), 0, st, score, N, pass, state, hist);
     }
     const int64_t span = N > p.padded ? N : p.padded;
-    int64_t cblocks = (span + 256 * kCompactPer - 1) / (256 * kCompactPer);
+    int64_t cblocks = (span + kChunk - 1) / kChunk;
     if (cblocks > 2048) cblocks = 2048;
+    if (!small) {
+        int64_t tblocks = (N + kChunk - 1) / kChunk;
+        if (tblocks > 2048) tblocks = 2048;
+        hipLaunchKernelGGL(topk_tie_count_kernel, dim3((unsigned)tblocks), dim3(256), 0, st, score, N, state,
+                           (const unsigned int *)hist, ties);
+        hipLaunchKernelGGL(topk_tie_scan_kernel, dim3(1), dim3(1024), 0, st, (const SelectState *)state, ties, p.chunks);
+    }
     hipLaunchKernelGGL(topk_compact_kernel, dim3((unsigned)cblocks), dim3(256), 0, st, score, N, state,
-                       (const unsigned int *)hist, small ? 0 : 1, sel, rank, k_sel, p.padded);
+                       (const unsigned int *)ties, sel, rank, k_sel, p.padded);
     if (p.padded <= kSortOne) {
         // few selected keys: rank every key among all of them, then write in rank order
         const unsigned kb = (unsigned)((k_sel + 255) / 256);
         const int64_t seg = 1024;
-        hipLaunchKernelGGL(topk_rank_kernel, dim3(kb, (unsigned)((k_sel + seg - 1) / seg)), dim3(256), 0, st,
+        const unsigned rb = (unsigned)((k_sel + 256 * kRankPer - 1) / (256 * kRankPer));
+        hipLaunchKernelGGL(topk_rank_kernel, dim3(rb, (unsigned)((k_sel + seg - 1) / seg)), dim3(256), 0, st,
                            (const unsigned long long *)sel, k_sel, seg, rank);
         hipLaunchKernelGGL(topk_scatter_kernel, dim3(kb), dim3(256), 0, st, (const unsigned long long *)sel,
                            (const unsigned int *)rank, k_sel, score, N, idx, val);

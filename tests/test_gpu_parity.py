@@ -317,6 +317,27 @@ def test_topk_identical_without_ties(N, k_sel):
     np.testing.assert_array_equal(val.cpu().numpy().view(np.uint32), ref_v.view(np.uint32))
 
 
+@pytest.mark.parametrize("N,k_sel", [(40000, 1), (40000, 777), (40000, 40000), (300000, 150001), (2000, 1999)])
+@pytest.mark.parametrize("kind", ["all_equal", "two_values", "top_is_max_float", "sign_codes"])
+def test_topk_threshold_ties_taken_in_index_order(kind, N, k_sel):
+    """Degenerate score sets: the threshold score is shared by many examples, of which the ones with the
+    smallest indices are selected."""
+    _say("topk ties %s N=%d k_sel=%d" % (kind, N, k_sel))
+    rng = np.random.default_rng(N + k_sel)
+    if kind == "all_equal":
+        s = np.full(N, 0.25, dtype=np.float32)
+    elif kind == "two_values":
+        s = np.where(rng.random(N) < 0.3, np.float32(1.5), np.float32(-2.0)).astype(np.float32)
+    elif kind == "top_is_max_float":
+        s = np.where(rng.random(N) < 0.5, np.float32(np.finfo(np.float32).max), np.float32(np.inf)).astype(np.float32)
+    else:                                                                    # what 1-bit codes give: a few hundred levels
+        s = ((rng.binomial(512, 0.5, size=N) - 256) / np.float32(512.0)).astype(np.float32)
+    ref_i, ref_v = oracle.topk(s, k_sel)
+    idx, val = Q.topk(torch.from_numpy(s).to(DEV), k_sel)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ref_i)
+    np.testing.assert_array_equal(val.cpu().numpy().view(np.uint32), ref_v.view(np.uint32))
+
+
 @pytest.mark.parametrize("mode", [Q.AGG_MAX, Q.AGG_MEAN])
 @pytest.mark.parametrize("N,ends", [(1000, [57]), (333, [1, 2, 9, 20, 29]), (5000, list(range(1, 65))), (1, [3])])
 def test_aggregate_over_validation_groups_bit_exact(mode, N, ends):
