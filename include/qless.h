@@ -178,8 +178,9 @@ qless_status qless_score16(const void *const *train16, const void *const *val16,
  *
  *   score  device, N fp32 (N < 2^32)     idx  device, k_sel int64
  *   val    device, k_sel fp32 receiving score[idx[t]], or NULL
- *   ws     device workspace of at least qless_topk_workspace(N, k_sel) bytes
- * 0 <= k_sel <= N.
+ *   ws     device workspace, 8-byte aligned, of at least qless_topk_workspace(N, k_sel) bytes
+ * 0 <= k_sel <= N.  Errors: QLESS_ERR_INVALID_ARG (sizes, null pointers, misaligned ws), QLESS_ERR_WORKSPACE
+ * (ws missing or too small), QLESS_ERR_UNSUPPORTED (N >= 2^32); nothing is launched then.
  * ------------------------------------------------------------------------------------------- */
 size_t qless_topk_workspace(int64_t N, int64_t k_sel);
 qless_status qless_topk(const float *score, int64_t N, int64_t k_sel, int64_t *idx, float *val,
