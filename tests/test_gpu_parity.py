@@ -338,6 +338,33 @@ def test_topk_threshold_ties_taken_in_index_order(kind, N, k_sel):
     np.testing.assert_array_equal(val.cpu().numpy().view(np.uint32), ref_v.view(np.uint32))
 
 
+def test_topk_random_sizes_and_score_sets():
+    """Seeded sweep over sizes on both sides of the single-workgroup limit, selection counts from 1 to N and score
+    sets with few or many equal values, signed zeros and infinities."""
+    rng = np.random.default_rng(20250201)
+    for case in range(40):
+        N = int(rng.choice([rng.integers(1, 300), rng.integers(300, 40000), rng.integers(40000, 400000)]))
+        k_sel = int(rng.choice([1, N, rng.integers(1, N + 1), max(1, N // 20)]))
+        kind = case % 4
+        if kind == 0:
+            s = rng.standard_normal(N).astype(np.float32)
+        elif kind == 1:
+            s = (rng.integers(-3, 4, size=N) / np.float32(4.0)).astype(np.float32)          # seven levels
+        elif kind == 2:
+            s = (rng.integers(-40000, 40000, size=N) / np.float32(65536.0)).astype(np.float32)
+        else:
+            s = rng.standard_normal(N).astype(np.float32)
+            s[rng.integers(0, N, size=max(1, N // 10))] = np.float32(np.inf)
+            s[rng.integers(0, N, size=max(1, N // 10))] = np.float32(-np.inf)
+            s[rng.integers(0, N, size=max(1, N // 10))] = np.float32(-0.0)
+            s[rng.integers(0, N, size=max(1, N // 10))] = np.float32(0.0)
+        _say("topk random case %d: N=%d k_sel=%d kind=%d" % (case, N, k_sel, kind))
+        ref_i, ref_v = oracle.topk(s, k_sel)
+        idx, val = Q.topk(torch.from_numpy(s).to(DEV), k_sel)
+        np.testing.assert_array_equal(idx.cpu().numpy(), ref_i, err_msg="case %d" % case)
+        np.testing.assert_array_equal(val.cpu().numpy().view(np.uint32), ref_v.view(np.uint32), err_msg="case %d" % case)
+
+
 @pytest.mark.parametrize("mode", [Q.AGG_MAX, Q.AGG_MEAN])
 @pytest.mark.parametrize("N,ends", [(1000, [57]), (333, [1, 2, 9, 20, 29]), (5000, list(range(1, 65))), (1, [3])])
 def test_aggregate_over_validation_groups_bit_exact(mode, N, ends):
