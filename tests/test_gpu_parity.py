@@ -398,3 +398,48 @@ def test_config1_end_to_end_planted_recovery():
         osc = oracle.score([oc], [orn], [ovc], [ovr], [1.0], 512, bits)
         np.testing.assert_array_equal(sc.cpu().numpy().view(np.uint32), osc.view(np.uint32))
         np.testing.assert_array_equal(idx.cpu().numpy(), oracle.topk(osc, 50)[0])
+
+
+@pytest.mark.parametrize("bits,M", [(1, 12), (8, 40), (4, 300)])
+def test_quantize_score_topk_replay_in_a_hip_graph(bits, M):
+    """The calls only enqueue kernels on the caller's stream (no allocation, no memset, no host copy), so a
+    caller may capture them in a HIP graph: every replay, with eager work and synchronisations in between,
+    gives the bits of the eager calls on the same inputs."""
+    _say("graph replay bits=%d M=%d" % (bits, M))
+    N, k, C, ksel = 5000, 1024, 2, 250
+    gen = torch.Generator(device=DEV); gen.manual_seed(bits * 100 + M)
+    Pt = [torch.randn(N, k, generator=gen, device=DEV) for _ in range(C)]
+    Pv = [torch.randn(M, k, generator=gen, device=DEV) for _ in range(C)]
+    vq = [Q.quantize(p, bits) for p in Pv]
+    vc, vr = [q[0] for q in vq], [q[2] for q in vq]
+    tc = [torch.empty(N, Q.code_bytes(k, bits), dtype=torch.uint8, device=DEV) for _ in range(C)]
+    tS = [torch.empty(N, dtype=torch.float32, device=DEV) for _ in range(C)]
+    tr = [torch.empty(N, dtype=torch.float32, device=DEV) for _ in range(C)]
+    sc = torch.empty(N, dtype=torch.float32, device=DEV)
+    ws_s = torch.empty(max(Q.score_workspace(N, M, k, bits, C), 16), dtype=torch.uint8, device=DEV)
+    ws_t = torch.empty(Q.topk_workspace(N, ksel), dtype=torch.uint8, device=DEV)
+    eta = [1.0, 0.5]
+
+    def run():
+        for c in range(C):
+            Q.quantize(Pt[c], bits, codes=tc[c], S=tS[c], rnorm=tr[c])
+        Q.score(tc, tr, vc, vr, eta, k, bits, score_out=sc, ws=ws_s)
+        return Q.topk(sc, ksel, ws=ws_t)
+
+    run()                                           # eager first: per-kernel attributes are set outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        g_idx, g_val = run()
+    for rep in range(3):
+        for c in range(C):
+            Pt[c].copy_(torch.randn(N, k, generator=gen, device=DEV))        # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got_i, got_v, got_s = g_idx.clone(), g_val.clone(), sc.clone()
+        sc.zero_()
+        e_idx, e_val = run()
+        torch.cuda.synchronize()
+        assert torch.equal(got_s, sc), rep
+        assert torch.equal(got_i, e_idx) and torch.equal(got_v, e_val), rep
