@@ -941,7 +941,8 @@ score_stream_mfma32_kernel(ScoreArgs a, const int8_t *vexp, int32_t Mp, int32_t 
 // Shape of the NW waves of a workgroup: WX waves across the val tile, NW / WX down the train
 // rows; each wave owns WR x WC accumulators of 32 x 32.  Train tile height MT = 32 WR NW / WX, val
 // tile width VT = 32 WC WX:
-//   M > 64: <2, 2, 2, 8> (64 x 64 per wave, 256 x 128 per workgroup);  M <= 64: <1, 2, 1, 8> (256 x 64);
+//   M > 64: <2, 2, 2, 8> (64 x 64 per wave, 256 x 128 per workgroup), or for sign codes <2, 3, 1, 8>
+//   (64 x 96 per wave, 512 x 96 per workgroup) when that pads M less;  M <= 64: <1, 2, 1, 8> (256 x 64);
 //   M <= 32: <1, 1, 1, 8> (256 x 32) or <1, 1, 1, 4> (128 x 32), whichever fills the chip more evenly.
 template <int BITS, int WR, int WC, int WX, int NW, bool VH = false>
 struct MfmaShape {
@@ -1389,6 +1390,9 @@ struct MfmaPlan { int32_t vt, Mp, kp; size_t off_vw, off_smax, total; };
 static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int bits, int C) {
     MfmaPlan p{};
     p.vt = M > 64 ? 128 : (M > 32 ? 64 : 32);
+    // sign codes: 512 x 96 tiles (64 x 96 per wave) where 96-wide tiles pad the validation set less than
+    // 128-wide ones (M = 285: 288 instead of 384 columns)
+    if (bits == 1 && M > 64 && (M + 95) / 96 * 96 < (M + 127) / 128 * 128) p.vt = 96;
     p.Mp = (M + p.vt - 1) / p.vt * p.vt;
     const int ke = narrow_stage_elements(bits, p.vt);                 // MfmaShape::KE of the shape used
     p.kp = (k + ke - 1) / ke * ke;
@@ -1467,7 +1471,10 @@ static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st) {
     w.vrow = BITS == 1 ? (p.vt > 64 ? p.kp / 2 : 0) : (BITS == 2 ? p.kp / 2 : p.kp);
     hipLaunchKernelGGL((score_prepare_kernel<BITS, F16>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
     qless_status rc;
-    if (p.vt == 128) rc = launch_mfma_shape<BITS, 2, 2, 2, 8, F16>(a, w, 0, st);
+    if (p.vt == 96) {
+        if constexpr (BITS == 1) rc = launch_mfma_shape<BITS, 2, 3, 1, 8, F16>(a, w, 0, st);
+        else rc = QLESS_ERR_UNSUPPORTED;
+    } else if (p.vt == 128) rc = launch_mfma_shape<BITS, 2, 2, 2, 8, F16>(a, w, 0, st);
     else if (p.vt == 64) {
         const NarrowChoice c = choose_narrow<BITS, 2>(a.N);
         if (c.nw == 8) rc = launch_mfma_shape<BITS, 1, 2, 1, 8, F16>(a, w, c.per_cu, st);
@@ -1535,7 +1542,7 @@ static qless_status launch_stream_mfma(const ScoreArgs &a, int bits, const Strea
 // 8 rings of nb slots (nb = 0: does not fit).  Narrower windows cost more barriers, deeper rings
 // hide more memory latency: the widest window that leaves room for three slots, else for two.
 #ifndef QLESS_STREAM32_MAX_M
-#define QLESS_STREAM32_MAX_M 320
+#define QLESS_STREAM32_MAX_M 192
 #endif
 constexpr int kStream32MaxVal = QLESS_STREAM32_MAX_M;                // 1-bit: beyond this the tile kernel takes over
 struct Stream32Plan { int wb, nb; size_t val_bytes, lds; };

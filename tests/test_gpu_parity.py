@@ -201,7 +201,9 @@ def _datastore(n, k, bits, C, seed):
                                      (333, 12, 128, 2), (161, 9, 2048, 4), (50, 2, 8192, 4), (7, 6, 640, 1),
                                      (500, 40, 1024, 3), (1000, 64, 512, 2), (333, 100, 1024, 2), (129, 17, 8192, 4),
                                      (4100, 33, 512, 1), (64, 320, 1024, 2), (2000, 129, 2048, 3),
-                                     (600, 513, 192, 3), (300, 1024, 576, 4), (520, 700, 64, 1), (257, 600, 8192, 2)])
+                                     (600, 513, 192, 3), (300, 1024, 576, 4), (520, 700, 64, 1), (257, 600, 8192, 2),
+                                     (500, 285, 512, 3), (700, 540, 1024, 2), (520, 260, 2048, 2), (300, 1030, 640, 1),
+                                     (1100, 192, 1024, 2), (600, 193, 512, 2)])
 def test_score_bit_exact(bits, N, M, k, C):
     _say("score bits=%d N=%d M=%d k=%d C=%d" % (bits, N, M, k, C))
     tc, tr = _datastore(N, k, bits, C, 1000 + bits)
