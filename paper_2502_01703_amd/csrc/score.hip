@@ -421,10 +421,15 @@ __device__ inline void wait_vmcnt_even(int n) {
     }
 }
 
-// MV = 8 or 16 validation rows held in LDS (M <= MV); NW wavefronts per workgroup, one workgroup per compute unit
+// MV = 8 or 16 validation rows held in LDS (M <= MV); NW wavefronts per workgroup, one workgroup per compute unit.
+// A launch covers the checkpoints c0 .. c1 - 1 (all of them when their validation rows fit in LDS next
+// to the rings; else groups of cg, one launch each): a launch that does not start at checkpoint 0
+// continues from the fp32 sums the launch before left in `partial` ([N][16]), one that does not end
+// at the last checkpoint leaves its sums there, so the order of the additions is that of one launch.
 template <int BITS, int MV, int NW, int PPS>
 __global__ void __launch_bounds__(64 * NW, NW / 4)
-score_stream_mfma_kernel(ScoreArgs a, int64_t rb_each, int64_t rb_extra, int nb, unsigned ring_off) {
+score_stream_mfma_kernel(ScoreArgs a, int64_t rb_each, int64_t rb_extra, int nb, unsigned ring_off,
+                         int c0, int c1, int cg, float *partial) {
     constexpr int NPL = BITS;                   // bit planes per row
     constexpr int L = 2 * NPL * PPS;            // 1 KB copies per ring slot (PPS panels, one slice)
     constexpr int SLOT = L * 1024;
@@ -434,7 +439,7 @@ score_stream_mfma_kernel(ScoreArgs a, int64_t rb_each, int64_t rb_extra, int nb,
     // LDS: [C][MV] validation rows of cb + 16 bytes | [C][MV] weights | per wave a ring of nb slots
     extern __shared__ __attribute__((aligned(16))) unsigned char vlds[];
     const int lane = threadIdx.x & 63;
-    const int cg = lane & 7, crr = lane >> 3;  // copy role: position and row inside a 1 KB copy
+    const int cgp = lane & 7, crr = lane >> 3; // copy role: position and row inside a 1 KB copy
     const int l16 = lane & 15, kg = lane >> 4; // matrix role: row of the panel and chunk group
     const int wv_id = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // 8-row blocks are dealt out evenly: wavefront w takes rb_each blocks, the first rb_extra
@@ -447,22 +452,22 @@ score_stream_mfma_kernel(ScoreArgs a, int64_t rb_each, int64_t rb_extra, int nb,
     const int plane = a.k / 8;                  // bytes per bit plane, a multiple of 16 here
     const int nsl = (plane + 127) / 128;        // 128-byte slices per plane
     const int vstride = cb + 16;                // rows 4 banks apart: 8 rows read together do not collide
-    const float *wlds = (const float *)(vlds + (size_t)a.C * MV * vstride);
+    const float *wlds = (const float *)(vlds + (size_t)cg * MV * vstride);
     unsigned char *ring = vlds + ring_off + (size_t)wv_id * nb * SLOT;
     const unsigned ring_lds = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)ring);
 
     // validation codes and weights eta * rnorm' of every checkpoint -> LDS (rows past M repeat the
     // last one; they are masked at the output)
     {
-        const int per_row = cb / 16, total = a.C * MV * per_row;
+        const int per_row = cb / 16, total = (c1 - c0) * MV * per_row;
         for (int i = threadIdx.x; i < total; i += 64 * NW) {
-            const int c16 = i % per_row, rowi = i / per_row, j = rowi % MV, ci = rowi / MV;
+            const int c16 = i % per_row, rowi = i / per_row, j = rowi % MV, ci = c0 + rowi / MV;
             const int jc = j < a.M ? j : a.M - 1;
             *(uint4 *)(vlds + (size_t)rowi * vstride + c16 * 16) = *(const uint4 *)(a.vc[ci] + (int64_t)jc * cb + c16 * 16);
         }
-        float *wdst = (float *)(vlds + (size_t)a.C * MV * vstride);
-        for (int i = threadIdx.x; i < a.C * MV; i += 64 * NW) {
-            const int j = i % MV, ci = i / MV;
+        float *wdst = (float *)(vlds + (size_t)cg * MV * vstride);
+        for (int i = threadIdx.x; i < (c1 - c0) * MV; i += 64 * NW) {
+            const int j = i % MV, ci = c0 + i / MV;
             wdst[i] = __fmul_rn(a.eta[ci], a.vr[ci][j < a.M ? j : a.M - 1]);
         }
         __syncthreads();
@@ -475,12 +480,12 @@ score_stream_mfma_kernel(ScoreArgs a, int64_t rb_each, int64_t rb_extra, int nb,
         const int rows = r_end - rp < PASS ? (int)(r_end - rp) : PASS;
         const int np = (rows + 15) / 16;
         const int ns = (np + PPS - 1) / PPS;     // ring slots per slice
-        const int T = a.C * nsl * ns;            // ring slots the pass consumes
+        const int T = (c1 - c0) * nsl * ns;      // ring slots the pass consumes
         const int last = rows - 1;
         // producer state: the next slot to request is (f_ci, f_sl, f_p) into ring position f_pos
-        int f_ci = 0, f_sl = 0, f_p = 0, f_pos = 0, f_it = 0;
+        int f_ci = c0, f_sl = 0, f_p = 0, f_pos = 0, f_it = 0;
         auto fetch = [&]() {
-            int off = f_sl * 128 + ((cg ^ crr) << 4);
+            int off = f_sl * 128 + ((cgp ^ crr) << 4);
             if (off >= plane) off = plane - 16;                              // zeroed on the validation side
             const unsigned char *base = a.tc[f_ci] + rp * cb;               // wave-uniform
             const unsigned slot = ring_lds + (unsigned)f_pos * (unsigned)SLOT;
@@ -502,15 +507,26 @@ score_stream_mfma_kernel(ScoreArgs a, int64_t rb_each, int64_t rb_extra, int nb,
         for (int p = 0; p < NP; ++p)
 #pragma unroll
             for (int v = 0; v < 4; ++v) { acc[p][v] = 0.0f; facc[p][v] = 0.0f; }
+        if (c0 > 0) {                            // continue from the sums of the checkpoints before
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+                if (p < np && p * 16 + l16 < rows) {
+                    const float4 pv = *(const float4 *)(partial + (rp + p * 16 + l16) * 16 + 4 * kg);
+                    facc[p][0] = pv.x; facc[p][1] = pv.y; facc[p][2] = pv.z; facc[p][3] = pv.w;
+                }
+            // the loads are awaited here, before the first ring copies: a wait for them later would drain the ring
+#pragma unroll
+            for (int p = 0; p < NP; ++p) asm volatile("" : "+v"(facc[p][0]), "+v"(facc[p][1]), "+v"(facc[p][2]), "+v"(facc[p][3]));
+        }
 
         for (int i = 0; i < nb - 1 && i < T; ++i) fetch();
         int it = 0, pos = 0;
-        for (int ci = 0; ci < a.C; ++ci) {
+        for (int ci = c0; ci < c1; ++ci) {
             for (int sl = 0; sl < nsl; ++sl) {
                 // validation fragments of this slice: 8 K steps (2 chunks x 4 dwords) of 4 FP4 dwords
                 i32x8 vf[8];
                 {
-                    const unsigned char *vrow = vlds + (size_t)(ci * MV + (l16 & (MV - 1))) * vstride;
+                    const unsigned char *vrow = vlds + (size_t)((ci - c0) * MV + (l16 & (MV - 1))) * vstride;
 #pragma unroll
                     for (int c2 = 0; c2 < 2; ++c2) {
                         const int off = sl * 128 + (4 * c2 + kg) * 16;
@@ -574,7 +590,7 @@ score_stream_mfma_kernel(ScoreArgs a, int64_t rb_each, int64_t rb_extra, int nb,
                     const float rt = a.tr[ci][rp + (p * 16 + l16 < rows ? p * 16 + l16 : last)];
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const float wv = wlds[ci * MV + ((4 * kg + v) & (MV - 1))];
+                        const float wv = wlds[(ci - c0) * MV + ((4 * kg + v) & (MV - 1))];
                         const float t = __fmul_rn(__fmul_rn(acc[p][v], rt), wv);      // acc holds the integer D exactly
                         facc[p][v] = __fadd_rn(facc[p][v], t);
                         acc[p][v] = 0.0f;
@@ -583,6 +599,13 @@ score_stream_mfma_kernel(ScoreArgs a, int64_t rb_each, int64_t rb_extra, int nb,
             }
         }
         // outputs: lane (row, group kg) holds validation vectors 4 kg .. 4 kg + 3
+        if (c1 < a.C) {                          // more checkpoints follow: leave the sums for the next launch
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+                if (p < np && p * 16 + l16 < rows)
+                    *(float4 *)(partial + (rp + p * 16 + l16) * 16 + 4 * kg) = float4{facc[p][0], facc[p][1], facc[p][2], facc[p][3]};
+            continue;
+        }
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             if (p < np) {
@@ -1501,18 +1524,27 @@ static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st) {
 // LDS plan of score_stream_mfma_kernel: validation rows and weights, then 8 rings of nb slots
 // (nb = 0: does not fit)
 constexpr int kStreamWaves = 8;                                      // wavefronts per workgroup of the kernel
-struct StreamMfmaPlan { int mv, nb; size_t val_bytes, lds; };
+// cg: checkpoints per launch, the most whose validation rows leave room for rings of two slots (fewer
+// than C: the launches hand their fp32 sums on through a workspace of N x 16 floats)
+struct StreamMfmaPlan { int mv, nb, cg; size_t val_bytes, lds; };
 static StreamMfmaPlan stream_mfma_plan(int32_t M, int32_t k, int bits, int C) {
     StreamMfmaPlan p{};
     p.mv = M <= 8 ? 8 : 16;
-    p.val_bytes = (((size_t)C * p.mv * ((size_t)k * bits / 8 + 16 + 4)) + 1023) & ~(size_t)1023;
     const size_t slot = 4096;                                        // 32 / bits rows of one 128-byte slice
-    const size_t room = 158 * 1024 > p.val_bytes ? (158 * 1024 - p.val_bytes) / (kStreamWaves * slot) : 0;
-    p.nb = room < 2 ? 0 : (room > 5 ? 5 : (int)room);                // waits: 4 copies per slot x (nb - 2) <= 14
+    for (p.cg = C; p.cg >= 1; --p.cg) {
+        p.val_bytes = (((size_t)p.cg * p.mv * ((size_t)k * bits / 8 + 16 + 4)) + 1023) & ~(size_t)1023;
+        const size_t room = 158 * 1024 > p.val_bytes ? (158 * 1024 - p.val_bytes) / (kStreamWaves * slot) : 0;
+        p.nb = room < 2 ? 0 : (room > 5 ? 5 : (int)room);            // waits: 4 copies per slot x (nb - 2) <= 14
+        if (p.nb >= 2) break;
+    }
+    if (p.cg < 1) { p.cg = 0; p.nb = 0; }
     p.lds = p.val_bytes + (size_t)kStreamWaves * p.nb * slot;
     return p;
 }
-static qless_status launch_stream_mfma(const ScoreArgs &a, int bits, const StreamMfmaPlan &sp, hipStream_t st) {
+static size_t stream_mfma_partial_bytes(const StreamMfmaPlan &p, int64_t N, int C) {
+    return p.nb >= 2 && p.cg < C ? (size_t)N * 16 * sizeof(float) : 0;
+}
+static qless_status launch_stream_mfma(const ScoreArgs &a, int bits, const StreamMfmaPlan &sp, float *partial, hipStream_t st) {
     constexpr int NW = kStreamWaves;
     static std::atomic<bool> allowed{false};                         // LDS above 64 KB has to be allowed per kernel
     if (!allowed) {
@@ -1531,10 +1563,13 @@ static qless_status launch_stream_mfma(const ScoreArgs &a, int bits, const Strea
     const int64_t each = total_rb / waves, extra = total_rb % waves;
     const dim3 grid((unsigned)groups), block(64 * NW);
     const unsigned ro = (unsigned)sp.val_bytes;
-    if (bits == 1 && sp.mv == 8) hipLaunchKernelGGL((score_stream_mfma_kernel<1, 8, NW, 2>), grid, block, sp.lds, st, a, each, extra, sp.nb, ro);
-    else if (bits == 1) hipLaunchKernelGGL((score_stream_mfma_kernel<1, 16, NW, 2>), grid, block, sp.lds, st, a, each, extra, sp.nb, ro);
-    else if (sp.mv == 8) hipLaunchKernelGGL((score_stream_mfma_kernel<2, 8, NW, 1>), grid, block, sp.lds, st, a, each, extra, sp.nb, ro);
-    else hipLaunchKernelGGL((score_stream_mfma_kernel<2, 16, NW, 1>), grid, block, sp.lds, st, a, each, extra, sp.nb, ro);
+    for (int c0 = 0; c0 < a.C; c0 += sp.cg) {
+        const int c1 = c0 + sp.cg < a.C ? c0 + sp.cg : a.C;
+        if (bits == 1 && sp.mv == 8) hipLaunchKernelGGL((score_stream_mfma_kernel<1, 8, NW, 2>), grid, block, sp.lds, st, a, each, extra, sp.nb, ro, c0, c1, sp.cg, partial);
+        else if (bits == 1) hipLaunchKernelGGL((score_stream_mfma_kernel<1, 16, NW, 2>), grid, block, sp.lds, st, a, each, extra, sp.nb, ro, c0, c1, sp.cg, partial);
+        else if (sp.mv == 8) hipLaunchKernelGGL((score_stream_mfma_kernel<2, 8, NW, 1>), grid, block, sp.lds, st, a, each, extra, sp.nb, ro, c0, c1, sp.cg, partial);
+        else hipLaunchKernelGGL((score_stream_mfma_kernel<2, 16, NW, 1>), grid, block, sp.lds, st, a, each, extra, sp.nb, ro, c0, c1, sp.cg, partial);
+    }
     return launch_status();
 }
 
@@ -1642,8 +1677,12 @@ using namespace qless;
 
 extern "C" size_t qless_score_workspace(int64_t N, int32_t M, int32_t k, int bits, int C) {
     if (N < 0 || M < 1 || k <= 0 || C < 1 || !valid_bits(bits)) return 0;
-    if (!use_mfma_path(bits, M, k)) return 0;
-    return mfma_plan(N, M, k, bits, C).total;
+    size_t need = 0;
+    if (bits <= 2 && M <= kStreamMfmaVal && k % 128 == 0)      // checkpoint groups hand their sums on through the workspace
+        need = stream_mfma_partial_bytes(stream_mfma_plan(M, k, bits, C), N, C);
+    if (!use_mfma_path(bits, M, k)) return need;
+    const size_t tiles = mfma_plan(N, M, k, bits, C).total;
+    return tiles > need ? tiles : need;
 }
 
 extern "C" qless_status qless_score(const void *const *train_codes, const float *const *train_rnorm,
@@ -1667,7 +1706,12 @@ extern "C" qless_status qless_score(const void *const *train_codes, const float 
     hipStream_t st = (hipStream_t)stream;
     if (bits <= 2 && M <= kStreamMfmaVal && k % 128 == 0) {
         const StreamMfmaPlan sp = stream_mfma_plan(M, k, bits, C);
-        if (sp.nb >= 2) return launch_stream_mfma(a, bits, sp, st);
+        if (sp.nb >= 2) {
+            const size_t need = stream_mfma_partial_bytes(sp, N, C);
+            if (need && (!ws || ws_bytes < need)) return QLESS_ERR_WORKSPACE;
+            if (need && (uintptr_t)ws % 16) return QLESS_ERR_WORKSPACE;
+            return launch_stream_mfma(a, bits, sp, (float *)ws, st);
+        }
     }
     if (bits == 1 && M <= kStream32MaxVal && k % 512 == 0 && stream_mfma32_plan(1, 2, 64, k, C).nb >= 2)
         return launch_stream_mfma32(a, st);

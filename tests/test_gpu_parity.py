@@ -203,7 +203,9 @@ def _datastore(n, k, bits, C, seed):
                                      (4100, 33, 512, 1), (64, 320, 1024, 2), (2000, 129, 2048, 3),
                                      (600, 513, 192, 3), (300, 1024, 576, 4), (520, 700, 64, 1), (257, 600, 8192, 2),
                                      (500, 285, 512, 3), (700, 540, 1024, 2), (520, 260, 2048, 2), (300, 1030, 640, 1),
-                                     (1100, 192, 1024, 2), (600, 193, 512, 2)])
+                                     (1100, 192, 1024, 2), (600, 193, 512, 2),
+                                     (300, 12, 8192, 4), (1000, 16, 8192, 3), (200, 9, 16384, 4), (100, 16, 32768, 4),
+                                     (150, 5, 65536, 2)])
 def test_score_bit_exact(bits, N, M, k, C):
     _say("score bits=%d N=%d M=%d k=%d C=%d" % (bits, N, M, k, C))
     tc, tr = _datastore(N, k, bits, C, 1000 + bits)
