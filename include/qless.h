@@ -140,7 +140,9 @@ qless_status qless_project_quantize(const void *G, qless_dtype dt, int64_t n, in
  *   ws         device workspace, 16-byte aligned, of at least qless_score_workspace(N, M, k, bits, C)
  *              bytes (0 for the configurations that need none).  It holds the validation codes
  *              expanded for the tiled matrix-core path and the running row maxima; the paths that
- *              stream the train codes once (bit-plane codes, few validation vectors) leave it untouched.
+ *              stream the train codes once (bit-plane codes, few validation vectors) leave it untouched,
+ *              unless the checkpoints are scored in groups of launches (their validation rows do not
+ *              all fit in LDS): then it carries N x 16 fp32 sums from one launch to the next.
  * N == 0 is valid; M >= 1.  Whichever kernels a shape selects, the results are the same bits.  With
  * more than 64 validation vectors a call may consist of several launches that update score in
  * place: score and full are complete once the stream has run the whole call.
