@@ -294,7 +294,8 @@ def test_score16_matches_oracle_from_the_same_store(N, M, k, C):
 
 
 @pytest.mark.parametrize("N,k_sel", [(1000, 50), (100000, 5000), (100000, 20000), (5000, 5000),
-                                     (4097, 4097), (7, 0), (1, 1), (270000, 13500), (1048576, 9), (1300000, 70000)])
+                                     (4097, 4097), (7, 0), (1, 1), (270000, 13500), (1048576, 9), (1300000, 70000),
+                                     (32768, 1000), (32769, 1000), (33000, 33000), (40000, 16384), (40000, 16385)])
 def test_topk_identical_with_ties(N, k_sel):
     _say("topk N=%d k_sel=%d" % (N, k_sel))
     rng = np.random.default_rng(N + k_sel)
