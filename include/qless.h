@@ -189,6 +189,23 @@ qless_status qless_topk(const float *score, int64_t N, int64_t k_sel, int64_t *i
                         void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * qless_topk for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, same
+ * results and same errors as qless_topk, without ws: the workspace is a fixed array inside the
+ * library's device image (about 0.8 MB on every GPU the library runs on, held until the process
+ * ends).  Limits: N <= QLESS_TOPK_NOALLOC_MAX_N and k_sel <= QLESS_TOPK_NOALLOC_MAX_SEL, beyond
+ * them QLESS_ERR_UNSUPPORTED and nothing is launched.  The call allocates and frees nothing.  All
+ * calls on one GPU share that GPU's array: two calls that overlap on one GPU (different streams
+ * without ordering between them) race; calls on one stream, or ordered by events, are safe, and a
+ * call needs nothing of what the call before left in the array.  The array's address is looked up
+ * on the first call on each device (no allocation, no device work).
+ * ------------------------------------------------------------------------------------------- */
+#define QLESS_TOPK_NOALLOC_MAX_N 4194304
+#define QLESS_TOPK_NOALLOC_MAX_SEL 65536
+qless_status qless_topk_noalloc(const float *score, int64_t N, int64_t k_sel, int64_t *idx, float *val,
+                                void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Aggregation of pairwise influences over groups of validation examples (Sec. 4.1 selects by
  * "cumulative influence scores" and evaluates on benchmarks with sub-tasks, without a formula for
  * combining validation examples; qless_score reduces by the maximum over all of them).  From the

@@ -16,6 +16,7 @@ _lib = None
 F32, BF16 = 0, 1
 RADEMACHER, GAUSSIAN = 0, 1
 MAX_CHECKPOINTS = 16
+TOPK_NOALLOC_MAX_N, TOPK_NOALLOC_MAX_SEL = 4194304, 65536     # QLESS_TOPK_NOALLOC_MAX_* of qless.h
 
 _c = ctypes
 _i64, _i32, _u64, _u32, _vp, _sz = (_c.c_int64, _c.c_int32, _c.c_uint64, _c.c_uint32, _c.c_void_p,
@@ -40,6 +41,7 @@ EXPORTS = {
     "qless_score16": (_c.c_int, [_vp, _vp, _vp, _c.c_int, _i64, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
     "qless_topk_workspace": (_sz, [_i64, _i64]),
     "qless_topk": (_c.c_int, [_vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
+    "qless_topk_noalloc": (_c.c_int, [_vp, _i64, _i64, _vp, _vp, _vp]),
     "qless_aggregate": (_c.c_int, [_vp, _i64, _i32, _vp, _c.c_int, _c.c_int, _vp, _vp]),
 }
 
@@ -254,6 +256,18 @@ def topk(score_vec, k_sel, want_val=True, ws=None):
                             _vp(val.data_ptr()) if want_val else None, _vp(w.data_ptr()), w.numel(),
                             _stream()), "qless_topk")
     return (idx, val) if want_val else idx
+
+
+def topk_noalloc(score_vec, idx, val=None):
+    """qless_topk_noalloc: as topk, into the caller's idx (int64 [k_sel]) and val (fp32 [k_sel] or None);
+    the call itself allocates nothing (the workspace is the library's own device array)."""
+    assert score_vec.is_cuda and score_vec.dtype == torch.float32 and score_vec.is_contiguous()
+    assert idx.is_cuda and idx.dtype == torch.int64 and idx.is_contiguous()
+    assert val is None or (val.is_cuda and val.dtype == torch.float32 and val.numel() == idx.numel())
+    _check(lib().qless_topk_noalloc(_vp(score_vec.data_ptr()), score_vec.numel(), idx.numel(),
+                                    _vp(idx.data_ptr()), _vp(val.data_ptr()) if val is not None else None,
+                                    _stream()), "qless_topk_noalloc")
+    return idx, val
 
 
 AGG_MAX, AGG_MEAN = 0, 1

@@ -19,6 +19,8 @@
 //   its rank: two short launches); above that, a bitonic network (LDS spans of 4096 keys with global
 //   steps in between), then  4. decode indices and gather the scores.
 #include "common.h"
+#include <atomic>
+#include <mutex>
 
 namespace qless {
 
@@ -490,17 +492,11 @@ extern "C" size_t qless_topk_workspace(int64_t N, int64_t k_sel) {
     return topk_plan(N, k_sel).total;
 }
 
-extern "C" qless_status qless_topk(const float *score, int64_t N, int64_t k_sel, int64_t *idx,
-                                   float *val, void *ws, size_t ws_bytes, void *stream) {
-    if (N < 0 || k_sel < 0 || k_sel > N) return QLESS_ERR_INVALID_ARG;
-    if (N > 0 && !score) return QLESS_ERR_INVALID_ARG;
-    if (k_sel > 0 && !idx) return QLESS_ERR_INVALID_ARG;
-    if (N >= ((int64_t)1 << 32)) return QLESS_ERR_UNSUPPORTED;
-    if (k_sel == 0) return QLESS_OK;
+// Enqueues the whole selection on `st`; `ws` holds at least topk_plan(N, k_sel).total bytes, 8-byte
+// aligned; 1 <= k_sel <= N < 2^32, all pointers checked by the caller.
+static qless_status topk_run(const float *score, int64_t N, int64_t k_sel, int64_t *idx, float *val,
+                             void *ws, hipStream_t st) {
     const TopkPlan p = topk_plan(N, k_sel);
-    if (!ws || ws_bytes < p.total) return QLESS_ERR_WORKSPACE;
-    if ((uintptr_t)ws % 8) return QLESS_ERR_INVALID_ARG;
-    hipStream_t st = (hipStream_t)stream;
     unsigned char *w = (unsigned char *)ws;
     unsigned long long *sel = (unsigned long long *)(w + p.off_sel);
     unsigned int *hist = (unsigned int *)(w + p.off_hist);
@@ -552,4 +548,69 @@ extern "C" qless_status qless_topk(const float *score, int64_t N, int64_t k_sel,
     }
     hipLaunchKernelGGL(topk_emit_kernel, dim3(blocks_for(k_sel)), dim3(256), 0, st, sel, k_sel, score, N, idx, val);
     return launch_status();
+}
+
+static qless_status topk_check(const float *score, int64_t N, int64_t k_sel, const int64_t *idx) {
+    if (N < 0 || k_sel < 0 || k_sel > N) return QLESS_ERR_INVALID_ARG;
+    if (N > 0 && !score) return QLESS_ERR_INVALID_ARG;
+    if (k_sel > 0 && !idx) return QLESS_ERR_INVALID_ARG;
+    if (N >= ((int64_t)1 << 32)) return QLESS_ERR_UNSUPPORTED;
+    return QLESS_OK;
+}
+
+extern "C" qless_status qless_topk(const float *score, int64_t N, int64_t k_sel, int64_t *idx,
+                                   float *val, void *ws, size_t ws_bytes, void *stream) {
+    const qless_status rc = topk_check(score, N, k_sel, idx);
+    if (rc != QLESS_OK || k_sel == 0) return rc;
+    if (!ws || ws_bytes < topk_plan(N, k_sel).total) return QLESS_ERR_WORKSPACE;
+    if ((uintptr_t)ws % 8) return QLESS_ERR_INVALID_ARG;
+    return topk_run(score, N, k_sel, idx, val, ws, (hipStream_t)stream);
+}
+
+// ------------------------------------------------------------------------------------------
+// The same selection for callers that cannot allocate: its workspace is a file-scope device
+// array, one copy per GPU.  On the host the array's name only stands for the symbol; the
+// address the kernels receive is the one hipGetSymbolAddress returns on each device.
+// ------------------------------------------------------------------------------------------
+constexpr int64_t kNoAllocMaxN = QLESS_TOPK_NOALLOC_MAX_N;
+constexpr int64_t kNoAllocMaxSel = QLESS_TOPK_NOALLOC_MAX_SEL;
+// topk_plan(kNoAllocMaxN, kNoAllocMaxSel).total, rounded up (checked at set-up)
+constexpr size_t kScratchBytes = (size_t)kNoAllocMaxSel * 12 + 4096 + 256 + (size_t)(kNoAllocMaxN / 1024 + 2) * 4 + 256;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_mutex;
+static std::atomic<void *> scratch_ptr[kMaxDevices];
+
+// device address of this GPU's copy of `scratch` (resolved once per device, with that device current)
+static qless_status scratch_address(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return QLESS_ERR_DEVICE;
+    void *p = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> lock(scratch_mutex);
+        p = scratch_ptr[dev].load(std::memory_order_relaxed);
+        if (!p) {
+            if (topk_plan(kNoAllocMaxN, kNoAllocMaxSel).total > kScratchBytes) return QLESS_ERR_WORKSPACE;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return QLESS_ERR_DEVICE;
+            scratch_ptr[dev].store(p, std::memory_order_release);
+        }
+    }
+    *out = p;
+    return QLESS_OK;
+}
+
+extern "C" qless_status qless_topk_noalloc(const float *score, int64_t N, int64_t k_sel, int64_t *idx,
+                                           float *val, void *stream) {
+    const qless_status rc = topk_check(score, N, k_sel, idx);
+    if (rc != QLESS_OK) return rc;
+    if (N > kNoAllocMaxN || k_sel > kNoAllocMaxSel) return QLESS_ERR_UNSUPPORTED;
+    if (k_sel == 0) return QLESS_OK;
+    void *ws = nullptr;
+    const qless_status rs = scratch_address(&ws);
+    if (rs != QLESS_OK) return rs;
+    // every word of the workspace that a launch reads is written earlier in the same call (init /
+    // select kernels clear histograms, states and the cursor; the compaction clears padding and ranks;
+    // the tie counts are written before they are scanned), so nothing of the call before survives
+    return topk_run(score, N, k_sel, idx, val, ws, (hipStream_t)stream);
 }
