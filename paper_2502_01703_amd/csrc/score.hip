@@ -244,6 +244,7 @@ constexpr int log2c(int x) { return x <= 1 ? 0 : 1 + log2c(x / 2); }
 struct ScorePrep {                             // workspace views (device pointers)
     int8_t *vexp;                              // [C][Mp][kp]
     float *vw;                                 // [C][Mp]
+    int32_t *vbias;                            // [C][Mp] sign codes on wide tiles: what the scaled validation codes leave to add to a dot product
     unsigned int *smax;                        // [N] order-preserving keys of the row maxima
     int32_t Mp, kp;                            // padded validation rows / elements per row
     int32_t vrow;                              // bytes per expanded validation row: kp, or kp / 2 for 1-bit (FP4 codes)
@@ -287,23 +288,43 @@ score_prepare_kernel(ScoreArgs a, ScorePrep w) {
     if (BITS <= 2) {
         // two FP4 codes per byte: 0x2 = +1.0, 0xA = -1.0, 0x0 = 0 (2-bit zeros, and past the end of the
         // vector).  1-bit with few validation vectors (vrow == 0): the main kernel stages the packed codes itself.
+        // 1-bit on wide tiles: the train side feeds FP4 dword jd of a word as the word's bits 4 n + 3 - jd
+        // left in place (no shift), i.e. as 2 s, s, s / 2 for jd = 1, 2, 3 with s = 1 for a negative code
+        // a = 1 - 2 s; the validation code b of such a position is stored as -b, -2 b, -4 b, so that every
+        // product is -2 s b = a b - b, and the sum of b over these positions is added back after the
+        // dot product (vbias).  jd = 0 keeps +-1 on both sides.
+        int bias = 0;
         for (int bi = threadIdx.x; bi < w.vrow; bi += 256) {
             unsigned byte = 0;
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                const int m = val_source_element<BITS>(2 * bi + e);      // source elements past k: code 0
+                const int p = 2 * bi + e;
+                const int m = val_source_element<BITS>(p);               // source elements past k: code 0
                 if (live && m < a.k) {
                     unsigned nz = 1u, neg;
                     if (BITS == 2) {
                         nz = (src[m >> 3] >> (m & 7)) & 1u;
                         neg = (src[a.k / 8 + (m >> 3)] >> (m & 7)) & 1u;
+                        byte |= ((nz << 1) | (neg << 3)) << (4 * e);
                     } else {
                         neg = (src[m >> 3] >> (m & 7)) & 1u;
+                        const int jd = (p >> 3) & 3;
+                        const unsigned mag = jd == 3 ? 0x6u : (jd == 2 ? 0x4u : 0x2u);     // 4.0, 2.0, 1.0
+                        const unsigned sgn = jd == 0 ? neg : neg ^ 1u;
+                        byte |= (mag | (sgn << 3)) << (4 * e);
+                        if (jd != 0) bias += neg ? -1 : 1;
                     }
-                    byte |= ((nz << 1) | (neg << 3)) << (4 * e);
                 }
             }
             dst[bi] = (int8_t)byte;
+        }
+        if (BITS == 1 && w.vrow > 0) {
+            __shared__ int sh_bias;
+            if (threadIdx.x == 0) sh_bias = 0;
+            __syncthreads();
+            if (bias) atomicAdd(&sh_bias, bias);
+            __syncthreads();
+            if (threadIdx.x == 0) w.vbias[ci * w.Mp + row] = sh_bias;
         }
     } else {
         for (int p = threadIdx.x; p < w.kp; p += 256) {
@@ -1161,8 +1182,10 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
             if constexpr (BITS == 1 && !Sh::VPACKED) {
                 // sign codes as FP4: one 64-element K step per matrix-core instruction.  A lane reads 16
                 // bytes of its row (chunk 2 q + half: four words of 32 signs) per four K steps; word j
-                // becomes four dwords of FP4 codes, dword jd = bits 3 - jd of every nibble:
-                // ((w << jd) & 0x88888888) | 0x22222222 -> 0x2 = +1.0, 0xA = -1.0.  The pre-expanded
+                // becomes four dwords of FP4 codes, dword jd = bits 3 - jd of every nibble, left where they
+                // are: (w & 0x88888888) | 0x22222222 = +-1.0, then w & 0x44444444, w & 0x22222222,
+                // w & 0x11111111 = 2 s, s, s / 2 (four operations per word; the pre-pass scaled the
+                // validation codes of those positions to match, see score_prepare_kernel).  The pre-expanded
                 // validation rows follow the same order and are zero past the end of the vectors.
                 // The validation fragments of K step ks + 1 and the train words of the next four steps are
                 // requested before the matrix instructions of step ks (scheduling barriers keep that
@@ -1190,8 +1213,10 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
 #pragma unroll
                     for (int b = 0; b < WR; ++b) {
                         const unsigned int wd = (unsigned int)wq[q][b][j];
-#pragma unroll
-                        for (int jd = 0; jd < 4; ++jd) af[b][jd] = (int)sign_bits_or(wd << jd, ones);
+                        af[b][0] = (int)sign_bits_or(wd, ones);        // +-1.0
+                        af[b][1] = (int)(wd & 0x44444444u);            // 2 s
+                        af[b][2] = (int)(wd & 0x22222222u);            // s
+                        af[b][3] = (int)(wd & 0x11111111u);            // s / 2
 #pragma unroll
                         for (int jd = 4; jd < 8; ++jd) af[b][jd] = 0;
 #pragma unroll
@@ -1347,10 +1372,12 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
         if (myrow > a.N - 1) myrow = a.N - 1;
         const float rt_lane = F16 ? 1.0f : a.tr[ci][myrow];
         float wv[WC];
+        int vbias[WC];
 #pragma unroll
         for (int c = 0; c < WC; ++c) {
             const int col = v0 + vcol + 32 * c + l32;               // < Mp (padded)
             wv[c] = w.vw[ci * w.Mp + col];
+            vbias[c] = (BITS == 1 && !Sh::VPACKED) ? w.vbias[ci * w.Mp + col] : 0;
         }
 #pragma unroll
         for (int b = 0; b < WR; ++b)
@@ -1363,7 +1390,8 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
                     if (F16) {
                         t = __fmul_rn((float)acc[b][c][v], wv[c]);
                     } else {
-                        const int D = BITS == 4 ? ((int)acc[b][c][v] >> 4) : (int)acc[b][c][v];   // 1-bit: an exact integer in fp32
+                        int D = BITS == 4 ? ((int)acc[b][c][v] >> 4) : (int)acc[b][c][v];   // 1-/2-bit: an exact integer in fp32
+                        if (BITS == 1 && !Sh::VPACKED) D += vbias[c];
                         t = __fmul_rn(__fmul_rn((float)D, rt), wv[c]);
                     }
                     facc[b][c][v] = __fadd_rn(facc[b][c][v], t);
@@ -1409,7 +1437,7 @@ static int compute_units() {
     return cus;
 }
 
-struct MfmaPlan { int32_t vt, Mp, kp; size_t off_vw, off_smax, total; };
+struct MfmaPlan { int32_t vt, Mp, kp; size_t off_vw, off_vbias, off_smax, total; };
 static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int bits, int C) {
     MfmaPlan p{};
     p.vt = M > 64 ? 128 : (M > 32 ? 64 : 32);
@@ -1422,6 +1450,8 @@ static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int bits, int C) {
     size_t o = (size_t)C * p.Mp * (size_t)p.kp;
     o = (o + 255) & ~(size_t)255;
     p.off_vw = o;   o += (size_t)C * p.Mp * 4;
+    o = (o + 255) & ~(size_t)255;
+    p.off_vbias = o; o += (size_t)C * p.Mp * 4;
     o = (o + 255) & ~(size_t)255;
     p.off_smax = o; o += (size_t)(N > 0 ? N : 1) * 4;
     p.total = o;
@@ -1489,7 +1519,7 @@ static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st) {
     const MfmaPlan p = mfma_plan(a.N, a.M, a.k, BITS, a.C);
     ScorePrep w{};
     unsigned char *base = (unsigned char *)ws;
-    w.vexp = (int8_t *)base; w.vw = (float *)(base + p.off_vw);
+    w.vexp = (int8_t *)base; w.vw = (float *)(base + p.off_vw); w.vbias = (int32_t *)(base + p.off_vbias);
     w.smax = (unsigned int *)(base + p.off_smax); w.Mp = p.Mp; w.kp = p.kp;
     w.vrow = BITS == 1 ? (p.vt > 64 ? p.kp / 2 : 0) : (BITS == 2 ? p.kp / 2 : p.kp);
     hipLaunchKernelGGL((score_prepare_kernel<BITS, F16>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
@@ -1649,7 +1679,7 @@ static qless_status launch_stream_i8(const ScoreArgs &a, void *ws, hipStream_t s
     if (BITS == 4) {
         const MfmaPlan p = mfma_plan(a.N, a.M, a.k, BITS, a.C);
         unsigned char *base = (unsigned char *)ws;
-        w.vexp = (int8_t *)base; w.vw = (float *)(base + p.off_vw);
+        w.vexp = (int8_t *)base; w.vw = (float *)(base + p.off_vw); w.vbias = (int32_t *)(base + p.off_vbias);
         w.smax = (unsigned int *)(base + p.off_smax); w.Mp = p.Mp; w.kp = p.kp; w.vrow = p.kp;
         hipLaunchKernelGGL((score_prepare_kernel<BITS, false>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
     }
