@@ -148,7 +148,11 @@ def main():
                 traffic = int(line.split("=")[1])
     roofline = {"kernel": "project_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "traffic": traffic, "flops_per_launch": flops, "avg_launch_ms": round(proj_ms, 4)}
+                "traffic": traffic,
+                "traffic_source": ("profiles/project_kernel_c3_hbm_traffic.txt: rocprofv3 --pmc FETCH_SIZE, then "
+                                   "WRITE_SIZE, of this kernel at this shape, each scaled by the same counter of a "
+                                   "plain copy (a stored counter figure, not measured in this run)") if traffic else None,
+                "flops_per_launch": flops, "avg_launch_ms": round(proj_ms, 4)}
 
     # ------------------------------------------------------------- scoring-only leg (1-bit, 270K x 1024)
     extra = {}

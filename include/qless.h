@@ -4,7 +4,7 @@
  * The calls follow the pipeline of the QLESS paper (arXiv 2502.01703):
  *   qless_project   Eq.(1)        random projection of per-example gradients, d -> k
  *   qless_quantize  Eq.(4),(5)    absmax b-bit quantisation into the packed gradient datastore
-   qless_project_quantize        both of the above in one call
+ *   qless_project_quantize        both of the above in one call
  *   qless_score     Eq.(6),(7)    normalised quantised cosine, learning-rate weighted over
  *                                 checkpoints, reduced by max over validation examples
  *   qless_topk      Sec. 4.1      selection of the highest-scoring training examples
@@ -13,13 +13,19 @@
  * Conventions common to every call
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
  *     host memory read before the call returns.  The library allocates and frees nothing on
- *     the device and keeps no state between calls.
+ *     the device.  Its only state is set up once per device (see qless_init): the dynamic-LDS
+ *     limits of its kernels and the address of one fixed device array; no result depends on it.
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream);
  *     no call synchronises.  Outputs are valid once the caller has synchronised the stream.
  *   - Every call returns a qless_status.  Arguments are validated on the host before anything
  *     is launched; on any status other than QLESS_OK no output has been touched.
  *   - Workspace sizes come from the matching *_workspace() query with the same shape
- *     arguments; a workspace may be reused by later calls on the same stream.
+ *     arguments; a workspace may be reused by later calls on the same stream.  A workspace that is
+ *     missing, too small or not aligned as its call states gives QLESS_ERR_WORKSPACE.
+ *   - HIP graph capture: every entry point only enqueues kernels (no allocation, no memset, no copy,
+ *     no synchronisation) and may be captured, provided qless_init() has run on that device before
+ *     the capture begins (without it the first launching call on a device does the set-up, which
+ *     is host-side work that must not fall inside a capture).
  *   - Inputs must be finite (no NaN/Inf); this is not checked.
  */
 #ifndef QLESS_H
@@ -36,7 +42,7 @@ typedef enum {
     QLESS_OK = 0,
     QLESS_ERR_INVALID_ARG = 1,   /* null pointer, negative size, leading dimension too small */
     QLESS_ERR_UNSUPPORTED = 2,   /* bits not in {1,2,4,8}, k not a multiple of 64, ... */
-    QLESS_ERR_WORKSPACE = 3,     /* workspace missing or smaller than the query's answer */
+    QLESS_ERR_WORKSPACE = 3,     /* workspace missing, smaller than the query's answer, or misaligned */
     QLESS_ERR_DEVICE = 4         /* the HIP runtime reported an error at launch */
 } qless_status;
 
@@ -47,6 +53,14 @@ typedef enum { QLESS_RADEMACHER = 0, QLESS_GAUSSIAN = 1 } qless_proj;
 
 const char *qless_status_string(qless_status s);
 
+/* One-time set-up for the current device (hipSetDevice): allows the library's kernels their dynamic
+ * LDS (up to 160 KB per workgroup) and looks up the device address of the array behind
+ * qless_topk_noalloc.  Host-side only: nothing is launched, allocated or synchronised.  Optional:
+ * every entry point that launches such a kernel does the same on its first call on a device; call
+ * it explicitly before capturing entry points into a HIP graph.  Thread-safe; later calls return at
+ * once.  QLESS_ERR_DEVICE if there is no usable device. */
+qless_status qless_init(void);
+
 /* ---------------------------------------------------------------------------------------------
  * Projection, Eq.(1) (Sec. 2.2; matrix families of Sec. 2.4):  P[i][m] = sum_j R[m][d_offset+j] G[i][j]
  *
@@ -56,11 +70,13 @@ const char *qless_status_string(qless_status s);
  *
  *   G          device, n x d_len, row-major with leading dimension ldG (elements), dtype dt
  *   d_offset   column of R that G's column 0 multiplies; lets a caller feed a long gradient in
- *              slices (per layer).  Must be a multiple of 32; d_offset + d_len <= 2^36.
+ *              slices (per layer).  Must be a multiple of 32; d_offset + d_len <= 2^36 for
+ *              QLESS_RADEMACHER and <= 2^34 for QLESS_GAUSSIAN (its generator numbers words of
+ *              four columns with 32 bits; beyond that columns would repeat): QLESS_ERR_UNSUPPORTED.
  *   k          projected dimension, a positive multiple of 64
  *   accumulate 0: P = R G      non-zero: P = P + R G   (slices are summed in call order)
  *   P          device, n x k fp32, leading dimension ldP >= k
- *   ws         device workspace of at least qless_project_workspace(n, d_len, k) bytes
+ *   ws         device workspace, 16-byte aligned, of at least qless_project_workspace(n, d_len, k) bytes
  * Arithmetic: gradient values enter as bfloat16 (fp32 input is rounded to nearest-even),
  * products are exact, sums are fp32 in a fixed order (results are run-to-run identical).
  * n == 0 or d_len == 0 is valid (P is zero-filled unless accumulating).
@@ -86,7 +102,7 @@ qless_status qless_gaussian_table(float *host_out256);
  * (bits >= 2) or all +1 (bits == 1) and S = 0.
  *
  *   P      device, n x k fp32, leading dimension ldP >= k;  k a positive multiple of 64
- *   codes  device, n rows of k*bits/8 bytes, packed:
+ *   codes  device, 4-byte aligned (QLESS_ERR_INVALID_ARG otherwise), n rows of k*bits/8 bytes, packed:
  *            8: int8 at byte m        4: two's-complement nibbles, element 2t low, 2t+1 high
  *            2: k/8 bytes "non-zero" plane then k/8 bytes "negative" plane, element m at bit
  *               m%8 of byte m/8       1: the "negative" plane only
@@ -181,8 +197,8 @@ qless_status qless_score16(const void *const *train16, const void *const *val16,
  *   score  device, N fp32 (N < 2^32)     idx  device, k_sel int64
  *   val    device, k_sel fp32 receiving score[idx[t]], or NULL
  *   ws     device workspace, 8-byte aligned, of at least qless_topk_workspace(N, k_sel) bytes
- * 0 <= k_sel <= N.  Errors: QLESS_ERR_INVALID_ARG (sizes, null pointers, misaligned ws), QLESS_ERR_WORKSPACE
- * (ws missing or too small), QLESS_ERR_UNSUPPORTED (N >= 2^32); nothing is launched then.
+ * 0 <= k_sel <= N.  Errors: QLESS_ERR_INVALID_ARG (sizes, null pointers), QLESS_ERR_WORKSPACE
+ * (ws missing, too small or misaligned), QLESS_ERR_UNSUPPORTED (N >= 2^32); nothing is launched then.
  * ------------------------------------------------------------------------------------------- */
 size_t qless_topk_workspace(int64_t N, int64_t k_sel);
 qless_status qless_topk(const float *score, int64_t N, int64_t k_sel, int64_t *idx, float *val,
@@ -206,9 +222,10 @@ qless_status qless_topk_noalloc(const float *score, int64_t N, int64_t k_sel, in
                                 void *stream);
 
 /* ---------------------------------------------------------------------------------------------
- * Aggregation of pairwise influences over groups of validation examples (Sec. 4.1 selects by
- * "cumulative influence scores" and evaluates on benchmarks with sub-tasks, without a formula for
- * combining validation examples; qless_score reduces by the maximum over all of them).  From the
+ * Aggregation of pairwise influences over groups of validation examples (Sec. 4.1 ranks the training
+ * examples by their influence summed over checkpoints and evaluates on benchmarks with sub-tasks,
+ * without a formula for combining validation examples; qless_score reduces by the maximum over all
+ * of them).  From the
  * full matrix of qless_score / qless_score16:
  *   QLESS_AGG_MAX   out[z][t] = max of full[z][j] over group t (the first of equal values)
  *   QLESS_AGG_MEAN  out[z][t] = fl32(s / n), s = the fp32 sum of the group's entries in column order

@@ -132,6 +132,9 @@ int oracle_project_rows(const void *G, int dtype, int64_t n, int64_t d_len, int6
                         const int32_t *rows, int32_t nrows, double *out) {
     if (!G || !out || n < 0 || d_len < 0 || nrows < 0 || (dtype != 0 && dtype != 1) ||
         (kind != 0 && kind != 1) || d_offset < 0 || ldG < d_len) return ORACLE_BAD_ARG;
+    /* the word counter has 32 bits: 32 columns per Rademacher word, 4 per Gaussian word; past these
+     * limits columns would repeat, so such a column range is outside the definition of R */
+    if (d_offset + d_len > (kind == 0 ? ((int64_t)1 << 37) : ((int64_t)1 << 34))) return ORACLE_BAD_ARG;
     if (kind == 1 && !g_table_ready) build_gauss_table();
     int64_t r;
     #pragma omp parallel for schedule(dynamic, 1)
@@ -414,8 +417,8 @@ int oracle_topk(const float *score, int64_t N, int64_t k_sel, int64_t *idx, floa
     return ORACLE_OK;
 }
 
-/* Aggregation of the pairwise influences over groups of validation examples (Sec. 4.1 selects by
- * "cumulative influence scores" and its benchmarks have sub-tasks, but the paper gives no formula:
+/* Aggregation of the pairwise influences over groups of validation examples (Sec. 4.1 ranks by
+ * the influence summed over checkpoints and its benchmarks have sub-tasks, but the paper gives no formula:
  * parity unpinned against the paper; the benchmark spec fixes the maximum over all validation examples).
  * Group t is the columns [group_end[t-1], group_end[t]) of full (group_end[-1] = 0).
  *   mode 0: out[z][t] = the maximum of the group's entries (the first of equal ones, compared with >)

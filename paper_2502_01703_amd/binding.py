@@ -24,6 +24,7 @@ _i64, _i32, _u64, _u32, _vp, _sz = (_c.c_int64, _c.c_int32, _c.c_uint64, _c.c_ui
 
 EXPORTS = {
     "qless_status_string": (_c.c_char_p, [_c.c_int]),
+    "qless_init": (_c.c_int, []),
     "qless_project_workspace": (_sz, [_i64, _i64, _i32]),
     "qless_project": (_c.c_int, [_vp, _c.c_int, _i64, _i64, _i64, _i64, _i32, _c.c_int, _u64, _c.c_int,
                                  _vp, _i64, _vp, _sz, _vp]),
@@ -67,6 +68,11 @@ def lib():
             fn.argtypes = args
         _lib = L
     return _lib
+
+
+def init():
+    """qless_init: one-time host-side set-up for the current device (needed before a graph capture)."""
+    _check(lib().qless_init(), "qless_init")
 
 
 def _stream():

@@ -69,6 +69,22 @@ template <int N> __device__ inline void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
+// Kernels that ask for more dynamic LDS than the 64 KB a launch may use by default.  Each such
+// kernel is entered in a list while the library is loaded (no HIP call is made then);
+// device_ready() raises the limit of every listed kernel on the current device, once per device,
+// and is called by qless_init() and at the top of every entry point that launches one of them.
+bool register_lds_kernel(const void *fn, int bytes);
+qless_status device_ready();
+template <auto Fn, int BYTES> struct LdsKernel {
+    static inline const bool listed = register_lds_kernel((const void *)Fn, BYTES);
+};
+// names a kernel's list entry so that the entry exists in the loaded library
+#define QLESS_LDS_KERNEL(fn, bytes) ((void)qless::LdsKernel<&fn, (bytes)>::listed)
+
+// topk.hip: device address of the current GPU's scratch array of qless_topk_noalloc (looked up once
+// per device)
+qless_status topk_scratch_address(void **out);
+
 inline qless_status launch_status() {
     return hipGetLastError() == hipSuccess ? QLESS_OK : QLESS_ERR_DEVICE;
 }

@@ -17,7 +17,6 @@
 // of +-1.0 for K-step s; V_CVT_SCALEF32_PK_BF16_FP4 expands them to packed bf16 +-1.0, two
 // elements per instruction.
 #include "common.h"
-#include <atomic>
 
 namespace qless {
 
@@ -133,6 +132,7 @@ union Frag { bf16x8 v; bf16x2 p[4]; uint4 u; uint32_t w[4]; uint16_t h[8]; };
 // case stages through registers into two padded buffers.
 constexpr int kRing = 4;
 constexpr int kGaussCopies = 32;                // copies of the Gaussian table in LDS
+constexpr int kProjectMaxLds = kRing * 128 * kStageD * 2 + 256 * kGaussCopies * 2;   // largest request of any shape (128-row tiles)
 
 template <bool IN_F32, bool ALIGNED, bool GAUSS, bool DIRECT, int NB>
 __global__ void __launch_bounds__(kWaves * 64, 2)
@@ -394,10 +394,12 @@ static qless_status project_partials(const void *G, qless_dtype dt, int64_t n, i
     if (kind != QLESS_RADEMACHER && kind != QLESS_GAUSSIAN) return QLESS_ERR_UNSUPPORTED;
     if (k % 64 != 0 || d_offset % 32 != 0) return QLESS_ERR_UNSUPPORTED;
     if (d_offset + d_len > ((int64_t)1 << 36)) return QLESS_ERR_UNSUPPORTED;
+    // the Gaussian stream numbers its words with 32 bits, four columns to a word
+    if (kind == QLESS_GAUSSIAN && d_offset + d_len > ((int64_t)1 << 34)) return QLESS_ERR_UNSUPPORTED;
     if (n > ((int64_t)1 << 31)) return QLESS_ERR_UNSUPPORTED;
     if (n == 0) return QLESS_OK;
     ProjectPlan plan = make_plan(n, d_len, k, kind == QLESS_GAUSSIAN);
-    if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return QLESS_ERR_WORKSPACE;
+    if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes || (uintptr_t)ws % 16 != 0)) return QLESS_ERR_WORKSPACE;
     if (plan.grid > 0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
     if (plan.nsplit == 0) return QLESS_OK;
 
@@ -416,15 +418,11 @@ static qless_status project_partials(const void *G, qless_dtype dt, int64_t n, i
     const size_t lds = (direct ? (size_t)kRing * (32 * nb) * kStageD * 2 : (size_t)2 * (32 * nb) * kLdsStride) +
                        (gauss ? (size_t)256 * kGaussCopies * 2 : 0);
     dim3 grid((unsigned)plan.grid), block(kWaves * 64);
-    // more than 64 KB of dynamic LDS has to be allowed per kernel (host-side attribute, no device work)
+    if (lds > (size_t)kProjectMaxLds) return QLESS_ERR_DEVICE;
+    const qless_status ready = device_ready();     // more than 64 KB of dynamic LDS has to be allowed per kernel
+    if (ready != QLESS_OK) return ready;
 #define QLESS_LAUNCH_NB(F32, AL, GA, DI, NBLK) do { \
-        static std::atomic<bool> once{false}; \
-        if (!once) { \
-            if (hipFuncSetAttribute((const void *)project_kernel<F32, AL, GA, DI, NBLK>, \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
-                return QLESS_ERR_DEVICE; \
-            once = true; \
-        } \
+        QLESS_LDS_KERNEL((project_kernel<F32, AL, GA, DI, NBLK>), kProjectMaxLds); \
         hipLaunchKernelGGL((project_kernel<F32, AL, GA, DI, NBLK>), grid, block, lds, st, a, gt); } while (0)
 #define QLESS_LAUNCH(F32, AL, GA, DI) do { \
         if (nb == 4) QLESS_LAUNCH_NB(F32, AL, GA, DI, 4); else QLESS_LAUNCH_NB(F32, AL, GA, DI, 2); } while (0)
@@ -470,6 +468,7 @@ extern "C" qless_status qless_project_quantize(const void *G, qless_dtype dt, in
                                                void *stream) {
     if (d_len <= 0 || (P && ldP < k)) return QLESS_ERR_INVALID_ARG;
     if (n > 0 && (!codes || !S || !rnorm)) return QLESS_ERR_INVALID_ARG;
+    if ((uintptr_t)codes % 4) return QLESS_ERR_INVALID_ARG;
     if (!valid_bits(bits)) return QLESS_ERR_UNSUPPORTED;
     if (ws && (uintptr_t)ws % 16 != 0) return QLESS_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;

@@ -454,6 +454,7 @@ extern "C" qless_status qless_quantize(const float *P, int64_t ldP, int64_t n, i
                                        void *codes, float *S, float *rnorm, void *stream) {
     if (n < 0 || k <= 0 || ldP < k) return QLESS_ERR_INVALID_ARG;
     if (n > 0 && (!P || !codes || !S || !rnorm)) return QLESS_ERR_INVALID_ARG;
+    if ((uintptr_t)codes % 4) return QLESS_ERR_INVALID_ARG;            // the packed codes are stored as 32-bit words
     if (!valid_bits(bits) || k % 64 != 0) return QLESS_ERR_UNSUPPORTED;
     if (n == 0) return QLESS_OK;
     return quantize_rows(P, ldP, 1, 0, nullptr, 0, n, k, bits, codes, S, rnorm, (hipStream_t)stream);
@@ -463,6 +464,7 @@ extern "C" qless_status qless_quantize_absmean(const float *P, int64_t ldP, int6
                                                void *codes, float *S, float *rnorm, void *stream) {
     if (n < 0 || k <= 0 || ldP < k) return QLESS_ERR_INVALID_ARG;
     if (n > 0 && (!P || !codes || !S || !rnorm)) return QLESS_ERR_INVALID_ARG;
+    if ((uintptr_t)codes % 4) return QLESS_ERR_INVALID_ARG;            // the packed codes are stored as 32-bit words
     if (!valid_bits(bits) || k % 64 != 0) return QLESS_ERR_UNSUPPORTED;
     if (n == 0) return QLESS_OK;
     hipStream_t st = (hipStream_t)stream;

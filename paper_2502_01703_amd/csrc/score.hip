@@ -1472,13 +1472,10 @@ static qless_status launch_mfma_shape(const ScoreArgs &a, const ScorePrep &w, in
         const size_t share = ((size_t)kLdsPerCU / per_cu - kStaticLds) & ~(size_t)511;
         if (share > lds) lds = share;
     }
-    static std::atomic<size_t> allowed{0};            // two host threads may race here: both then set the attribute
-    if (lds > allowed) {
-        if (hipFuncSetAttribute((const void *)score_mfma_kernel<BITS, WR, WC, WX, NW, F16, VH>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return QLESS_ERR_DEVICE;
-        allowed = lds;
-    }
+    // the kernel's static LDS (row maxima: 4 bytes per train row of the tile) counts against the same 160 KB
+    constexpr int kMaxDynamic = (int)kLdsPerCU - 4 * Sh::MT;
+    QLESS_LDS_KERNEL((score_mfma_kernel<BITS, WR, WC, WX, NW, F16, VH>), kMaxDynamic);
+    if (lds > (size_t)kMaxDynamic) return QLESS_ERR_DEVICE;
     const int64_t ttiles = (a.N + Sh::MT - 1) / Sh::MT;
     const int vtiles = w.Mp / Sh::VT;
     const int64_t grid = 8 * (int64_t)vtiles * ((ttiles + 7) / 8);
@@ -1576,15 +1573,10 @@ static size_t stream_mfma_partial_bytes(const StreamMfmaPlan &p, int64_t N, int 
 }
 static qless_status launch_stream_mfma(const ScoreArgs &a, int bits, const StreamMfmaPlan &sp, float *partial, hipStream_t st) {
     constexpr int NW = kStreamWaves;
-    static std::atomic<bool> allowed{false};                         // LDS above 64 KB has to be allowed per kernel
-    if (!allowed) {
-        const void *fns[4] = {(const void *)score_stream_mfma_kernel<1, 8, NW, 2>, (const void *)score_stream_mfma_kernel<1, 16, NW, 2>,
-                              (const void *)score_stream_mfma_kernel<2, 8, NW, 1>, (const void *)score_stream_mfma_kernel<2, 16, NW, 1>};
-        for (const void *f : fns)
-            if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 158 * 1024) != hipSuccess)
-                return QLESS_ERR_DEVICE;
-        allowed = true;
-    }
+    QLESS_LDS_KERNEL((score_stream_mfma_kernel<1, 8, NW, 2>), 158 * 1024);
+    QLESS_LDS_KERNEL((score_stream_mfma_kernel<1, 16, NW, 2>), 158 * 1024);
+    QLESS_LDS_KERNEL((score_stream_mfma_kernel<2, 8, NW, 1>), 158 * 1024);
+    QLESS_LDS_KERNEL((score_stream_mfma_kernel<2, 16, NW, 1>), 158 * 1024);
     // at most one workgroup per compute unit; the 8-row blocks are dealt out evenly over all wavefronts
     const int64_t total_rb = (a.N + 7) / 8;
     int64_t groups = compute_units();
@@ -1632,13 +1624,7 @@ static int stream32_rows(int32_t mc) { return mc <= 8 ? 8 : (mc <= 16 ? 16 : (mc
 template <int BITS, int VB, int VR>
 static qless_status launch_stream32_shape(const ScoreArgs &a, const ScorePrep &w, int32_t m0, int32_t mc, hipStream_t st) {
     constexpr int NW = kStream32Waves;
-    static std::atomic<bool> allowed{false};                         // LDS above 64 KB has to be allowed per kernel
-    if (!allowed) {
-        if (hipFuncSetAttribute((const void *)score_stream_mfma32_kernel<BITS, VB, VR>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU) != hipSuccess)
-            return QLESS_ERR_DEVICE;
-        allowed = true;
-    }
+    QLESS_LDS_KERNEL((score_stream_mfma32_kernel<BITS, VB, VR>), (int)kLdsPerCU);
     // at most one workgroup per compute unit; the 8-row blocks are dealt out evenly over all wavefronts
     const int64_t total_rb = (a.N + 7) / 8;
     int64_t groups = compute_units();
@@ -1734,6 +1720,8 @@ extern "C" qless_status qless_score(const void *const *train_codes, const float 
     a.C = C; a.N = N; a.M = M; a.k = k; a.score = score; a.full = full;
     if (N == 0) return QLESS_OK;
     hipStream_t st = (hipStream_t)stream;
+    const qless_status ready = device_ready();            // LDS limits of the kernels, once per device
+    if (ready != QLESS_OK) return ready;
     if (bits <= 2 && M <= kStreamMfmaVal && k % 128 == 0) {
         const StreamMfmaPlan sp = stream_mfma_plan(M, k, bits, C);
         if (sp.nb >= 2) {
@@ -1748,7 +1736,7 @@ extern "C" qless_status qless_score(const void *const *train_codes, const float 
     if (use_mfma_path(bits, M, k)) {
         const size_t need = mfma_plan(N, M, k, bits, C).total;
         if (!ws || ws_bytes < need) return QLESS_ERR_WORKSPACE;
-        if ((uintptr_t)ws % 16) return QLESS_ERR_INVALID_ARG;
+        if ((uintptr_t)ws % 16) return QLESS_ERR_WORKSPACE;
         if (N > (int64_t)0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
         if (use_stream_i8(bits, M, k, C)) return bits == 8 ? launch_stream_i8<8>(a, ws, st) : launch_stream_i8<4>(a, ws, st);
         if (bits == 8) return launch_mfma<8>(a, ws, st);
@@ -1795,6 +1783,8 @@ extern "C" qless_status qless_score16(const void *const *train16, const void *co
     if (N == 0) return QLESS_OK;
     const size_t need = mfma_plan(N, M, a.k, 8, C).total;
     if (!ws || ws_bytes < need) return QLESS_ERR_WORKSPACE;
-    if ((uintptr_t)ws % 16) return QLESS_ERR_INVALID_ARG;
+    if ((uintptr_t)ws % 16) return QLESS_ERR_WORKSPACE;
+    const qless_status ready = device_ready();
+    if (ready != QLESS_OK) return ready;
     return launch_mfma<8, true>(a, ws, (hipStream_t)stream);
 }

@@ -563,7 +563,7 @@ extern "C" qless_status qless_topk(const float *score, int64_t N, int64_t k_sel,
     const qless_status rc = topk_check(score, N, k_sel, idx);
     if (rc != QLESS_OK || k_sel == 0) return rc;
     if (!ws || ws_bytes < topk_plan(N, k_sel).total) return QLESS_ERR_WORKSPACE;
-    if ((uintptr_t)ws % 8) return QLESS_ERR_INVALID_ARG;
+    if ((uintptr_t)ws % 8) return QLESS_ERR_WORKSPACE;
     return topk_run(score, N, k_sel, idx, val, ws, (hipStream_t)stream);
 }
 
@@ -583,7 +583,7 @@ static std::mutex scratch_mutex;
 static std::atomic<void *> scratch_ptr[kMaxDevices];
 
 // device address of this GPU's copy of `scratch` (resolved once per device, with that device current)
-static qless_status scratch_address(void **out) {
+qless_status qless::topk_scratch_address(void **out) {
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return QLESS_ERR_DEVICE;
     void *p = scratch_ptr[dev].load(std::memory_order_acquire);
@@ -607,7 +607,7 @@ extern "C" qless_status qless_topk_noalloc(const float *score, int64_t N, int64_
     if (N > kNoAllocMaxN || k_sel > kNoAllocMaxSel) return QLESS_ERR_UNSUPPORTED;
     if (k_sel == 0) return QLESS_OK;
     void *ws = nullptr;
-    const qless_status rs = scratch_address(&ws);
+    const qless_status rs = topk_scratch_address(&ws);
     if (rs != QLESS_OK) return rs;
     // every word of the workspace that a launch reads is written earlier in the same call (init /
     // select kernels clear histograms, states and the cursor; the compaction clears padding and ranks;

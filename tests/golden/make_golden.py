@@ -20,5 +20,18 @@ def generator_words():
     open(os.path.join(HERE, "generator_words.txt"), "w").write("\n".join(lines) + "\n")
 
 
+def gaussian_table():
+    """The 256 table values of the Gaussian family as bfloat16 bit patterns (hex), entry i on line i."""
+    import numpy as np
+    T = oracle.gauss_table().astype(np.float32)
+    bits = T.view(np.uint32)
+    assert np.all((bits & 0xFFFF) == 0), "table entries are bfloat16 values"
+    lines = ["# bfloat16 bit patterns of T[i] = bf16_rne(Phi^-1((i + 1/2) / 256)), i = 0..255, written by the oracle.",
+             "# Both implementations (CPU oracle, HIP library) are compared against these."]
+    lines += ["%04x" % (int(b) >> 16) for b in bits]
+    open(os.path.join(HERE, "gaussian_table_bf16.txt"), "w").write("\n".join(lines) + "\n")
+
+
 if __name__ == "__main__":
     generator_words()
+    gaussian_table()

@@ -431,7 +431,7 @@ def test_quantize_score_topk_replay_in_a_hip_graph(bits, M):
         Q.score(tc, tr, vc, vr, eta, k, bits, score_out=sc, ws=ws_s)
         return Q.topk(sc, ksel, ws=ws_t)
 
-    run()                                           # eager first: per-kernel attributes are set outside the capture
+    Q.init()                                        # the library's one-time device set-up must not fall inside a capture
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):

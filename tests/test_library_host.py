@@ -125,6 +125,47 @@ def test_quantize_score_topk_argument_validation():
     assert ag(one, 0, 100, ends(*range(1, 66)), 65, 0, one, None) == UNSUPPORTED   # more than QLESS_MAX_GROUPS
 
 
-def test_gaussian_table_matches_the_oracle_table():
+def _golden_gaussian_table():
+    path = os.path.join(ROOT, "tests", "golden", "gaussian_table_bf16.txt")
+    bits = np.array([int(l, 16) for l in open(path) if not l.startswith("#")], dtype=np.uint32)
+    assert bits.size == 256
+    return (bits << 16).view(np.float32).astype(np.float64)
+
+
+def test_gaussian_table_matches_the_stored_table_and_the_oracle():
+    """The library's table is a constant array; the oracle computes its own with the host's math library; both
+    must equal the stored bfloat16 bit patterns (a different libm must not move an entry)."""
     import oracle
-    np.testing.assert_array_equal(binding.gaussian_table().numpy().astype(np.float64), oracle.gauss_table())
+    gold = _golden_gaussian_table()
+    np.testing.assert_array_equal(binding.gaussian_table().numpy().astype(np.float64), gold)
+    np.testing.assert_array_equal(oracle.gauss_table(), gold)
+    np.testing.assert_array_equal(gold, -gold[::-1])
+
+
+def test_gaussian_columns_end_at_2_to_34_on_both_sides():
+    """The Gaussian stream numbers words of four columns with 32 bits: a column range past 2^34 is refused by
+    the library (before any launch) and by the oracle; the Rademacher family goes on to 2^36."""
+    import oracle
+    L = binding.lib()
+    one = ctypes.c_void_p(16)
+    f = L.qless_project
+    off = (1 << 34) - 64
+    need = L.qless_project_workspace(4, 128, 64)
+    assert f(one, 1, 4, 128, 128, off, 64, 1, 0, 0, one, 64, one, need, None) == UNSUPPORTED       # Gaussian, ends past 2^34
+    assert f(one, 1, 0, 128, 128, off, 64, 0, 0, 0, one, 64, one, need, None) == OK                # Rademacher (n = 0: no launch)
+    assert f(one, 1, 0, 64, 64, off, 64, 1, 0, 0, one, 64, one, need, None) == OK                  # Gaussian, ends at 2^34
+    G = np.zeros((1, 128), dtype=np.float32)
+    with pytest.raises(Exception):
+        oracle.project_rows(G, [0], kind=oracle.GAUSSIAN, d_offset=off)
+    assert oracle.project_rows(G[:, :64], [0], kind=oracle.GAUSSIAN, d_offset=off).shape == (1, 1)
+    assert oracle.project_rows(G, [0], kind=oracle.RADEMACHER, d_offset=off).shape == (1, 1)
+
+
+def test_misaligned_workspaces_and_codes_are_refused():
+    L = binding.lib()
+    one, odd = ctypes.c_void_p(16), ctypes.c_void_p(18)
+    assert L.qless_topk(one, 10, 5, one, None, odd, 1 << 30, None) == WORKSPACE
+    need = L.qless_project_workspace(4, 64, 64)
+    assert L.qless_project(one, 1, 4, 64, 64, 0, 64, 0, 0, 0, one, 64, odd, need + 64, None) == WORKSPACE
+    assert L.qless_quantize(one, 64, 4, 64, 8, odd, one, one, None) == INVALID
+    assert L.qless_quantize_absmean(one, 64, 4, 64, 8, odd, one, one, None) == INVALID
