@@ -72,6 +72,36 @@ def test_config5_gaussian_projection_at_13b_lora_shape():
     np.testing.assert_array_equal(rn.cpu().numpy(), orn)
 
 
+def test_config3_projection_every_row_and_every_column_block():
+    """d = 2^27 bf16, batch of 64, k = 8192: every batch row against one coordinate of each 1024-wide
+    column tile, and two batch rows against one coordinate of every 32-column block of every tile."""
+    n, d, k = 64, 1 << 27, 8192
+    _say("config 3: project [64, 2^27] -> 8192: all 64 rows x 8 coordinates, 2 rows x 256 coordinates")
+    G, _ = synth.student_t_gradients(n, d, seed=3001, device=DEV, dtype=torch.bfloat16)
+    P = Q.project(G, k, seed=5)
+    per_tile = [1024 * t + (131 * t + 17) % 1024 for t in range(8)]
+    _check_sampled_projection(G, P, list(range(n)), per_tile, Q.RADEMACHER, 5, 1e-3)
+    per_block = [32 * b + (7 * b + 3) % 32 for b in range(k // 32)]
+    _check_sampled_projection(G, P, [21, 42], per_block, Q.RADEMACHER, 5, 1e-3)
+
+
+def test_config5_gaussian_projection_with_128_row_tiles():
+    """d = 2^28 bf16, k = 16384, Gaussian, a batch of 128 (the launch shape a full batch takes: 128-row
+    tiles): batch rows from each 32-row block against one coordinate of every 512-wide column tile."""
+    n, d, k = 128, 1 << 28, 16384
+    _say("config 5: project [128, 2^28] bf16 -> 16384 Gaussian (128-row tiles), 6 rows x 32 coordinates")
+    G, _ = synth.student_t_gradients(n, d, seed=5001, device=DEV, dtype=torch.bfloat16)
+    P = Q.project(G, k, kind=Q.GAUSSIAN, seed=78)
+    rows = [512 * t + (37 * t + 5) % 512 for t in range(k // 512)]
+    # the bar is 4e-2 of the row's rms per element; fp32 sums over 2^28 heavy-tailed terms come to about 1e-3
+    _check_sampled_projection(G, P, [0, 31, 32, 77, 96, 127], rows, Q.GAUSSIAN, 78, 4e-3)
+    del G
+    codes, S, rn = Q.quantize(P, 2)
+    oc, oS, orn = oracle.quantize(P.cpu().numpy(), 2)
+    np.testing.assert_array_equal(codes.cpu().numpy(), oc)
+    np.testing.assert_array_equal(rn.cpu().numpy(), orn)
+
+
 def _big_datastore(N, M, k, C, bits, seed):
     """codes / rnorm per checkpoint for N train and M val vectors with planted pairs."""
     gen = torch.Generator(device=DEV)
@@ -122,6 +152,39 @@ def test_config4_large_datastore_scoring(bits):
     np.testing.assert_array_equal(val.cpu().numpy().view(np.uint32), ov.view(np.uint32))
     # every planted train row is selected (expected cosine ~0.33 at 1 bit vs null maximum ~0.07)
     assert set(planted.cpu().tolist()) <= set(oi.tolist())
+
+
+def _score_and_topk_at_shape(N, M, k, C, bits, k_sel, seed, n_sample, expect_planted):
+    tcs, trs, vcs, vrs, planted = _big_datastore(N, M, k, C, bits, seed)
+    score = Q.score(tcs, trs, vcs, vrs, ETA, k, bits)
+    assert torch.equal(score, Q.score(tcs, trs, vcs, vrs, ETA, k, bits))
+    rng = np.random.default_rng(seed)
+    sample = np.unique(np.concatenate([rng.integers(0, N, n_sample), planted[:8].cpu().numpy(),
+                                       [0, 127, 128, 255, 256, 511, 512, N - 257, N - 256, N - 1]]))
+    idx_t = torch.from_numpy(sample).to(DEV)
+    ref = oracle.score([t[idx_t].cpu().numpy() for t in tcs], [t[idx_t].cpu().numpy() for t in trs],
+                       [v.cpu().numpy() for v in vcs], [v.cpu().numpy() for v in vrs], ETA, k, bits)
+    np.testing.assert_array_equal(score[idx_t].cpu().numpy().view(np.uint32), ref.view(np.uint32))
+    idx, val = Q.topk(score, k_sel)
+    oi, ov = oracle.topk(score.cpu().numpy(), k_sel)
+    np.testing.assert_array_equal(idx.cpu().numpy(), oi)
+    np.testing.assert_array_equal(val.cpu().numpy().view(np.uint32), ov.view(np.uint32))
+    if expect_planted:
+        assert set(planted.cpu().tolist()) <= set(oi.tolist())
+
+
+@pytest.mark.parametrize("bits", [1, 4])
+def test_config3_scoring_and_topk_at_7b_lora_shape(bits):
+    """N = 65536, M = 512, k = 8192, C = 4, 1-bit and 4-bit datastores, top 5 % = 3276: the scoring leg of
+    the benchmark step at its own shape; sampled rows bit-exact, top-k exact, planted rows selected."""
+    _say("config 3: score %d-bit N=65536 M=512 k=8192 C=4 + top-3276" % bits)
+    _score_and_topk_at_shape(65536, 512, 8192, 4, bits, 3276, 3300 + bits, 48, True)
+
+
+def test_config5_scoring_and_topk_at_13b_lora_shape():
+    """N = 8192, M = 256, k = 16384, C = 4, 2-bit datastore, top 5 % = 409."""
+    _say("config 5: score 2-bit N=8192 M=256 k=16384 C=4 + top-409")
+    _score_and_topk_at_shape(8192, 256, 16384, 4, 2, 409, 5300, 96, False)
 
 
 @pytest.mark.parametrize("M", [24, 13, 7])

@@ -205,7 +205,9 @@ def _datastore(n, k, bits, C, seed):
                                      (500, 285, 512, 3), (700, 540, 1024, 2), (520, 260, 2048, 2), (300, 1030, 640, 1),
                                      (1100, 192, 1024, 2), (600, 193, 512, 2),
                                      (300, 12, 8192, 4), (1000, 16, 8192, 3), (200, 9, 16384, 4), (100, 16, 32768, 4),
-                                     (150, 5, 65536, 2)])
+                                     (150, 5, 65536, 2),
+                                     (300, 256, 16384, 4), (260, 100, 16384, 2), (200, 40, 512, 16), (300, 140, 256, 16),
+                                     (400, 12, 384, 16)])
 def test_score_bit_exact(bits, N, M, k, C):
     _say("score bits=%d N=%d M=%d k=%d C=%d" % (bits, N, M, k, C))
     tc, tr = _datastore(N, k, bits, C, 1000 + bits)
@@ -213,7 +215,7 @@ def test_score_bit_exact(bits, N, M, k, C):
     if bits > 1:
         tc[0][5] = 0
         tr[0][5] = 0.0                                 # an all-zero code vector scores 0
-    eta = [1.0, 0.75, 0.5, 0.25, 0.125][:C]
+    eta = ([1.0, 0.75, 0.5, 0.25, 0.125] + [0.1 + 0.01 * i for i in range(11)])[:C]
     ref_s, ref_f = oracle.score(tc, tr, vc, vr, eta, k, bits, want_full=True)
     dev = lambda arrs: [torch.from_numpy(a).to(DEV) for a in arrs]
     s, f = Q.score(dev(tc), dev(tr), dev(vc), dev(vr), eta, k, bits, want_full=True)
