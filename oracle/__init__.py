@@ -67,6 +67,8 @@ def lib():
         L.oracle_less16_store.argtypes = [_vp, _i64, _i64, _i32, _vp]
         L.oracle_less16_score.restype = _c.c_int
         L.oracle_less16_score.argtypes = [_vp, _vp, _vp, _c.c_int, _i64, _i32, _i32, _vp, _vp]
+        L.oracle_score_mixed.restype = _c.c_int
+        L.oracle_score_mixed.argtypes = [_vp, _vp, _vp, _vp, _c.c_int, _i64, _i32, _i32, _c.c_int, _vp, _vp]
         L.oracle_num_threads.restype = _c.c_int
         _lib = L
     return _lib
@@ -277,4 +279,21 @@ def less16_score(train16, val16, eta, want_full=False):
     full = np.zeros((N, M), dtype=np.float64) if want_full else None
     _check(lib().oracle_less16_score(_ptr_array(tr), _ptr_array(va), _ptr(eta), C, N, M, k, _ptr(sc),
                                      _ptr(full) if want_full else None), "less16_score")
+    return (sc, full) if want_full else sc
+
+
+def score_mixed(train_codes, train_rnorm, val16, eta, k, bits, want_full=False):
+    """b-bit train codes against stored bfloat16 validation rows (uint16 [M, k]), fp64: score [N] (and full [N, M])."""
+    C = len(train_codes)
+    tc = [np.ascontiguousarray(a, dtype=np.uint8) for a in train_codes]
+    tr = [np.ascontiguousarray(a, dtype=np.float32) for a in train_rnorm]
+    va = [np.ascontiguousarray(a, dtype=np.uint16) for a in val16]
+    eta = np.ascontiguousarray(eta, dtype=np.float32)
+    if not (len(tr) == len(va) == eta.size == C):
+        raise ValueError("oracle score_mixed: one entry per checkpoint is needed in every list")
+    N, M = tc[0].shape[0], va[0].shape[0]
+    sc = np.zeros(N, dtype=np.float64)
+    full = np.zeros((N, M), dtype=np.float64) if want_full else None
+    _check(lib().oracle_score_mixed(_ptr_array(tc), _ptr_array(tr), _ptr_array(va), _ptr(eta), C, N, M, k, bits,
+                                    _ptr(sc), _ptr(full) if want_full else None), "score_mixed")
     return (sc, full) if want_full else sc

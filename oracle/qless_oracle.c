@@ -17,6 +17,7 @@
  *                       (no formula in the paper: parity unpinned)
  *   oracle_less_cosine  Eq.(2),(3), Sec. 2.2: the un-quantised LESS influence (comparator only).
  *   oracle_less16_*     the same comparator from a stored 16-bit (bfloat16) datastore (Table 1 baseline).
+ *   oracle_score_mixed  Eq.(7) with b-bit train codes against 16-bit validation rows (this build's variant).
  *
  * Arithmetic: projection sums in fp64 in index order and rounds once to fp32; integer dot
  * products in int64; the score epilogue is a fixed sequence of single fp32 operations (this file
@@ -524,6 +525,47 @@ int oracle_less16_score(const uint16_t *const *train, const uint16_t *const *val
             if (v == 0 || acc > best) best = acc;
         }
         if (score) score[z] = best;
+    }
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Mixed-precision influence: the train datastore keeps its b-bit codes (Sec. 3.1) while the few
+ * validation gradients stay at 16 bits as in LESS (Sec. 2.2: stored unit-normalised; read as
+ * bfloat16 like oracle_less16_store).  Eq.(7) with the validation factor of Eq.(6) replaced by
+ * the stored unit vector y' of Eq.(2):
+ *   acc(z,z') = sum_i eta_i * rnorm_i(z) * sum_m q_{z,i,m} * y'_{z',i,m},   score[z] = max_z' acc(z,z')
+ * everything in fp64 from the stored values (codes as integers, rnorm as the stored fp32, y' as
+ * the stored bfloat16).  The paper quantises both sides alike (Sec. 3.2); this variant is this
+ * build's reading of "validation gradients kept at higher precision" and is pinned by brute
+ * force and by the cases in which it must coincide with oracle_score / oracle_less16_score.
+ * ------------------------------------------------------------------------------------------ */
+int oracle_score_mixed(const uint8_t *const *train_codes, const float *const *train_rnorm,
+                       const uint16_t *const *val16, const float *eta, int C, int64_t N, int32_t M,
+                       int32_t k, int bits, double *score, double *full) {
+    if (!train_codes || !train_rnorm || !val16 || !eta || C <= 0 || N < 0 || M <= 0 || k <= 0 || k % 64 ||
+        (bits != 1 && bits != 2 && bits != 4 && bits != 8) || (!score && !full)) return ORACLE_BAD_ARG;
+    int64_t cb = oracle_code_bytes(k, bits);
+    int64_t z;
+    #pragma omp parallel for schedule(static)
+    for (z = 0; z < N; ++z) {
+        int8_t *tq = (int8_t *)malloc((size_t)C * (size_t)k);
+        for (int i = 0; i < C; ++i) unpack_row(train_codes[i] + z * cb, k, bits, tq + (int64_t)i * k);
+        double best = 0.0;
+        for (int32_t v = 0; v < M; ++v) {
+            double acc = 0.0;
+            for (int i = 0; i < C; ++i) {
+                const int8_t *a = tq + (int64_t)i * k;
+                const uint16_t *b = val16[i] + (int64_t)v * k;
+                double d = 0.0;
+                for (int32_t m = 0; m < k; ++m) d += (double)a[m] * bf16_value(b[m]);
+                acc += (double)eta[i] * (double)train_rnorm[i][z] * d;
+            }
+            if (full) full[z * (int64_t)M + v] = acc;
+            if (v == 0 || acc > best) best = acc;
+        }
+        if (score) score[z] = best;
+        free(tq);
     }
     return ORACLE_OK;
 }
