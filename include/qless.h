@@ -191,6 +191,27 @@ qless_status qless_score16(const void *const *train16, const void *const *val16,
                            void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Mixed-precision influence: the train datastore keeps its b-bit codes (Sec. 3.1, Eq.(4),(5)), the
+ * validation gradients stay at 16 bits as stored by qless_normalize16 (Sec. 2.2, Eq.(2)); Eq.(7) with
+ * the unit vector y' in place of the normalised validation code:
+ *   acc(z, z') = sum_{i<C} eta[i] * rnorm_i(z) * <q_{z,i}, y'_{z',i}>,    score[z] = max_{z'} acc(z, z')
+ * (the paper quantises both sides alike; this variant is the library's own).  Products are exact, sums
+ * are fp32 on the matrix cores in an unspecified order, the epilogue is (D * rnorm_i(z)) * eta[i] added
+ * over i in order: results agree with an fp64 evaluation to sum|eta| * (k/16 + 24) * 2^-24, not bit for bit.
+ *   train_codes, train_rnorm   as for qless_score (host arrays of C device pointers; codes 16-byte aligned)
+ *   val16      host array of C device pointers to M bfloat16 rows of k, 16-byte aligned
+ *   k          a multiple of 64, at most 32768;  bits in {1, 2, 4, 8};  1 <= C <= QLESS_MAX_CHECKPOINTS
+ *   score, full, stream   as for qless_score
+ *   ws         device workspace, 16-byte aligned, of at least qless_score_mixed_workspace(N, M, k, bits, C)
+ *              bytes: blocks of 8192 train rows are written out as bfloat16 values there and scored in turn
+ * ------------------------------------------------------------------------------------------- */
+size_t qless_score_mixed_workspace(int64_t N, int32_t M, int32_t k, int bits, int C);
+qless_status qless_score_mixed(const void *const *train_codes, const float *const *train_rnorm,
+                               const void *const *val16, const float *eta, int C, int64_t N, int32_t M,
+                               int32_t k, int bits, float *score, float *full,
+                               void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Selection (Sec. 4.1: the top 5 % by score): indices of the k_sel largest scores ordered by
  * (score descending, index ascending); +0 and -0 compare equal.
  *

@@ -40,6 +40,8 @@ EXPORTS = {
     "qless_normalize16": (_c.c_int, [_vp, _i64, _i64, _i32, _vp, _vp]),
     "qless_score16_workspace": (_sz, [_i64, _i32, _i32, _c.c_int]),
     "qless_score16": (_c.c_int, [_vp, _vp, _vp, _c.c_int, _i64, _i32, _i32, _vp, _vp, _vp, _sz, _vp]),
+    "qless_score_mixed_workspace": (_sz, [_i64, _i32, _i32, _c.c_int, _c.c_int]),
+    "qless_score_mixed": (_c.c_int, [_vp, _vp, _vp, _vp, _c.c_int, _i64, _i32, _i32, _c.c_int, _vp, _vp, _vp, _sz, _vp]),
     "qless_topk_workspace": (_sz, [_i64, _i64]),
     "qless_topk": (_c.c_int, [_vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
     "qless_topk_noalloc": (_c.c_int, [_vp, _i64, _i64, _vp, _vp, _vp]),
@@ -241,6 +243,34 @@ def score16(train16, val16, eta, want_score=True, want_full=False, ws=None):
                                _vp(score_out.data_ptr()) if want_score else None,
                                _vp(full_out.data_ptr()) if want_full else None,
                                _vp(w.data_ptr()), w.numel(), _stream()), "qless_score16")
+    if want_score and want_full:
+        return score_out, full_out
+    return score_out if want_score else full_out
+
+
+def score_mixed_workspace(N, M, k, bits, C):
+    return int(lib().qless_score_mixed_workspace(N, M, k, bits, C))
+
+
+def score_mixed(train_codes, train_rnorm, val16, eta, k, bits, want_score=True, want_full=False, ws=None):
+    """qless_score_mixed: b-bit train codes against bfloat16 validation rows -> score [N] (and/or full [N, M])."""
+    C = len(train_codes)
+    assert len(train_rnorm) == C and len(val16) == C and len(eta) == C
+    N, M = train_codes[0].shape[0], val16[0].shape[0]
+    dev = val16[0].device
+    for t in val16:
+        assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.shape[1] == k
+    for t in train_codes:
+        assert t.is_cuda and t.dtype == torch.uint8 and t.is_contiguous() and t.shape[1] == code_bytes(k, bits)
+    score_out = torch.empty(N, dtype=torch.float32, device=dev) if want_score else None
+    full_out = torch.empty(N, M, dtype=torch.float32, device=dev) if want_full else None
+    eta_arr = (_c.c_float * C)(*[float(e) for e in eta])
+    w = _ws(score_mixed_workspace(N, M, k, bits, C), dev, ws)
+    _check(lib().qless_score_mixed(_ptr_array(train_codes), _ptr_array(train_rnorm), _ptr_array(val16),
+                                   _c.cast(eta_arr, _vp), C, N, M, k, bits,
+                                   _vp(score_out.data_ptr()) if want_score else None,
+                                   _vp(full_out.data_ptr()) if want_full else None,
+                                   _vp(w.data_ptr()), w.numel(), _stream()), "qless_score_mixed")
     if want_score and want_full:
         return score_out, full_out
     return score_out if want_score else full_out

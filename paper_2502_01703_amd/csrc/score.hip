@@ -347,10 +347,13 @@ score_prepare_kernel(ScoreArgs a, ScorePrep w) {
     }
 }
 
-__global__ void score_finish_kernel(const unsigned int *smax, int64_t N, float *score) {
+// also leaves the keys cleared, so that a later launch on the same workspace needs no pre-pass
+__global__ void score_finish_kernel(unsigned int *smax, int64_t N, float *score) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N;
-         i += (int64_t)gridDim.x * blockDim.x)
+         i += (int64_t)gridDim.x * blockDim.x) {
         score[i] = f32_from_order_key(smax[i]);
+        smax[i] = 0u;
+    }
 }
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -1370,7 +1373,9 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
         // Lane L < 32 WR of the wave holds rnorm of train row (trow + L); rows are fetched by shuffle.
         int64_t myrow = row0 + trow + (lane & (32 * WR - 1));
         if (myrow > a.N - 1) myrow = a.N - 1;
-        const float rt_lane = F16 ? 1.0f : a.tr[ci][myrow];
+        // bfloat16 rows: no train factor (the 16-bit comparator's rows are unit vectors) unless the caller
+        // gives one (mixed precision: rows of integer codes with their 1 / ||q||)
+        const float rt_lane = (F16 && !a.tr[ci]) ? 1.0f : a.tr[ci][myrow];
         float wv[WC];
         int vbias[WC];
 #pragma unroll
@@ -1388,7 +1393,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
                 for (int c = 0; c < WC; ++c) {
                     float t;
                     if (F16) {
-                        t = __fmul_rn((float)acc[b][c][v], wv[c]);
+                        t = __fmul_rn(__fmul_rn((float)acc[b][c][v], rt), wv[c]);     // rt = 1: the product is acc itself
                     } else {
                         int D = BITS == 4 ? ((int)acc[b][c][v] >> 4) : (int)acc[b][c][v];   // 1-/2-bit: an exact integer in fp32
                         if (BITS == 1 && !Sh::VPACKED) D += vbias[c];
@@ -1511,15 +1516,18 @@ static NarrowChoice choose_narrow(int64_t N) {
     return best;
 }
 
+// prepare = false: the workspace still holds the pre-pass of an earlier launch with the same validation
+// side and at least as many train rows (the finish kernel leaves the row maxima cleared)
 template <int BITS, bool F16 = false>
-static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st) {
-    const MfmaPlan p = mfma_plan(a.N, a.M, a.k, BITS, a.C);
+static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st, bool prepare = true, int64_t plan_rows = 0) {
+    const MfmaPlan p = mfma_plan(plan_rows > 0 ? plan_rows : a.N, a.M, a.k, BITS, a.C);
     ScorePrep w{};
     unsigned char *base = (unsigned char *)ws;
     w.vexp = (int8_t *)base; w.vw = (float *)(base + p.off_vw); w.vbias = (int32_t *)(base + p.off_vbias);
     w.smax = (unsigned int *)(base + p.off_smax); w.Mp = p.Mp; w.kp = p.kp;
     w.vrow = BITS == 1 ? (p.vt > 64 ? p.kp / 2 : 0) : (BITS == 2 ? p.kp / 2 : p.kp);
-    hipLaunchKernelGGL((score_prepare_kernel<BITS, F16>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
+    if (prepare)
+        hipLaunchKernelGGL((score_prepare_kernel<BITS, F16>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
     qless_status rc;
     if (p.vt == 96) {
         if constexpr (BITS == 1) rc = launch_mfma_shape<BITS, 2, 3, 1, 8, F16>(a, w, 0, st);
@@ -1687,9 +1695,126 @@ static void launch_popcount(const ScoreArgs &a, hipStream_t st) {
     hipLaunchKernelGGL((score_popcount_kernel<BITS, RT, CT, TY, TX>), dim3(grid), dim3(256), lds, st, a);
 }
 
+// ------------------------------------------------------------------------------------------
+// Mixed precision: b-bit train codes against bfloat16 validation rows.  The train codes of a block
+// of rows are written out as bfloat16 values (small integers: exact) and the block is scored by the
+// bfloat16 matrix-core kernel of the 16-bit comparator with the code norms as train factors.
+// ------------------------------------------------------------------------------------------
+constexpr int64_t kMixedRows = 8192;           // train rows per block
+
+struct ExpandArgs {
+    const unsigned char *tc[QLESS_MAX_CHECKPOINTS];
+    uint16_t *out;                             // [C][rows][k] bfloat16
+    int64_t r0, rows;
+    int32_t k;
+    int C;
+};
+
+__device__ inline uint32_t bf16_pair(int lo, int hi) {                // exact for |values| < 256
+    return (__float_as_uint((float)lo) >> 16) | (__float_as_uint((float)hi) & 0xFFFF0000u);
+}
+
+// one thread per 8 consecutive codes of a row
+template <int BITS>
+__global__ void __launch_bounds__(256)
+mixed_expand_kernel(ExpandArgs e) {
+    const int per_row = e.k / 8;
+    const int64_t total = (int64_t)e.C * e.rows * per_row;
+    const int64_t cb = (int64_t)e.k * BITS / 8;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int g = (int)(i % per_row);
+        const int64_t rr = i / per_row;
+        const int64_t r = rr % e.rows;
+        const int ci = (int)(rr / e.rows);
+        const unsigned char *src = e.tc[ci] + (e.r0 + r) * cb;
+        int q[8];
+        if (BITS == 8) {
+            const uint2 w = *(const uint2 *)(src + 8 * g);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) { q[t] = (int)(int8_t)(w.x >> (8 * t)); q[4 + t] = (int)(int8_t)(w.y >> (8 * t)); }
+        } else if (BITS == 4) {
+            const uint32_t w = *(const uint32_t *)(src + 4 * g);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) q[t] = ((int)(w << (28 - 4 * t))) >> 28;       // sign-extended nibble t
+        } else {
+            const unsigned sg = src[(BITS == 2 ? e.k / 8 : 0) + g];
+            const unsigned nz = BITS == 2 ? src[g] : 0xFFu;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) q[t] = ((nz >> t) & 1u) ? (((sg >> t) & 1u) ? -1 : 1) : 0;
+        }
+        uint4 o;
+        o.x = bf16_pair(q[0], q[1]); o.y = bf16_pair(q[2], q[3]); o.z = bf16_pair(q[4], q[5]); o.w = bf16_pair(q[6], q[7]);
+        *(uint4 *)(e.out + ((size_t)ci * e.rows + r) * (size_t)e.k + 8 * g) = o;
+    }
+}
+
+struct MixedPlan { int64_t rows; size_t off_tiles, total; };
+static MixedPlan mixed_plan(int64_t N, int32_t M, int32_t k, int C) {
+    MixedPlan p{};
+    p.rows = N < kMixedRows ? (N > 0 ? N : 1) : kMixedRows;
+    size_t o = (size_t)C * (size_t)p.rows * (size_t)k * 2;
+    o = (o + 255) & ~(size_t)255;
+    p.off_tiles = o;
+    p.total = o + mfma_plan(p.rows, M, 2 * k, 8, C).total;
+    return p;
+}
+
 }  // namespace qless
 
 using namespace qless;
+
+extern "C" size_t qless_score_mixed_workspace(int64_t N, int32_t M, int32_t k, int bits, int C) {
+    if (N < 0 || M < 1 || k <= 0 || k > 32768 || C < 1 || !valid_bits(bits)) return 0;
+    return mixed_plan(N, M, k, C).total;
+}
+
+extern "C" qless_status qless_score_mixed(const void *const *train_codes, const float *const *train_rnorm,
+                                          const void *const *val16, const float *eta, int C, int64_t N, int32_t M,
+                                          int32_t k, int bits, float *score, float *full, void *ws, size_t ws_bytes,
+                                          void *stream) {
+    if (!train_codes || !train_rnorm || !val16 || !eta) return QLESS_ERR_INVALID_ARG;
+    if (C < 1 || N < 0 || M < 1 || k <= 0) return QLESS_ERR_INVALID_ARG;
+    if (!score && !full) return QLESS_ERR_INVALID_ARG;
+    if (C > QLESS_MAX_CHECKPOINTS || !valid_bits(bits) || k % 64 != 0 || k > 32768) return QLESS_ERR_UNSUPPORTED;
+    if (N > (int64_t)0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
+    for (int i = 0; i < C; ++i) {
+        if (!val16[i] || (N > 0 && (!train_codes[i] || !train_rnorm[i]))) return QLESS_ERR_INVALID_ARG;
+        if ((uintptr_t)val16[i] % 16 || (uintptr_t)train_codes[i] % 16) return QLESS_ERR_INVALID_ARG;
+    }
+    if (N == 0) return QLESS_OK;
+    const MixedPlan mp = mixed_plan(N, M, k, C);
+    if (!ws || ws_bytes < mp.total || (uintptr_t)ws % 16) return QLESS_ERR_WORKSPACE;
+    const qless_status ready = device_ready();
+    if (ready != QLESS_OK) return ready;
+    hipStream_t st = (hipStream_t)stream;
+    ExpandArgs e{};
+    e.out = (uint16_t *)ws; e.k = k; e.C = C;
+    for (int i = 0; i < C; ++i) e.tc[i] = (const unsigned char *)train_codes[i];
+    for (int64_t r0 = 0; r0 < N; r0 += mp.rows) {
+        const int64_t rows = N - r0 < mp.rows ? N - r0 : mp.rows;
+        e.r0 = r0; e.rows = rows;
+        int64_t blocks = ((int64_t)C * rows * (k / 8) + 255) / 256;
+        if (blocks > 16384) blocks = 16384;
+        switch (bits) {
+            case 8: hipLaunchKernelGGL(mixed_expand_kernel<8>, dim3((unsigned)blocks), dim3(256), 0, st, e); break;
+            case 4: hipLaunchKernelGGL(mixed_expand_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, st, e); break;
+            case 2: hipLaunchKernelGGL(mixed_expand_kernel<2>, dim3((unsigned)blocks), dim3(256), 0, st, e); break;
+            default: hipLaunchKernelGGL(mixed_expand_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, st, e); break;
+        }
+        ScoreArgs a{};
+        for (int i = 0; i < C; ++i) {
+            a.tc[i] = (const unsigned char *)(e.out + (size_t)i * rows * (size_t)k);
+            a.vc[i] = (const unsigned char *)val16[i];
+            a.tr[i] = train_rnorm[i] + r0; a.vr[i] = nullptr; a.eta[i] = eta[i];
+        }
+        a.C = C; a.N = rows; a.M = M; a.k = 2 * k;                    // k in bytes from here on
+        a.score = score ? score + r0 : nullptr;
+        a.full = full ? full + r0 * (int64_t)M : nullptr;
+        const qless_status rc = launch_mfma<8, true>(a, (unsigned char *)ws + mp.off_tiles, st, r0 == 0, mp.rows);
+        if (rc != QLESS_OK) return rc;
+    }
+    return launch_status();
+}
 
 extern "C" size_t qless_score_workspace(int64_t N, int32_t M, int32_t k, int bits, int C) {
     if (N < 0 || M < 1 || k <= 0 || C < 1 || !valid_bits(bits)) return 0;

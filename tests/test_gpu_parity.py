@@ -450,3 +450,32 @@ def test_quantize_score_topk_replay_in_a_hip_graph(bits, M):
         torch.cuda.synchronize()
         assert torch.equal(got_s, sc), rep
         assert torch.equal(got_i, e_idx) and torch.equal(got_v, e_val), rep
+
+
+# ------------------------------------------------------------------- mixed precision (16-bit validation rows)
+@pytest.mark.parametrize("bits", [8, 4, 2, 1])
+@pytest.mark.parametrize("N,M,k,C", [(300, 70, 576, 3), (129, 8, 1024, 2), (9000, 33, 256, 2), (64, 130, 8192, 4),
+                                     (17000, 12, 128, 1), (1, 1, 64, 1)])
+def test_mixed_precision_score_within_the_derived_tolerance(bits, N, M, k, C):
+    """b-bit train codes against bfloat16 validation rows: |acc - fp64| <= sum|eta| (k/16 + 24) 2^-24 1.01 for every
+    pair (the bound of the design notes), row maxima within the same bound; N > 8192 takes several blocks."""
+    _say("mixed score bits=%d N=%d M=%d k=%d C=%d" % (bits, N, M, k, C))
+    rng = np.random.default_rng(5000 + bits + N)
+    tq = [oracle.quantize((rng.standard_normal((N, k)) * np.exp(rng.standard_normal((N, 1)))).astype(np.float32), bits)
+          for _ in range(C)]
+    tc, tr = [t[0] for t in tq], [t[2] for t in tq]
+    if bits > 1 and N > 5:
+        tc[0][5] = 0
+        tr[0][5] = 0.0
+    v16 = [oracle.less16_store((rng.standard_normal((M, k)) * np.exp(rng.standard_normal((M, 1)))).astype(np.float32))
+           for _ in range(C)]
+    eta = [1.0, 0.75, 0.5, 0.25][:C]
+    ref_s, ref_f = oracle.score_mixed(tc, tr, v16, eta, k, bits, want_full=True)
+    dev = lambda arrs: [torch.from_numpy(a).to(DEV) for a in arrs]
+    dv16 = [torch.from_numpy(a.view(np.int16)).to(DEV).view(torch.bfloat16) for a in v16]
+    s, f = Q.score_mixed(dev(tc), dev(tr), dv16, eta, k, bits, want_full=True)
+    tol = sum(eta) * (k / 16 + 24) * 2.0 ** -24 * 1.01
+    assert np.abs(f.cpu().numpy().astype(np.float64) - ref_f).max() <= tol
+    assert np.abs(s.cpu().numpy().astype(np.float64) - ref_s).max() <= tol
+    assert torch.equal(s, f.max(dim=1).values)
+    assert torch.equal(s, Q.score_mixed(dev(tc), dev(tr), dv16, eta, k, bits))

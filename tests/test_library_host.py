@@ -169,3 +169,26 @@ def test_misaligned_workspaces_and_codes_are_refused():
     assert L.qless_project(one, 1, 4, 64, 64, 0, 64, 0, 0, 0, one, 64, odd, need + 64, None) == WORKSPACE
     assert L.qless_quantize(one, 64, 4, 64, 8, odd, one, one, None) == INVALID
     assert L.qless_quantize_absmean(one, 64, 4, 64, 8, odd, one, one, None) == INVALID
+
+
+def test_score_mixed_argument_validation():
+    L = binding.lib()
+    one = ctypes.c_void_p(16)
+    ptrs = (ctypes.c_void_p * 1)(16)
+    eta = (ctypes.c_float * 1)(1.0)
+    f = L.qless_score_mixed
+    a = lambda C=1, N=4, M=2, k=64, bits=8, score=one, ws=one, wsb=1 << 30, tc=ptrs: (
+        tc, ptrs, ptrs, ctypes.cast(eta, ctypes.c_void_p), C, N, M, k, bits, score, None, ws, wsb, None)
+    assert f(*a(C=0)) == INVALID
+    assert f(*a(M=0)) == INVALID
+    assert f(*a(score=None)) == INVALID
+    assert f(*a(bits=3)) == UNSUPPORTED
+    assert f(*a(k=100)) == UNSUPPORTED
+    assert f(*a(k=65536)) == UNSUPPORTED
+    assert f(*a(ws=None)) == WORKSPACE
+    assert f(*a(wsb=16)) == WORKSPACE
+    assert f(*a(ws=ctypes.c_void_p(24))) == WORKSPACE
+    assert f(*a(N=0, ws=None, wsb=0)) == OK
+    need = L.qless_score_mixed_workspace(20000, 100, 1024, 4, 2)
+    assert need >= 2 * 8192 * 1024 * 2
+    assert L.qless_score_mixed_workspace(4, 2, 64, 3, 1) == 0
