@@ -139,6 +139,32 @@ qless_status qless_project_quantize(const void *G, qless_dtype dt, int64_t n, in
                                     float *P, int64_t ldP, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * The same datastore build for gradients that arrive in slices (Sec. 3.1 projects and stores each
+ * gradient as it is extracted; per-example gradients come layer by layer).  One call per slice, in any
+ * fixed order of the caller's choosing:
+ *   P = (first ? 0 : P) + R[:, d_offset : d_offset + d_len] G        (fp32, the slice's own partial sums
+ *                                                                     added first, then the running P)
+ * and on the slice with last != 0, after that addition, P = P + P_other (if given) and then
+ * Eq.(4),(5) on the rows of P into codes, S, rnorm.  The result is the same bits as qless_project with
+ * accumulate over the same slices in the same order followed by qless_quantize; on the last slice the
+ * additions and the quantiser run in one kernel (k <= 16384), so that slice's partial sums and the
+ * final P are not read back from memory.
+ *   P        device, n x k fp32 accumulator with leading dimension ldP >= k; holds the projection afterwards
+ *   P_other  device, n x k fp32 with leading dimension ldO, or NULL; only with last != 0.  It lets a caller
+ *            run alternate slices on two streams, each stream with its own accumulator and workspace
+ *            (so that one slice's tail overlaps the next one's start), and join the two sums in a fixed
+ *            order; the caller orders the last call after the other stream's work (an event).
+ *   codes, S, rnorm, bits   as for qless_quantize; read only when last != 0
+ *   ws       as for qless_project (16-byte aligned, qless_project_workspace(n, d_len, k) bytes)
+ * d_len == 0 is valid (the slice adds nothing).
+ * ------------------------------------------------------------------------------------------- */
+qless_status qless_project_quantize_slice(const void *G, qless_dtype dt, int64_t n, int64_t d_len, int64_t ldG,
+                                          int64_t d_offset, int32_t k, qless_proj kind, uint64_t seed,
+                                          int first, int last, float *P, int64_t ldP,
+                                          const float *P_other, int64_t ldO, int bits, void *codes,
+                                          float *S, float *rnorm, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Influence scores, Eq.(6),(7) (Sec. 3.2) and the max over validation examples:
  *   acc(z, z') = sum_{i<C} eta[i] * <q_{z,i}, q_{z',i}> * rnorm_i(z) * rnorm'_i(z')
  *   score[z]   = max_{z' < M} acc(z, z')

@@ -34,6 +34,8 @@ EXPORTS = {
     "qless_quantize_absmean": (_c.c_int, [_vp, _i64, _i64, _i32, _c.c_int, _vp, _vp, _vp, _vp]),
     "qless_project_quantize": (_c.c_int, [_vp, _c.c_int, _i64, _i64, _i64, _i64, _i32, _c.c_int, _u64, _c.c_int,
                                           _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
+    "qless_project_quantize_slice": (_c.c_int, [_vp, _c.c_int, _i64, _i64, _i64, _i64, _i32, _c.c_int, _u64, _c.c_int, _c.c_int,
+                                                _vp, _i64, _vp, _i64, _c.c_int, _vp, _vp, _vp, _vp, _sz, _vp]),
     "qless_score_workspace": (_sz, [_i64, _i32, _i32, _c.c_int, _c.c_int]),
     "qless_score": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _c.c_int, _i64, _i32, _i32, _c.c_int, _vp, _vp,
                                _vp, _sz, _vp]),
@@ -173,6 +175,34 @@ def project_quantize(G, k, bits, kind=RADEMACHER, seed=0, d_offset=0, want_P=Fal
                                         _vp(P.data_ptr()) if want_P else None, k,
                                         _vp(w.data_ptr()), w.numel(), _stream()), "qless_project_quantize")
     return (codes, S, rnorm, P) if want_P else (codes, S, rnorm)
+
+
+def project_quantize_slice(G, k, d_offset, P, first, last, bits=1, kind=RADEMACHER, seed=0, P_other=None,
+                           codes=None, S=None, rnorm=None, ws=None):
+    """qless_project_quantize_slice: P (n x k fp32 accumulator) takes the slice G [n, d_len] at column d_offset of
+    R; with last, P_other is added and the rows are quantised into codes, S, rnorm (returned)."""
+    assert G.is_cuda and G.dim() == 2 and G.stride(1) == 1
+    assert P.is_cuda and P.dtype == torch.float32 and P.stride(1) == 1 and P.shape[1] == k
+    n, d = G.shape
+    dev = G.device
+    if last:
+        if codes is None:
+            codes = torch.empty(n, code_bytes(k, bits), dtype=torch.uint8, device=dev)
+        if S is None:
+            S = torch.empty(n, dtype=torch.float32, device=dev)
+        if rnorm is None:
+            rnorm = torch.empty(n, dtype=torch.float32, device=dev)
+    ldG = G.stride(0) if n > 1 else max(d, G.stride(0))
+    ldP = P.stride(0) if n > 1 else max(k, P.stride(0))
+    ldO = 0 if P_other is None else (P_other.stride(0) if n > 1 else max(k, P_other.stride(0)))
+    w = _ws(project_workspace(n, d, k), dev, ws)
+    _check(lib().qless_project_quantize_slice(
+        _vp(G.data_ptr()), _dtype_code(G), n, d, ldG, d_offset, k, kind, seed, int(first), int(last),
+        _vp(P.data_ptr()), ldP, _vp(P_other.data_ptr()) if P_other is not None else None, ldO, bits,
+        _vp(codes.data_ptr()) if last else None, _vp(S.data_ptr()) if last else None,
+        _vp(rnorm.data_ptr()) if last else None, _vp(w.data_ptr()), w.numel(), _stream()),
+        "qless_project_quantize_slice")
+    return (codes, S, rnorm) if last else None
 
 
 def score_workspace(N, M, k, bits, C):

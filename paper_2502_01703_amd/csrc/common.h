@@ -92,9 +92,12 @@ inline bool valid_bits(int bits) { return bits == 1 || bits == 2 || bits == 4 ||
 
 // quantize.hip: Eq.(4),(5) over n rows whose value at (row, m) is the sum, in ascending s, of
 // src[s * plane + row * ld + m] for s < nsplit; `keep` (or null) receives the summed rows in fp32.
+// With `accum` the value is accum[row * ldA + m] + (that sum), and `other[row * ldO + m]` is added last
+// (accum may be the same memory as keep; rows of at most 16384 elements then).
 qless_status quantize_rows(const float *src, int64_t ld, int nsplit, size_t plane, float *keep, int64_t ldK,
                            int64_t n, int32_t k, int bits, void *codes, float *S, float *rnorm,
-                           hipStream_t st);
+                           hipStream_t st, const float *accum = nullptr, int64_t ldA = 0,
+                           const float *other = nullptr, int64_t ldO = 0);
 
 // Gaussian table (bf16 bit patterns), built once on the host
 const uint16_t *gaussian_table_bf16();

@@ -480,6 +480,54 @@ extern "C" qless_status qless_project_quantize(const void *G, qless_dtype dt, in
                          rnorm, st);
 }
 
+// P = (accumulate ? P : 0) + other, element by element (joins two accumulators when the last slice is
+// too long-rowed for the fused path)
+__global__ void __launch_bounds__(256)
+add_rows_kernel(float *P, int64_t ldP, const float *other, int64_t ldO, int64_t n, int32_t k) {
+    const int64_t total = n * (int64_t)k;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = i / k, m = i - row * k;
+        P[row * ldP + m] = P[row * ldP + m] + other[row * ldO + m];
+    }
+}
+
+extern "C" qless_status qless_project_quantize_slice(const void *G, qless_dtype dt, int64_t n, int64_t d_len,
+                                                     int64_t ldG, int64_t d_offset, int32_t k, qless_proj kind,
+                                                     uint64_t seed, int first, int last, float *P, int64_t ldP,
+                                                     const float *P_other, int64_t ldO, int bits, void *codes,
+                                                     float *S, float *rnorm, void *ws, size_t ws_bytes,
+                                                     void *stream) {
+    if (ldP < k || (n > 0 && !P) || (P_other && ldO < k)) return QLESS_ERR_INVALID_ARG;
+    if (P_other && !last) return QLESS_ERR_INVALID_ARG;
+    if (last) {
+        if (n > 0 && (!codes || !S || !rnorm)) return QLESS_ERR_INVALID_ARG;
+        if ((uintptr_t)codes % 4) return QLESS_ERR_INVALID_ARG;
+        if (!valid_bits(bits)) return QLESS_ERR_UNSUPPORTED;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    int nsplit = 0;
+    const qless_status rc = project_partials(G, dt, n, d_len, ldG, d_offset, k, kind, seed, ws, ws_bytes,
+                                             st, &nsplit);
+    if (rc != QLESS_OK || n == 0) return rc;
+    const int64_t total = n * (int64_t)k;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    // the last slice of rows that fit in registers: its partial sums, the accumulator and the second
+    // accumulator are added by the quantiser itself, in the order of the separate kernels
+    const bool fused = last && nsplit > 0 && k <= 16384;
+    if (!fused) {
+        if (nsplit > 0 || first)
+            hipLaunchKernelGGL(project_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                               (const float *)ws, nsplit, n, k, first ? 0 : 1, P, ldP);
+        if (!last) return launch_status();
+        if (P_other)
+            hipLaunchKernelGGL(add_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, P, ldP, P_other, ldO, n, k);
+        return quantize_rows(P, ldP, 1, 0, nullptr, 0, n, k, bits, codes, S, rnorm, st);
+    }
+    return quantize_rows((const float *)ws, k, nsplit, (size_t)n * (size_t)k, P, ldP, n, k, bits, codes, S,
+                         rnorm, st, first ? nullptr : P, ldP, P_other, ldO);
+}
+
 extern "C" qless_status qless_generator_words(uint64_t seed, uint32_t m0, int32_t nrows,
                                               uint32_t w0, int32_t nwords, uint32_t salt,
                                               uint32_t *out, void *stream) {

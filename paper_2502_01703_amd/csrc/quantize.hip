@@ -61,9 +61,11 @@ __device__ inline int quant1(float p, float scale, float alpha) {
 // The row's value at element m is p[m] + p[plane + m] + ... over nsplit planes, added in that
 // order (nsplit = 1 for an ordinary matrix; the fused projection passes its split-d partial sums).
 // SUM = false is the plain matrix (one plane): no loop, so a thread's loads go out back to back.
+// With an accumulator row `acc` the value is acc[m] + (that sum), and with a second one, `oth`, oth[m] is
+// added last (the sliced datastore build: slices accumulated in call order, two accumulators joined).
 template <int E, bool SUM>
 __device__ inline void load_elems(const float *p, int base, int32_t k, bool vec, int nsplit, size_t plane,
-                                  float (&v)[E]) {
+                                  float (&v)[E], const float *acc = nullptr, const float *oth = nullptr) {
     const bool in = base < k;
     const int b = in ? base : k - E;
     if (!SUM) nsplit = 1;
@@ -87,6 +89,16 @@ __device__ inline void load_elems(const float *p, int base, int32_t k, bool vec,
                 f.x = __fadd_rn(f.x, t.x); f.y = __fadd_rn(f.y, t.y);
                 f.z = __fadd_rn(f.z, t.z); f.w = __fadd_rn(f.w, t.w);
             }
+            if (SUM && acc) {
+                const float4 t = *(const float4 *)(acc + b + e);
+                f.x = __fadd_rn(t.x, f.x); f.y = __fadd_rn(t.y, f.y);
+                f.z = __fadd_rn(t.z, f.z); f.w = __fadd_rn(t.w, f.w);
+            }
+            if (SUM && oth) {
+                const float4 t = *(const float4 *)(oth + b + e);
+                f.x = __fadd_rn(f.x, t.x); f.y = __fadd_rn(f.y, t.y);
+                f.z = __fadd_rn(f.z, t.z); f.w = __fadd_rn(f.w, t.w);
+            }
             v[e] = in ? f.x : 0.0f; v[e + 1] = in ? f.y : 0.0f;
             v[e + 2] = in ? f.z : 0.0f; v[e + 3] = in ? f.w : 0.0f;
         }
@@ -95,6 +107,8 @@ __device__ inline void load_elems(const float *p, int base, int32_t k, bool vec,
         for (int e = 0; e < E; ++e) {
             float f = p[b + e];
             for (int s = 1; s < nsplit; ++s) f = __fadd_rn(f, p[(size_t)s * plane + b + e]);
+            if (SUM && acc) f = __fadd_rn(acc[b + e], f);
+            if (SUM && oth) f = __fadd_rn(f, oth[b + e]);
             v[e] = in ? f : 0.0f;
         }
     }
@@ -174,7 +188,8 @@ template <int BITS, int NG, bool SUM, bool MEAN = false>   // NG > 0: the row fi
 __global__ void __launch_bounds__(kQThreads)
 quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned char *__restrict__ codes,
                 float *__restrict__ S_out, float *__restrict__ rnorm_out, int vec, int nsplit, size_t plane,
-                float *__restrict__ keep, int64_t ldK) {
+                float *keep, int64_t ldK, const float *accum = nullptr, int64_t ldA = 0,
+                const float *other = nullptr, int64_t ldO = 0) {
     constexpr int E = 4;
     constexpr int GROUP = kQThreads * E;
     constexpr bool CACHED = NG > 0;
@@ -186,6 +201,7 @@ quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned ch
     const float *p = P + row * ldP;
     unsigned char *crow = codes + row * ((int64_t)k * BITS / 8);
     float *krow = keep ? keep + row * ldK : nullptr;
+    const float *arow = accum ? accum + row * ldA : nullptr, *orow = other ? other + row * ldO : nullptr;
     const int ngroups = (k + GROUP - 1) / GROUP;
 
     float reg[MAXG][E];
@@ -194,7 +210,7 @@ quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned ch
 #pragma unroll
         for (int g = 0; g < MAXG; ++g) {
             if (g < ngroups) {
-                load_elems<E, SUM>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[g]);
+                load_elems<E, SUM>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[g], arow, orow);
                 if (SUM) keep_elems<E>(krow, g * GROUP + tid * E, k, vec != 0, reg[g]);
 #pragma unroll
                 for (int e = 0; e < E; ++e) amax = fmaxf(amax, fabsf(reg[g][e]));
@@ -202,7 +218,7 @@ quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned ch
         }
     } else {
         for (int g = 0; g < ngroups; ++g) {
-            load_elems<E, SUM>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[0]);
+            load_elems<E, SUM>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[0], arow, orow);
             if (SUM) keep_elems<E>(krow, g * GROUP + tid * E, k, vec != 0, reg[0]);
 #pragma unroll
             for (int e = 0; e < E; ++e) amax = fmaxf(amax, fabsf(reg[0][e]));
@@ -229,7 +245,7 @@ quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned ch
                     }
             } else {
                 for (int g = 0; g < ngroups; ++g) {
-                    load_elems<E, SUM>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[0]);
+                    load_elems<E, SUM>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[0], arow, orow);
 #pragma unroll
                     for (int e = 0; e < E; ++e) u += (uint32_t)ldexpf(fabsf(reg[0][e]), 32 - ex);
                 }
@@ -251,7 +267,7 @@ quantize_kernel(const float *__restrict__ P, int64_t ldP, int32_t k, unsigned ch
             if (g < ngroups) emit_elems<BITS, E>(reg[g], g * GROUP + tid * E, k, scale, alpha, crow, lane, n2);
     } else {
         for (int g = 0; g < ngroups; ++g) {
-            load_elems<E, SUM>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[0]);
+            load_elems<E, SUM>(p, g * GROUP + tid * E, k, vec != 0, nsplit, plane, reg[0], arow, orow);
             emit_elems<BITS, E>(reg[0], g * GROUP + tid * E, k, scale, alpha, crow, lane, n2);
         }
     }
@@ -279,7 +295,8 @@ __global__ void __launch_bounds__(kQThreads)
 quantize_wave_kernel(const float *__restrict__ P, int64_t ldP, int64_t n, int32_t k,
                      unsigned char *__restrict__ codes, float *__restrict__ S_out,
                      float *__restrict__ rnorm_out, int nsplit, size_t plane,
-                     float *__restrict__ keep, int64_t ldK) {
+                     float *keep, int64_t ldK, const float *accum = nullptr, int64_t ldA = 0,
+                     const float *other = nullptr, int64_t ldO = 0) {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= n) return;                       // whole wavefront; nothing below synchronises
@@ -289,7 +306,8 @@ quantize_wave_kernel(const float *__restrict__ P, int64_t ldP, int64_t n, int32_
     float amax = 0.0f;
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-        load_elems<4, SUM>(p, g * 256 + lane * 4, k, VEC, nsplit, plane, reg[g]);
+        load_elems<4, SUM>(p, g * 256 + lane * 4, k, VEC, nsplit, plane, reg[g], accum ? accum + row * ldA : nullptr,
+                           other ? other + row * ldO : nullptr);
         if (SUM) keep_elems<4>(keep ? keep + row * ldK : nullptr, g * 256 + lane * 4, k, VEC, reg[g]);
 #pragma unroll
         for (int e = 0; e < 4; ++e) amax = fmaxf(amax, fabsf(reg[g][e]));
@@ -313,23 +331,27 @@ quantize_wave_kernel(const float *__restrict__ P, int64_t ldP, int64_t n, int32_
 // each sum many planes (more loads in flight per row).
 template <int BITS>
 static void launch_quantize(const float *P, int64_t ldP, int nsplit, size_t plane, float *keep, int64_t ldK,
-                            int64_t n, int32_t k, void *codes, float *S, float *rnorm, hipStream_t st) {
+                            int64_t n, int32_t k, void *codes, float *S, float *rnorm, hipStream_t st,
+                            const float *accum = nullptr, int64_t ldA = 0, const float *other = nullptr, int64_t ldO = 0) {
     constexpr int E = 4;
     const int groups = (k + kQThreads * E - 1) / (kQThreads * E);
     const int vec = ((uintptr_t)P % 16 == 0 && ldP % 4 == 0 && plane % 4 == 0 &&
-                     (!keep || ((uintptr_t)keep % 16 == 0 && ldK % 4 == 0))) ? 1 : 0;
+                     (!keep || ((uintptr_t)keep % 16 == 0 && ldK % 4 == 0)) &&
+                     (!accum || ((uintptr_t)accum % 16 == 0 && ldA % 4 == 0)) &&
+                     (!other || ((uintptr_t)other % 16 == 0 && ldO % 4 == 0))) ? 1 : 0;
     // summing kernels exist for 16-byte aligned planes only (the projection workspace always is)
-    const bool sum = nsplit > 1 || keep != nullptr;
+    const bool sum = nsplit > 1 || keep != nullptr || accum != nullptr || other != nullptr;
     if (k <= 8192 && (!sum || (n >= 2048 && vec))) {
         // wavefront per row; 4 rows per workgroup
         for (int64_t r0 = 0; r0 < n; r0 += 0x40000000) {
             const int64_t rows = n - r0 < 0x40000000 ? n - r0 : 0x40000000;
             const float *p = P + r0 * ldP;
             float *kp = keep ? keep + r0 * ldK : nullptr;
+            const float *ap = accum ? accum + r0 * ldA : nullptr, *op = other ? other + r0 * ldO : nullptr;
             unsigned char *c = (unsigned char *)codes + r0 * ((int64_t)k * BITS / 8);
             const dim3 grid((unsigned)((rows + 3) / 4)), block(kQThreads);
 #define QLESS_QW(NG) do { \
-                if (sum) hipLaunchKernelGGL((quantize_wave_kernel<BITS, NG, true, true>), grid, block, 0, st, p, ldP, rows, k, c, S + r0, rnorm + r0, nsplit, plane, kp, ldK); \
+                if (sum) hipLaunchKernelGGL((quantize_wave_kernel<BITS, NG, true, true>), grid, block, 0, st, p, ldP, rows, k, c, S + r0, rnorm + r0, nsplit, plane, kp, ldK, ap, ldA, op, ldO); \
                 else if (vec) hipLaunchKernelGGL((quantize_wave_kernel<BITS, NG, true, false>), grid, block, 0, st, p, ldP, rows, k, c, S + r0, rnorm + r0, nsplit, plane, kp, ldK); \
                 else hipLaunchKernelGGL((quantize_wave_kernel<BITS, NG, false, false>), grid, block, 0, st, p, ldP, rows, k, c, S + r0, rnorm + r0, nsplit, plane, kp, ldK); } while (0)
             if (k <= 2048) QLESS_QW(8);
@@ -344,10 +366,11 @@ static void launch_quantize(const float *P, int64_t ldP, int nsplit, size_t plan
         const int64_t rows = n - r0 < 0x40000000 ? n - r0 : 0x40000000;
         const float *p = P + r0 * ldP;
         float *kp = keep ? keep + r0 * ldK : nullptr;
+        const float *ap = accum ? accum + r0 * ldA : nullptr, *op = other ? other + r0 * ldO : nullptr;
         unsigned char *c = (unsigned char *)codes + r0 * ((int64_t)k * BITS / 8);
 #define QLESS_QB(NG) do { \
             if (sum) hipLaunchKernelGGL((quantize_kernel<BITS, NG, true>), dim3((unsigned)rows), dim3(kQThreads), 0, st, \
-                                        p, ldP, k, c, S + r0, rnorm + r0, vec, nsplit, plane, kp, ldK); \
+                                        p, ldP, k, c, S + r0, rnorm + r0, vec, nsplit, plane, kp, ldK, ap, ldA, op, ldO); \
             else hipLaunchKernelGGL((quantize_kernel<BITS, NG, false>), dim3((unsigned)rows), dim3(kQThreads), 0, st, \
                                     p, ldP, k, c, S + r0, rnorm + r0, vec, nsplit, plane, kp, ldK); } while (0)
         if (groups <= 4) QLESS_QB(4);
@@ -380,12 +403,14 @@ static void launch_quantize_absmean(const float *P, int64_t ldP, int64_t n, int3
 
 qless_status quantize_rows(const float *src, int64_t ld, int nsplit, size_t plane, float *keep, int64_t ldK,
                            int64_t n, int32_t k, int bits, void *codes, float *S, float *rnorm,
-                           hipStream_t st) {
+                           hipStream_t st, const float *accum, int64_t ldA, const float *other, int64_t ldO) {
+    // rows too long for registers are read twice: an accumulator that the kept copy overwrites cannot be
+    if ((accum || other) && k > kQThreads * 4 * 16) return QLESS_ERR_UNSUPPORTED;
     switch (bits) {
-        case 8: launch_quantize<8>(src, ld, nsplit, plane, keep, ldK, n, k, codes, S, rnorm, st); break;
-        case 4: launch_quantize<4>(src, ld, nsplit, plane, keep, ldK, n, k, codes, S, rnorm, st); break;
-        case 2: launch_quantize<2>(src, ld, nsplit, plane, keep, ldK, n, k, codes, S, rnorm, st); break;
-        default: launch_quantize<1>(src, ld, nsplit, plane, keep, ldK, n, k, codes, S, rnorm, st); break;
+        case 8: launch_quantize<8>(src, ld, nsplit, plane, keep, ldK, n, k, codes, S, rnorm, st, accum, ldA, other, ldO); break;
+        case 4: launch_quantize<4>(src, ld, nsplit, plane, keep, ldK, n, k, codes, S, rnorm, st, accum, ldA, other, ldO); break;
+        case 2: launch_quantize<2>(src, ld, nsplit, plane, keep, ldK, n, k, codes, S, rnorm, st, accum, ldA, other, ldO); break;
+        default: launch_quantize<1>(src, ld, nsplit, plane, keep, ldK, n, k, codes, S, rnorm, st, accum, ldA, other, ldO); break;
     }
     return launch_status();
 }

@@ -479,3 +479,65 @@ def test_mixed_precision_score_within_the_derived_tolerance(bits, N, M, k, C):
     assert np.abs(s.cpu().numpy().astype(np.float64) - ref_s).max() <= tol
     assert torch.equal(s, f.max(dim=1).values)
     assert torch.equal(s, Q.score_mixed(dev(tc), dev(tr), dv16, eta, k, bits))
+
+
+# ------------------------------------------------------------------- datastore build from gradient slices
+@pytest.mark.parametrize("bits", [8, 4, 2, 1])
+@pytest.mark.parametrize("n,k,slices,dtype", [(37, 576, [4096, 1024, 96, 8192], torch.bfloat16),
+                                               (64, 2048, [16384] * 3, torch.bfloat16),
+                                               (5, 64, [64], torch.float32),
+                                               (130, 1024, [2048, 0, 4128, 1024], torch.float32),
+                                               (3, 20480, [4096, 4096], torch.bfloat16)])
+def test_sliced_datastore_build_matches_the_accumulated_calls_and_the_oracle(n, k, slices, dtype, bits):
+    """A gradient fed slice by slice (Sec. 3.1; Eq.(1) then Eq.(4),(5)): the projection is within the projection bar of
+    the oracle's slice-by-slice accumulation, codes / S / rnorm are bit-identical to the oracle's from the same P and
+    to qless_project(accumulate) + qless_quantize over the same slices; also with alternate slices accumulated
+    separately (the two-stream use) and joined on the last call."""
+    _say("sliced build n=%d k=%d slices=%s %s bits=%d" % (n, k, slices, dtype, bits))
+    d = sum(slices)
+    G, _ = synth.gaussian_gradients(n, d, 7000 + n, dtype=dtype)
+    Gd = G.to(DEV)
+    offs = np.concatenate([[0], np.cumsum(slices)]).astype(np.int64)
+    # one accumulator
+    P = torch.full((n, k), float("nan"), dtype=torch.float32, device=DEV)
+    out = None
+    for i, ln in enumerate(slices):
+        out = Q.project_quantize_slice(Gd[:, offs[i]:offs[i + 1]], k, int(offs[i]), P, i == 0, i == len(slices) - 1,
+                                       bits=bits, seed=9)
+    codes, S, rn = out
+    ref = None
+    for i, ln in enumerate(slices):
+        ref = oracle.project(G[:, offs[i]:offs[i + 1]], k, seed=9, d_offset=int(offs[i]), P=ref)
+    assert _rel_l2(P.cpu().numpy(), ref).max() <= 1e-2
+    oc, oS, orn = oracle.quantize(P.cpu().numpy(), bits)
+    np.testing.assert_array_equal(codes.cpu().numpy(), oc)
+    np.testing.assert_array_equal(S.cpu().numpy(), oS)
+    np.testing.assert_array_equal(rn.cpu().numpy(), orn)
+    # the separate calls over the same slices: same bits
+    P2 = torch.empty(n, k, dtype=torch.float32, device=DEV)
+    for i, ln in enumerate(slices):
+        Q.project(Gd[:, offs[i]:offs[i + 1]], k, seed=9, d_offset=int(offs[i]), out=P2, accumulate=i > 0)
+    assert torch.equal(P2.view(torch.int32), P.view(torch.int32)) or torch.equal(P2, P)
+    c2, S2, r2 = Q.quantize(P2, bits)
+    assert torch.equal(c2, codes) and torch.equal(S2, S) and torch.equal(r2, rn)
+    # two accumulators (even / odd slices), joined on the last call
+    if len(slices) >= 2:
+        Pa = torch.empty(n, k, dtype=torch.float32, device=DEV)
+        Pb = torch.empty(n, k, dtype=torch.float32, device=DEV)
+        last = len(slices) - 1
+        seen = [False, False]
+        for i, ln in enumerate(slices):
+            if i == last:
+                continue
+            acc = Pa if i % 2 == 0 else Pb
+            Q.project_quantize_slice(Gd[:, offs[i]:offs[i + 1]], k, int(offs[i]), acc, not seen[i % 2], False, seed=9)
+            seen[i % 2] = True
+        mine, other = (Pa, Pb) if last % 2 == 0 else (Pb, Pa)
+        cj, Sj, rj = Q.project_quantize_slice(Gd[:, offs[last]:offs[last + 1]], k, int(offs[last]), mine,
+                                              not seen[last % 2], True, bits=bits, seed=9,
+                                              P_other=other if seen[1 - last % 2] else None)
+        assert _rel_l2(mine.cpu().numpy(), ref).max() <= 1e-2
+        ocj, oSj, ornj = oracle.quantize(mine.cpu().numpy(), bits)
+        np.testing.assert_array_equal(cj.cpu().numpy(), ocj)
+        np.testing.assert_array_equal(Sj.cpu().numpy(), oSj)
+        np.testing.assert_array_equal(rj.cpu().numpy(), ornj)

@@ -192,3 +192,21 @@ def test_score_mixed_argument_validation():
     need = L.qless_score_mixed_workspace(20000, 100, 1024, 4, 2)
     assert need >= 2 * 8192 * 1024 * 2
     assert L.qless_score_mixed_workspace(4, 2, 64, 3, 1) == 0
+
+
+def test_project_quantize_slice_argument_validation():
+    L = binding.lib()
+    one = ctypes.c_void_p(16)
+    f = L.qless_project_quantize_slice
+    a = lambda n=4, d=64, k=64, first=1, last=1, P=one, ldP=64, other=None, ldO=0, bits=8, codes=one, ws=one, wsb=1 << 30, off=0: (
+        one, 1, n, d, 64, off, k, 0, 0, first, last, P, ldP, other, ldO, bits, codes, one, one, ws, wsb, None)
+    assert f(*a(P=None)) == INVALID
+    assert f(*a(ldP=32)) == INVALID
+    assert f(*a(other=one, ldO=32)) == INVALID
+    assert f(*a(last=0, other=one, ldO=64)) == INVALID          # a second accumulator is joined on the last slice only
+    assert f(*a(codes=None)) == INVALID
+    assert f(*a(codes=ctypes.c_void_p(18))) == INVALID
+    assert f(*a(bits=5)) == UNSUPPORTED
+    assert f(*a(off=8)) == UNSUPPORTED
+    assert f(*a(ws=None, wsb=0)) == WORKSPACE
+    assert f(*a(n=0, P=None, codes=None, ws=None, wsb=0)) == OK
