@@ -287,6 +287,22 @@ typedef enum { QLESS_AGG_MAX = 0, QLESS_AGG_MEAN = 1 } qless_agg;
 qless_status qless_aggregate(const float *full, int64_t N, int32_t M, const int32_t *group_end, int T,
                              qless_agg mode, float *out, void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * qless_score and qless_aggregate in one call: out[z][t] = maximum or mean, as defined for
+ * qless_aggregate, of acc(z, z') of qless_score over the validation columns of group t -- the same bits
+ * as the two calls, without the N x M matrix in memory (with more than 64 validation vectors the
+ * aggregation is the epilogue of the scoring kernel; below that the matrix is small and passes through
+ * the workspace).  Arguments as for qless_score and qless_aggregate;
+ *   out   device, N x T fp32 row-major
+ *   ws    device workspace, 16-byte aligned, of at least qless_score_groups_workspace(N, M, k, bits, C) bytes
+ * ------------------------------------------------------------------------------------------- */
+size_t qless_score_groups_workspace(int64_t N, int32_t M, int32_t k, int bits, int C);
+qless_status qless_score_groups(const void *const *train_codes, const float *const *train_rnorm,
+                                const void *const *val_codes, const float *const *val_rnorm,
+                                const float *eta, int C, int64_t N, int32_t M, int32_t k, int bits,
+                                const int32_t *group_end, int T, qless_agg mode, float *out,
+                                void *ws, size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

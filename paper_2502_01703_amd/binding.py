@@ -48,6 +48,9 @@ EXPORTS = {
     "qless_topk": (_c.c_int, [_vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
     "qless_topk_noalloc": (_c.c_int, [_vp, _i64, _i64, _vp, _vp, _vp]),
     "qless_aggregate": (_c.c_int, [_vp, _i64, _i32, _vp, _c.c_int, _c.c_int, _vp, _vp]),
+    "qless_score_groups_workspace": (_sz, [_i64, _i32, _i32, _c.c_int, _c.c_int]),
+    "qless_score_groups": (_c.c_int, [_vp, _vp, _vp, _vp, _vp, _c.c_int, _i64, _i32, _i32, _c.c_int, _vp, _c.c_int,
+                                      _c.c_int, _vp, _vp, _sz, _vp]),
 }
 
 
@@ -348,4 +351,27 @@ def aggregate(full, group_end, mode=AGG_MAX, out=None):
         out = torch.empty(N, len(group_end), dtype=torch.float32, device=full.device)
     _check(lib().qless_aggregate(_vp(full.data_ptr()), N, M, _c.cast(ge, _vp), len(group_end), mode,
                                  _vp(out.data_ptr()), _stream()), "qless_aggregate")
+    return out
+
+
+def score_groups_workspace(N, M, k, bits, C):
+    return int(lib().qless_score_groups_workspace(N, M, k, bits, C))
+
+
+def score_groups(train_codes, train_rnorm, val_codes, val_rnorm, eta, k, bits, group_end, mode=AGG_MAX, out=None, ws=None):
+    """qless_score_groups: influence aggregated over groups of validation columns -> [N, T]."""
+    C = len(train_codes)
+    assert len(train_rnorm) == C and len(val_codes) == C and len(val_rnorm) == C and len(eta) == C
+    N, M = train_codes[0].shape[0], val_codes[0].shape[0]
+    dev = val_codes[0].device
+    T = len(group_end)
+    ge = (_c.c_int32 * T)(*[int(g) for g in group_end])
+    if out is None:
+        out = torch.empty(N, T, dtype=torch.float32, device=dev)
+    eta_arr = (_c.c_float * C)(*[float(e) for e in eta])
+    w = _ws(score_groups_workspace(N, M, k, bits, C), dev, ws)
+    _check(lib().qless_score_groups(_ptr_array(train_codes), _ptr_array(train_rnorm), _ptr_array(val_codes),
+                                    _ptr_array(val_rnorm), _c.cast(eta_arr, _vp), C, N, M, k, bits,
+                                    _c.cast(ge, _vp), T, mode, _vp(out.data_ptr()), _vp(w.data_ptr()), w.numel(),
+                                    _stream()), "qless_score_groups")
     return out

@@ -99,7 +99,13 @@ qless_status quantize_rows(const float *src, int64_t ld, int nsplit, size_t plan
                            hipStream_t st, const float *accum = nullptr, int64_t ldA = 0,
                            const float *other = nullptr, int64_t ldO = 0);
 
-// Gaussian table (bf16 bit patterns), built once on the host
+// Groups of consecutive validation columns: group t is [end[t-1], end[t]), end[-1] = 0.
+struct GroupEnds { int32_t end[QLESS_MAX_GROUPS]; };
+// misc.hip: out[z][t] = maximum (mean == 0) or left-to-right fp32 mean of full[z][group t], enqueued on st
+qless_status aggregate_rows(const float *full, int64_t N, int32_t M, const GroupEnds &ge, int T, int mean,
+                            float *out, hipStream_t st);
+
+// Gaussian table (bf16 bit patterns)
 const uint16_t *gaussian_table_bf16();
 
 }  // namespace qless

@@ -77,8 +77,6 @@ qless_status device_ready() {
     return QLESS_OK;
 }
 
-struct GroupEnds { int32_t end[QLESS_MAX_GROUPS]; };
-
 // one thread per (train example, group): the group's entries are visited in column order, so the
 // mean is the same sequence of fp32 additions for every launch shape
 __global__ void __launch_bounds__(256)
@@ -103,6 +101,15 @@ aggregate_kernel(const float *full, int64_t N, int32_t M, GroupEnds ge, int T, i
     }
 }
 
+qless_status aggregate_rows(const float *full, int64_t N, int32_t M, const GroupEnds &ge, int T, int mean,
+                            float *out, hipStream_t st) {
+    int64_t blocks = (N * (int64_t)T + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(aggregate_kernel, dim3((unsigned)blocks), dim3(256), 0, st, full, N, M, ge, T, mean, out);
+    return launch_status();
+}
+
 }  // namespace qless
 
 extern "C" qless_status qless_aggregate(const float *full, int64_t N, int32_t M, const int32_t *group_end, int T,
@@ -119,11 +126,7 @@ extern "C" qless_status qless_aggregate(const float *full, int64_t N, int32_t M,
     if (group_end[T - 1] != M) return QLESS_ERR_INVALID_ARG;
     if (N == 0) return QLESS_OK;
     if (!full || !out) return QLESS_ERR_INVALID_ARG;
-    int64_t blocks = (N * (int64_t)T + 255) / 256;
-    if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL(qless::aggregate_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, full, N, M, ge, T,
-                       mode == QLESS_AGG_MEAN ? 1 : 0, out);
-    return qless::launch_status();
+    return qless::aggregate_rows(full, N, M, ge, T, mode == QLESS_AGG_MEAN ? 1 : 0, out, (hipStream_t)stream);
 }
 
 extern "C" qless_status qless_init(void) { return qless::device_ready(); }

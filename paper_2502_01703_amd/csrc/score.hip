@@ -1036,9 +1036,16 @@ struct MfmaShape {
 // to the matrix core are eight bfloat16 values for v_mfma_f32_32x32x16_bf16 (same bytes, same
 // addresses as the int8 operands), the accumulator is fp32 and the epilogue is acc += eta * D:
 // the 16-bit LESS comparator (Eq.(2),(3)) on pre-normalised rows.
-template <int BITS, int WR, int WC, int WX, int NW, bool F16 = false, bool VH = false>
+// AGG: instead of score / full the kernel writes, per train row, the maximum or the left-to-right fp32
+// mean of acc over each group of consecutive validation columns (gout[N][T]).  One workgroup then takes a
+// train tile through all validation tiles in order; after each tile the sums go through LDS (the stage
+// ring is idle then) to one thread per train row, which walks the tile's columns in order and carries
+// the running value of the open group in a register.
+struct AggArgs { GroupEnds ge; int T, mean; float *gout; };
+
+template <int BITS, int WR, int WC, int WX, int NW, bool F16 = false, bool VH = false, bool AGG = false>
 __global__ void __launch_bounds__(64 * NW, (WR == 1 ? 4 : 2))
-score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
+score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles, AggArgs ag) {
     static_assert(!F16 || BITS == 8, "bfloat16 rows use the byte geometry of the 8-bit codes");
     using Sh = MfmaShape<BITS, WR, WC, WX, NW, VH>;
     constexpr int kMT = Sh::MT;
@@ -1053,8 +1060,9 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     const int64_t id = blockIdx.x;
     const int xcd = (int)(id & 7);
     const int64_t j = id >> 3;
-    const int vt = (int)(j % vtiles);
-    const int64_t tt = (j / vtiles) * 8 + xcd;
+    const int vt_first = AGG ? 0 : (int)(j % vtiles);
+    const int vt_end = AGG ? vtiles : vt_first + 1;
+    const int64_t tt = AGG ? id : (j / vtiles) * 8 + xcd;
     if (tt >= ttiles) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -1063,7 +1071,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
     const int wy = wave / WX, wx = wave % WX;
     const int trow = wy * 32 * WR, vcol = wx * 32 * WC;   // this wave's corner inside the tile
     const int64_t row0 = tt * kMT;
-    const int v0 = vt * VT;
+    int v0 = vt_first * VT;                             // advanced per validation tile (AGG)
     const int64_t cb = (int64_t)a.k * BITS / 8;
     const int nstages = (a.k + KE - 1) / KE;            // <= kp / KE: the expanded val rows cover every stage
     if (tid < kMT) s_rowmax[tid] = 0u;
@@ -1130,6 +1138,13 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
         else b_base[c] = TRAIN_BYTES + Rv * Sh::VROWB + (sw >> 1) * 32 + ((half ^ (sw & 1)) * 16);
     }
 
+    // AGG: thread t < kMT owns train row t of the tile: index and running value of its open group
+    int ag_group = 0;
+    float ag_run = 0.0f;
+    static_assert(!AGG || (!Sh::VPACKED && !VH), "group aggregation runs on the wide tiles");
+
+  for (int vt = vt_first; vt < vt_end; ++vt) {
+    v0 = vt * VT;
     float facc[WR][WC][16];
 #pragma unroll
     for (int b = 0; b < WR; ++b)
@@ -1403,6 +1418,39 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
                 }
             }
     }
+    if constexpr (AGG) {
+        // the tile's sums go to LDS as [kMT][VT + 1] floats (odd stride: a wavefront's rows fall in different
+        // banks); every copy of the tile has landed and every wavefront has read its last stage by now
+        constexpr int LD = VT + 1;
+        float *tile = (float *)smem;
+        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < WR; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int rloc = trow + 32 * b + 8 * (v >> 2) + 4 * half + (v & 3);
+#pragma unroll
+                for (int c = 0; c < WC; ++c) tile[rloc * LD + vcol + 32 * c + l32] = facc[b][c][v];
+            }
+        __syncthreads();
+        if (tid < kMT && row0 + tid < a.N) {
+            const float *trowp = tile + tid * LD;
+            const int ncol = a.M - v0 < VT ? a.M - v0 : VT;
+            for (int jc = 0; jc < ncol; ++jc) {
+                const int col = v0 + jc;
+                const int g0 = ag_group ? ag.ge.end[ag_group - 1] : 0, g1 = ag.ge.end[ag_group];
+                const float x = trowp[jc];
+                if (ag.mean) ag_run = __fadd_rn(col == g0 ? 0.0f : ag_run, x);
+                else ag_run = (col == g0 || x > ag_run) ? x : ag_run;
+                if (col == g1 - 1) {
+                    ag.gout[(row0 + tid) * ag.T + ag_group] = ag.mean ? __fdiv_rn(ag_run, (float)(g1 - g0)) : ag_run;
+                    ++ag_group;
+                }
+            }
+        }
+        __syncthreads();                             // the next tile's copies overwrite the buffer
+        continue;
+    }
     // tile epilogue: optional full matrix, row maxima over this val tile
 #pragma unroll
     for (int b = 0; b < WR; ++b)
@@ -1429,6 +1477,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles) {
         __syncthreads();
         if (tid < kMT && row0 + tid < a.N && s_rowmax[tid] != 0u) atomicMax(&w.smax[row0 + tid], s_rowmax[tid]);
     }
+  }
 }
 
 constexpr size_t kLdsPerCU = 160 * 1024;       // LDS of one compute unit
@@ -1443,12 +1492,12 @@ static int compute_units() {
 }
 
 struct MfmaPlan { int32_t vt, Mp, kp; size_t off_vw, off_vbias, off_smax, total; };
-static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int bits, int C) {
+static MfmaPlan mfma_plan(int64_t N, int32_t M, int32_t k, int bits, int C, bool wide128 = false) {
     MfmaPlan p{};
-    p.vt = M > 64 ? 128 : (M > 32 ? 64 : 32);
+    p.vt = (M > 64 || wide128) ? 128 : (M > 32 ? 64 : 32);
     // sign codes: 512 x 96 tiles (64 x 96 per wave) where 96-wide tiles pad the validation set less than
     // 128-wide ones (M = 285: 288 instead of 384 columns)
-    if (bits == 1 && M > 64 && (M + 95) / 96 * 96 < (M + 127) / 128 * 128) p.vt = 96;
+    if (!wide128 && bits == 1 && M > 64 && (M + 95) / 96 * 96 < (M + 127) / 128 * 128) p.vt = 96;
     p.Mp = (M + p.vt - 1) / p.vt * p.vt;
     const int ke = narrow_stage_elements(bits, p.vt);                 // MfmaShape::KE of the shape used
     p.kp = (k + ke - 1) / ke * ke;
@@ -1486,8 +1535,31 @@ static qless_status launch_mfma_shape(const ScoreArgs &a, const ScorePrep &w, in
     const int64_t grid = 8 * (int64_t)vtiles * ((ttiles + 7) / 8);
     if (grid > 0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
     hipLaunchKernelGGL((score_mfma_kernel<BITS, WR, WC, WX, NW, F16, VH>), dim3((unsigned)grid), dim3(64 * NW), lds, st, a, w,
-                       (int)ttiles, vtiles);
+                       (int)ttiles, vtiles, AggArgs{});
     return QLESS_OK;
+}
+
+// Wide tiles with the group aggregation in the epilogue: one workgroup per train tile.
+template <int BITS>
+static qless_status launch_mfma_groups(const ScoreArgs &a, void *ws, const AggArgs &ag, hipStream_t st) {
+    using Sh = MfmaShape<BITS, 2, 2, 2, 8, false>;
+    const MfmaPlan p = mfma_plan(a.N, a.M, a.k, BITS, a.C, true);               // 128-wide validation tiles
+    ScorePrep w{};
+    unsigned char *base = (unsigned char *)ws;
+    w.vexp = (int8_t *)base; w.vw = (float *)(base + p.off_vw); w.vbias = (int32_t *)(base + p.off_vbias);
+    w.smax = (unsigned int *)(base + p.off_smax); w.Mp = p.Mp; w.kp = p.kp;
+    w.vrow = BITS <= 2 ? p.kp / 2 : p.kp;
+    hipLaunchKernelGGL((score_prepare_kernel<BITS, false>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
+    constexpr int kMaxDynamic = (int)kLdsPerCU - 4 * Sh::MT;
+    QLESS_LDS_KERNEL((score_mfma_kernel<BITS, 2, 2, 2, 8, false, false, true>), kMaxDynamic);
+    size_t lds = (size_t)Sh::NBUF * Sh::BUF;
+    const size_t tile = (size_t)Sh::MT * (Sh::VT + 1) * sizeof(float);
+    if (tile > lds) lds = tile;
+    if (lds > (size_t)kMaxDynamic) return QLESS_ERR_DEVICE;
+    const int64_t ttiles = (a.N + Sh::MT - 1) / Sh::MT;
+    hipLaunchKernelGGL((score_mfma_kernel<BITS, 2, 2, 2, 8, false, false, true>), dim3((unsigned)ttiles), dim3(64 * 8), lds, st,
+                       a, w, (int)ttiles, p.Mp / Sh::VT, ag);
+    return launch_status();
 }
 
 // Few validation vectors: every workgroup streams its train rows at the same pace, so the launch
@@ -1881,6 +1953,68 @@ extern "C" qless_status qless_score(const void *const *train_codes, const float 
         else launch_popcount<2, 8, 1, 32, 8>(a, st);
     }
     return launch_status();
+}
+
+// Influence aggregated over groups of validation columns without the N x M matrix in memory.
+static bool groups_fused(int32_t M, int32_t k, int bits) { return M > 64 && (bits >= 4 || k % 128 == 0); }
+
+extern "C" size_t qless_score_groups_workspace(int64_t N, int32_t M, int32_t k, int bits, int C) {
+    if (N < 0 || M < 1 || k <= 0 || C < 1 || !valid_bits(bits)) return 0;
+    if (groups_fused(M, k, bits)) return mfma_plan(N, M, k, bits, C, true).total;
+    // few validation vectors (or bit planes that are not whole 16-byte chunks): the matrix is small; it is
+    // written to the workspace by the ordinary paths and aggregated from there
+    size_t full = ((size_t)N * (size_t)M * sizeof(float) + 255) & ~(size_t)255;
+    return full + qless_score_workspace(N, M, k, bits, C) + 16;
+}
+
+extern "C" qless_status qless_score_groups(const void *const *train_codes, const float *const *train_rnorm,
+                                           const void *const *val_codes, const float *const *val_rnorm,
+                                           const float *eta, int C, int64_t N, int32_t M, int32_t k, int bits,
+                                           const int32_t *group_end, int T, qless_agg mode, float *out,
+                                           void *ws, size_t ws_bytes, void *stream) {
+    if (!train_codes || !train_rnorm || !val_codes || !val_rnorm || !eta || !group_end) return QLESS_ERR_INVALID_ARG;
+    if (C < 1 || N < 0 || M < 1 || k <= 0 || T < 1) return QLESS_ERR_INVALID_ARG;
+    if (mode != QLESS_AGG_MAX && mode != QLESS_AGG_MEAN) return QLESS_ERR_UNSUPPORTED;
+    if (T > QLESS_MAX_GROUPS) return QLESS_ERR_UNSUPPORTED;
+    if (C > QLESS_MAX_CHECKPOINTS || !valid_bits(bits) || k % 64 != 0 || k > 65536) return QLESS_ERR_UNSUPPORTED;
+    if (N > (int64_t)0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
+    AggArgs ag{};
+    for (int t = 0; t < T; ++t) {
+        const int32_t g0 = t ? group_end[t - 1] : 0;
+        if (group_end[t] <= g0 || group_end[t] > M) return QLESS_ERR_INVALID_ARG;
+        ag.ge.end[t] = group_end[t];
+    }
+    if (group_end[T - 1] != M) return QLESS_ERR_INVALID_ARG;
+    if (N == 0) return QLESS_OK;
+    if (!out) return QLESS_ERR_INVALID_ARG;
+    const size_t need = qless_score_groups_workspace(N, M, k, bits, C);
+    if (!ws || ws_bytes < need || (uintptr_t)ws % 16) return QLESS_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    ag.T = T; ag.mean = mode == QLESS_AGG_MEAN ? 1 : 0; ag.gout = out;
+    if (!groups_fused(M, k, bits)) {
+        float *full = (float *)ws;
+        const size_t full_bytes = ((size_t)N * (size_t)M * sizeof(float) + 255) & ~(size_t)255;
+        const qless_status rc = qless_score(train_codes, train_rnorm, val_codes, val_rnorm, eta, C, N, M, k, bits,
+                                            nullptr, full, (unsigned char *)ws + full_bytes, ws_bytes - full_bytes, stream);
+        if (rc != QLESS_OK) return rc;
+        return aggregate_rows(full, N, M, ag.ge, T, ag.mean, out, st);
+    }
+    ScoreArgs a{};
+    for (int i = 0; i < C; ++i) {
+        if (!val_codes[i] || !val_rnorm[i] || !train_codes[i] || !train_rnorm[i]) return QLESS_ERR_INVALID_ARG;
+        if ((uintptr_t)val_codes[i] % 16 || (uintptr_t)train_codes[i] % 16) return QLESS_ERR_INVALID_ARG;
+        a.tc[i] = (const unsigned char *)train_codes[i]; a.vc[i] = (const unsigned char *)val_codes[i];
+        a.tr[i] = train_rnorm[i]; a.vr[i] = val_rnorm[i]; a.eta[i] = eta[i];
+    }
+    a.C = C; a.N = N; a.M = M; a.k = k; a.score = nullptr; a.full = nullptr;
+    const qless_status ready = device_ready();
+    if (ready != QLESS_OK) return ready;
+    switch (bits) {
+        case 8: return launch_mfma_groups<8>(a, ws, ag, st);
+        case 4: return launch_mfma_groups<4>(a, ws, ag, st);
+        case 2: return launch_mfma_groups<2>(a, ws, ag, st);
+        default: return launch_mfma_groups<1>(a, ws, ag, st);
+    }
 }
 
 // 16-bit LESS comparator: bfloat16 rows scored by the 8-bit kernel geometry on 2k bytes per row.

@@ -541,3 +541,23 @@ def test_sliced_datastore_build_matches_the_accumulated_calls_and_the_oracle(n, 
         np.testing.assert_array_equal(cj.cpu().numpy(), ocj)
         np.testing.assert_array_equal(Sj.cpu().numpy(), oSj)
         np.testing.assert_array_equal(rj.cpu().numpy(), ornj)
+
+
+# ------------------------------------------------------------------- scoring with the aggregation fused
+@pytest.mark.parametrize("mode", [Q.AGG_MAX, Q.AGG_MEAN])
+@pytest.mark.parametrize("bits", [8, 4, 2, 1])
+@pytest.mark.parametrize("N,M,k,C,ends", [(300, 130, 576, 3, [1, 2, 64, 65, 128, 129, 130]), (520, 257, 256, 2, [257]),
+                                          (1000, 300, 1024, 2, [100, 128, 256, 300]), (257, 600, 8192, 2, list(range(10, 601, 10))),
+                                          (700, 129, 192, 3, [64, 129]), (200, 40, 512, 2, [7, 40]), (150, 9, 128, 1, [9])])
+def test_score_groups_is_score_then_aggregate(bits, N, M, k, C, ends, mode):
+    """Eq.(6),(7) with the per-group maximum / mean in the scoring kernel's epilogue (M > 64 and whole 16-byte chunks),
+    or through a workspace matrix: bit-identical to the oracle's score followed by its aggregation."""
+    _say("score groups bits=%d N=%d M=%d k=%d C=%d T=%d mode=%d" % (bits, N, M, k, C, len(ends), mode))
+    tc, tr = _datastore(N, k, bits, C, 6000 + bits)
+    vc, vr = _datastore(M, k, bits, C, 7000 + bits)
+    eta = [1.0, 0.75, 0.5][:C]
+    _, ref_f = oracle.score(tc, tr, vc, vr, eta, k, bits, want_full=True)
+    ref = oracle.aggregate(ref_f, ends, mode)
+    dev = lambda arrs: [torch.from_numpy(a).to(DEV) for a in arrs]
+    got = Q.score_groups(dev(tc), dev(tr), dev(vc), dev(vr), eta, k, bits, ends, mode)
+    np.testing.assert_array_equal(got.cpu().numpy().view(np.uint32), ref.view(np.uint32))

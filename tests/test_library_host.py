@@ -210,3 +210,24 @@ def test_project_quantize_slice_argument_validation():
     assert f(*a(off=8)) == UNSUPPORTED
     assert f(*a(ws=None, wsb=0)) == WORKSPACE
     assert f(*a(n=0, P=None, codes=None, ws=None, wsb=0)) == OK
+
+
+def test_score_groups_argument_validation():
+    L = binding.lib()
+    one = ctypes.c_void_p(16)
+    ptrs = (ctypes.c_void_p * 1)(16)
+    eta = (ctypes.c_float * 1)(1.0)
+    ends = lambda *v: (ctypes.c_int32 * len(v))(*v)
+    f = L.qless_score_groups
+    a = lambda N=4, M=5, k=64, bits=8, ge=ends(2, 5), T=2, mode=0, out=one, ws=one, wsb=1 << 30: (
+        ptrs, ptrs, ptrs, ptrs, ctypes.cast(eta, ctypes.c_void_p), 1, N, M, k, bits, ge, T, mode, out, ws, wsb, None)
+    assert f(*a(ge=ends(2, 4))) == INVALID                 # last end != M
+    assert f(*a(ge=ends(3, 3, 5), T=3)) == INVALID         # empty group
+    assert f(*a(ge=None)) == INVALID
+    assert f(*a(mode=2)) == UNSUPPORTED
+    assert f(*a(bits=3)) == UNSUPPORTED
+    assert f(*a(out=None)) == INVALID
+    assert f(*a(ws=None)) == WORKSPACE
+    assert f(*a(wsb=8)) == WORKSPACE
+    assert f(*a(N=0, out=None, ws=None, wsb=0)) == OK
+    assert L.qless_score_groups_workspace(1000, 300, 1024, 1, 4) == L.qless_score_groups_workspace(1000, 300, 1024, 1, 4) > 0
