@@ -31,6 +31,190 @@ def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
+def _time_ms(torch, fn, reps=3, warm=1):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def _store(torch, Q, dev, rows, k, C, seed, sbits):
+    codes, rnorm = [], []
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    for c in range(C):
+        cc = torch.empty(rows, Q.code_bytes(k, sbits), dtype=torch.uint8, device=dev)
+        rr = torch.empty(rows, dtype=torch.float32, device=dev)
+        ss = torch.empty(rows, dtype=torch.float32, device=dev)
+        for r0 in range(0, rows, 16384):
+            r1 = min(rows, r0 + 16384)
+            Q.quantize(torch.randn(r1 - r0, k, generator=gen, device=dev), sbits, codes=cc[r0:r1], S=ss[r0:r1], rnorm=rr[r0:r1])
+        codes.append(cc)
+        rnorm.append(rr)
+    return codes, rnorm
+
+
+def extra_legs(torch, Q, synth, dev, G, eta, log):
+    """Legs beside the headline step: the other benchmark configurations at their own shapes and the variants of
+    the path (sliced datastore build on one and two streams, mixed precision, fused group aggregation)."""
+    out = {}
+    C = 4
+    # ---- sliced datastore build (Sec. 3.1): the 7B-class gradient as 128 per-matrix slices of 2^20 columns
+    n, d, k = G[0].shape[0], G[0].shape[1], 8192
+    if d >= 1 << 24:
+        nsl, sl = 128, d // 128
+        Pa = torch.empty(n, k, dtype=torch.float32, device=dev)
+        Pb = torch.empty(n, k, dtype=torch.float32, device=dev)
+        ws_a = torch.empty(max(Q.project_workspace(n, sl, k), 16), dtype=torch.uint8, device=dev)
+        ws_b = torch.empty_like(ws_a)
+        ws_w = torch.empty(max(Q.project_workspace(n, d, k), 16), dtype=torch.uint8, device=dev)
+        codes = torch.empty(n, Q.code_bytes(k, 1), dtype=torch.uint8, device=dev)
+        S = torch.empty(n, dtype=torch.float32, device=dev)
+        rn = torch.empty(n, dtype=torch.float32, device=dev)
+        g = G[0]
+
+        def whole():
+            Q.project_quantize_slice(g, k, 0, Pa, True, True, bits=1, codes=codes, S=S, rnorm=rn, ws=ws_w)
+
+        def one_stream():
+            for i in range(nsl):
+                Q.project_quantize_slice(g[:, i * sl:(i + 1) * sl], k, i * sl, Pa, i == 0, i == nsl - 1, bits=1,
+                                         codes=codes, S=S, rnorm=rn, ws=ws_a)
+
+        s2 = torch.cuda.Stream()
+
+        def two_streams():
+            main = torch.cuda.current_stream()
+            s2.wait_stream(main)
+            for i in range(nsl - 1):                          # even slices here, odd ones on the second stream
+                piece = g[:, i * sl:(i + 1) * sl]
+                if i % 2 == 0:
+                    Q.project_quantize_slice(piece, k, i * sl, Pa, i == 0, False, ws=ws_a)
+                else:
+                    with torch.cuda.stream(s2):
+                        Q.project_quantize_slice(piece, k, i * sl, Pb, i == 1, False, ws=ws_b)
+            i = nsl - 1                                       # odd: the last slice joins both sums on the second stream
+            s2.wait_stream(main)
+            with torch.cuda.stream(s2):
+                Q.project_quantize_slice(g[:, i * sl:], k, i * sl, Pb, False, True, bits=1, P_other=Pa,
+                                         codes=codes, S=S, rnorm=rn, ws=ws_b)
+            main.wait_stream(s2)
+
+        tw = _time_ms(torch, whole, reps=2)
+        t1 = _time_ms(torch, one_stream, reps=2)
+        t2 = _time_ms(torch, two_streams, reps=2)
+        out["sliced_build_1bit"] = {"workload": "one checkpoint's [64, 2^%d] bf16 batch -> k=8192, 1-bit, as %d slices of %d columns"
+                                                % (d.bit_length() - 1, nsl, sl),
+                                    "whole_ms": round(tw, 3), "slices_one_stream_ms": round(t1, 3),
+                                    "slices_two_streams_ms": round(t2, 3)}
+        log("sliced build: whole %.2f ms, %d slices on one stream %.2f ms, alternating on two streams %.2f ms" % (tw, nsl, t1, t2))
+        del Pa, Pb, ws_a, ws_b, ws_w
+    G.clear()
+    torch.cuda.empty_cache()
+
+    # ---- config 5: Gaussian projection d = 2^28 -> 16384, a batch of 128; 2-bit scoring 8192 x 256 x 4; top-409
+    n5, d5, k5 = 128, 1 << 28, 16384
+    g5, _ = synth.student_t_gradients(n5, d5, seed=5100, device=dev, dtype=torch.bfloat16)
+    ws5 = torch.empty(max(Q.project_workspace(n5, d5, k5), 16), dtype=torch.uint8, device=dev)
+    P5 = torch.empty(n5, k5, dtype=torch.float32, device=dev)
+    t5 = _time_ms(torch, lambda: Q.project(g5, k5, kind=Q.GAUSSIAN, seed=1, out=P5, ws=ws5), reps=2)
+    fl5 = 2.0 * n5 * d5 * k5
+    out["config5_project_gaussian"] = {"workload": "[128, 2^28] bf16 -> k=16384, Gaussian table entries", "ms": round(t5, 2),
+                                       "grads_per_s": round(n5 / (t5 * 1e-3), 2), "TFLOPs": round(fl5 / (t5 * 1e-3) / 1e12, 1),
+                                       "bf16_mfma_frac": round(fl5 / (t5 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+    log("config 5 Gaussian projection [128, 2^28] -> 16384: %.1f ms = %.0f TFLOP/s" % (t5, fl5 / (t5 * 1e-3) / 1e12))
+    del g5, ws5, P5
+    torch.cuda.empty_cache()
+    N5, M5 = 8192, 256
+    tc5, tr5 = _store(torch, Q, dev, N5, k5, C, 510, 2)
+    vc5, vr5 = _store(torch, Q, dev, M5, k5, C, 520, 2)
+    sc5 = torch.empty(N5, dtype=torch.float32, device=dev)
+    wss = torch.empty(max(Q.score_workspace(N5, M5, k5, 2, C), 16), dtype=torch.uint8, device=dev)
+    wst = torch.empty(max(Q.topk_workspace(N5, 409), 16), dtype=torch.uint8, device=dev)
+    ts = _time_ms(torch, lambda: Q.score(tc5, tr5, vc5, vr5, eta, k5, 2, score_out=sc5, ws=wss))
+    tt = _time_ms(torch, lambda: Q.topk(sc5, 409, ws=wst))
+    macs = float(N5) * M5 * C * k5
+    out["config5_score_2bit"] = {"workload": "N=8192 M=256 k=16384 C=4, 2-bit; top-409", "ms": round(ts, 4),
+                                 "pair_scores_per_s": round(N5 * M5 / (ts * 1e-3), 1),
+                                 "mfma_frac": round(macs / (ts * 1e-3) / 5.05e15, 4), "mfma_peak": "fp4 10.1 POP/s",
+                                 "hbm_frac": round(C * (N5 + M5) * (k5 // 4) / (ts * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                 "topk_409_ms": round(tt, 4)}
+    log("config 5 score 2-bit 8192x256x4 k=16384: %.3f ms; top-409 %.3f ms" % (ts, tt))
+    del tc5, tr5, vc5, vr5
+
+    # ---- config 2: N = 16384, M = 256, k = 2048, C = 4, all four widths; top-819
+    N2, M2, k2 = 16384, 256, 2048
+    for sb in (8, 4, 2, 1):
+        tc2, tr2 = _store(torch, Q, dev, N2, k2, C, 210 + sb, sb)
+        vc2, vr2 = _store(torch, Q, dev, M2, k2, C, 220 + sb, sb)
+        sc2 = torch.empty(N2, dtype=torch.float32, device=dev)
+        wss = torch.empty(max(Q.score_workspace(N2, M2, k2, sb, C), 16), dtype=torch.uint8, device=dev)
+        wst = torch.empty(max(Q.topk_workspace(N2, 819), 16), dtype=torch.uint8, device=dev)
+        ts = _time_ms(torch, lambda: Q.score(tc2, tr2, vc2, vr2, eta, k2, sb, score_out=sc2, ws=wss), reps=5)
+        tt = _time_ms(torch, lambda: Q.topk(sc2, 819, ws=wst), reps=5)
+        out["config2_score_%dbit" % sb] = {"workload": "N=16384 M=256 k=2048 C=4; top-819", "ms": round(ts, 4),
+                                           "pair_scores_per_s": round(N2 * M2 / (ts * 1e-3), 1),
+                                           "hbm_frac": round(C * (N2 + M2) * Q.code_bytes(k2, sb) / (ts * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                           "mfma_frac": round(float(N2) * M2 * C * k2 / (ts * 1e-3) / (5.05e15 if sb <= 2 else 2.5e15), 4),
+                                           "topk_819_ms": round(tt, 4)}
+        log("config 2 score %d-bit 16384x256x4 k=2048: %.3f ms; top-819 %.3f ms" % (sb, ts, tt))
+    n2, d2 = 2048, 1 << 20
+    g2, _ = synth.student_t_gradients(n2, d2, seed=2100, device=dev, dtype=torch.bfloat16)
+    ws2 = torch.empty(max(Q.project_workspace(n2, d2, k2), 16), dtype=torch.uint8, device=dev)
+    P2 = torch.empty(n2, k2, dtype=torch.float32, device=dev)
+    t2p = _time_ms(torch, lambda: Q.project(g2, k2, seed=11, out=P2, ws=ws2), reps=3)
+    fl2 = 2.0 * n2 * d2 * k2
+    out["config2_project"] = {"workload": "[2048, 2^20] bf16 -> k=2048, Rademacher", "ms": round(t2p, 3),
+                              "grads_per_s": round(n2 / (t2p * 1e-3), 1),
+                              "bf16_mfma_frac": round(fl2 / (t2p * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+    log("config 2 projection [2048, 2^20] -> 2048: %.2f ms = %.0f TFLOP/s" % (t2p, fl2 / (t2p * 1e-3) / 1e12))
+    del g2, ws2, P2
+
+    # ---- variants at the large-datastore shape: mixed precision and fused group aggregation (1-bit train codes)
+    N4, M4, k = 270000, 1024, 8192
+    tc4, tr4 = _store(torch, Q, dev, N4, k, C, 40, 1)
+    vc4, vr4 = _store(torch, Q, dev, M4, k, C, 50, 1)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(61)
+    v16 = []
+    for _ in range(C):
+        t16 = torch.empty(M4, k, dtype=torch.bfloat16, device=dev)
+        Q.normalize16(torch.randn(M4, k, generator=gen, device=dev), out=t16)
+        v16.append(t16)
+    wsm = torch.empty(max(Q.score_mixed_workspace(N4, M4, k, 1, C), 16), dtype=torch.uint8, device=dev)
+
+    def mixed():
+        Q.score_mixed(tc4, tr4, v16, eta, k, 1, ws=wsm)
+    tm = _time_ms(torch, mixed, reps=2)
+    out["score_mixed_1bit_M1024"] = {"workload": "N=270000 1-bit train codes x M=1024 bfloat16 validation rows, k=8192 C=4",
+                                     "ms": round(tm, 3), "pair_scores_per_s": round(N4 * M4 / (tm * 1e-3), 1),
+                                     "bf16_mfma_frac": round(2.0 * N4 * M4 * C * k / (tm * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+    log("mixed-precision score (1-bit train x bf16 val) 270000x1024x4: %.2f ms" % tm)
+    del wsm, v16
+    ends = [128 * (t + 1) for t in range(8)]
+    wsg = torch.empty(max(Q.score_groups_workspace(N4, M4, k, 1, C), 16), dtype=torch.uint8, device=dev)
+    og = torch.empty(N4, 8, dtype=torch.float32, device=dev)
+    tg = _time_ms(torch, lambda: Q.score_groups(tc4, tr4, vc4, vr4, eta, k, 1, ends, Q.AGG_MEAN, out=og, ws=wsg), reps=2)
+    full = torch.empty(N4, M4, dtype=torch.float32, device=dev)
+    wsf = torch.empty(max(Q.score_workspace(N4, M4, k, 1, C), 16), dtype=torch.uint8, device=dev)
+
+    def unfused():
+        Q.score(tc4, tr4, vc4, vr4, eta, k, 1, want_score=False, want_full=True, full_out=full, ws=wsf)
+        Q.aggregate(full, ends, Q.AGG_MEAN, out=og)
+    tu = _time_ms(torch, unfused, reps=2)
+    out["score_groups_1bit_M1024"] = {"workload": "N=270000 M=1024 k=8192 C=4 1-bit, mean over 8 groups of 128 validation vectors",
+                                      "fused_ms": round(tg, 3), "score_full_then_aggregate_ms": round(tu, 3),
+                                      "matrix_bytes_avoided": N4 * M4 * 4}
+    log("group means 270000x1024 -> 8 groups: fused %.2f ms, full matrix + aggregate %.2f ms" % (tg, tu))
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -167,7 +351,7 @@ def main():
             sc4 = torch.empty(N4, dtype=torch.float32, device=dev)
             ws4 = torch.empty(max(Q.topk_workspace(N4, 13500), 16), dtype=torch.uint8, device=dev)
             # M = 1024: matrix-core bound; M = 8: HBM bound; 9 / 81 / 285: few-shot validation sets (Sec. 4.1)
-            for M4 in ((1024, 285, 81, 64, 32, 16, 9, 8) if args.sweep else (1024, 64, 8)):
+            for M4 in ((1024, 285, 81, 64, 32, 16, 9, 8) if args.sweep else ((1024, 285, 81, 64, 8) if sb == 1 else (1024, 64, 8))):
                 vc4, vr4 = [v[:M4] for v in vc4f], [v[:M4] for v in vr4f]
                 wss = torch.empty(max(Q.score_workspace(N4, M4, k, sb, C), 16), dtype=torch.uint8, device=dev)
                 Q.score(tc4, tr4, vc4, vr4, eta, k, sb, score_out=sc4, ws=wss)
@@ -254,13 +438,18 @@ def main():
         log("quantize 1-bit 270000x8192: %.3f ms = %.0f GB/s" % (tq, qbytes / (tq * 1e-3) / 1e9))
         del Pq, cq
 
+    g0_host = G[0][0:1].cpu()
+    if not args.skip_scoring:
+        extra.update(extra_legs(torch, Q, synth, dev, G, eta, log))
+    del G
+
     # ----------------------------------------------------------------- CPU oracle on a bounded sample
     cpu = None
     if not args.skip_cpu:
         import numpy as np
         import oracle
         rows = list(range(0, k, 32))                       # 256 of the 8192 output coordinates
-        g0 = G[0][0:1].cpu()
+        g0 = g0_host
         t0 = time.perf_counter()
         oracle.project_rows(g0, rows, seed=0)
         t_proj = (time.perf_counter() - t0) * (k / len(rows))     # one gradient, all k coordinates
