@@ -60,11 +60,8 @@ def _store(torch, Q, dev, rows, k, C, seed, sbits):
     return codes, rnorm
 
 
-def extra_legs(torch, Q, synth, dev, G, eta, log):
-    """Legs beside the headline step: the other benchmark configurations at their own shapes and the variants of
-    the path (sliced datastore build on one and two streams, mixed precision, fused group aggregation)."""
-    out = {}
-    C = 4
+def leg_sliced(torch, Q, synth, dev, G, eta, log):
+    out, C = {}, 4
     # ---- sliced datastore build (Sec. 3.1): the 7B-class gradient as 128 per-matrix slices of 2^20 columns
     n, d, k = G[0].shape[0], G[0].shape[1], 8192
     if d >= 1 << 24:
@@ -115,9 +112,11 @@ def extra_legs(torch, Q, synth, dev, G, eta, log):
                                     "slices_two_streams_ms": round(t2, 3)}
         log("sliced build: whole %.2f ms, %d slices on one stream %.2f ms, alternating on two streams %.2f ms" % (tw, nsl, t1, t2))
         del Pa, Pb, ws_a, ws_b, ws_w
-    G.clear()
-    torch.cuda.empty_cache()
+    return out
 
+
+def leg_config5(torch, Q, synth, dev, eta, log):
+    out, C = {}, 4
     # ---- config 5: Gaussian projection d = 2^28 -> 16384, a batch of 128; 2-bit scoring 8192 x 256 x 4; top-409
     n5, d5, k5 = 128, 1 << 28, 16384
     g5, _ = synth.student_t_gradients(n5, d5, seed=5100, device=dev, dtype=torch.bfloat16)
@@ -148,6 +147,11 @@ def extra_legs(torch, Q, synth, dev, G, eta, log):
     log("config 5 score 2-bit 8192x256x4 k=16384: %.3f ms; top-409 %.3f ms" % (ts, tt))
     del tc5, tr5, vc5, vr5
 
+    return out
+
+
+def leg_config2(torch, Q, synth, dev, eta, log):
+    out, C = {}, 4
     # ---- config 2: N = 16384, M = 256, k = 2048, C = 4, all four widths; top-819
     N2, M2, k2 = 16384, 256, 2048
     for sb in (8, 4, 2, 1):
@@ -176,6 +180,11 @@ def extra_legs(torch, Q, synth, dev, G, eta, log):
     log("config 2 projection [2048, 2^20] -> 2048: %.2f ms = %.0f TFLOP/s" % (t2p, fl2 / (t2p * 1e-3) / 1e12))
     del g2, ws2, P2
 
+    return out
+
+
+def leg_variants(torch, Q, synth, dev, eta, log):
+    out, C = {}, 4
     # ---- variants at the large-datastore shape: mixed precision and fused group aggregation (1-bit train codes)
     N4, M4, k = 270000, 1024, 8192
     tc4, tr4 = _store(torch, Q, dev, N4, k, C, 40, 1)
@@ -215,6 +224,18 @@ def extra_legs(torch, Q, synth, dev, G, eta, log):
     return out
 
 
+def extra_legs(torch, Q, synth, dev, G, eta, log):
+    """Legs beside the headline step: the sliced datastore build on one and two streams, the other benchmark
+    configurations at their own shapes, and the variants of the path (mixed precision, fused group aggregation)."""
+    out = leg_sliced(torch, Q, synth, dev, G, eta, log)
+    G.clear()
+    torch.cuda.empty_cache()
+    out.update(leg_config5(torch, Q, synth, dev, eta, log))
+    out.update(leg_config2(torch, Q, synth, dev, eta, log))
+    out.update(leg_variants(torch, Q, synth, dev, eta, log))
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -226,6 +247,8 @@ def main():
     ap.add_argument("--skip-scoring", action="store_true", help="skip the scoring-only leg")
     ap.add_argument("--sweep", action="store_true",
                     help="scoring leg over all four code widths and the validation-set sizes 8 ... 1024")
+    ap.add_argument("--only", choices=["config5", "config2", "variants"], default=None,
+                    help="run one of the extra legs alone and print its figures (short runs for the profiler)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for profiler byte counters)")
     args = ap.parse_args()
@@ -242,6 +265,15 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     Q.lib()
+    if args.only:
+        leg = {"config5": leg_config5, "config2": leg_config2, "variants": leg_variants}[args.only]
+        if args.calibrate_copy:
+            src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+            src.clone()
+            torch.cuda.synchronize()
+            del src
+        print(json.dumps({"only": args.only, "legs": leg(torch, Q, synth, dev, [1.0, 0.75, 0.5, 0.25], log)}), flush=True)
+        return
 
     n, d, k, C, M, N, bits = 64, 1 << args.d_log2, 8192, 4, 512, 65536, args.bits
     k_sel = int(0.05 * N)
