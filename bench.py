@@ -388,7 +388,9 @@ def main():
                 wss = torch.empty(max(Q.score_workspace(N4, M4, k, sb, C), 16), dtype=torch.uint8, device=dev)
                 Q.score(tc4, tr4, vc4, vr4, eta, k, sb, score_out=sc4, ws=wss)
                 torch.cuda.synchronize()
-                reps = 3
+                # enough back-to-back launches that the host's launch latency before the first one (tens of
+                # microseconds with an idle GPU) does not weigh on kernels of a fraction of a millisecond
+                reps = 3 if M4 > 285 else 20
                 e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
                 e[0].record()
                 for _ in range(reps):

@@ -466,7 +466,7 @@ score_stream_mfma_kernel(ScoreArgs a, int64_t rb_each, int64_t rb_extra, int nb,
     const int cgp = lane & 7, crr = lane >> 3; // copy role: position and row inside a 1 KB copy
     const int l16 = lane & 15, kg = lane >> 4; // matrix role: row of the panel and chunk group
     const int wv_id = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // 8-row blocks are dealt out evenly: wavefront w takes rb_each blocks, the first rb_extra
+    // The train rows are dealt out evenly, to the row: wavefront w takes rb_each rows, the first rb_extra
     // wavefronts one more; w counts across workgroups first, so every compute unit gets its share
     // of the longer ranges
     const int64_t wave = (int64_t)wv_id * gridDim.x + blockIdx.x;
@@ -483,11 +483,23 @@ score_stream_mfma_kernel(ScoreArgs a, int64_t rb_each, int64_t rb_extra, int nb,
     // validation codes and weights eta * rnorm' of every checkpoint -> LDS (rows past M repeat the
     // last one; they are masked at the output)
     {
+        // four loads in flight per thread and round (the rounds are few: a round trip to L2 each)
         const int per_row = cb / 16, total = (c1 - c0) * MV * per_row;
-        for (int i = threadIdx.x; i < total; i += 64 * NW) {
-            const int c16 = i % per_row, rowi = i / per_row, j = rowi % MV, ci = c0 + rowi / MV;
-            const int jc = j < a.M ? j : a.M - 1;
-            *(uint4 *)(vlds + (size_t)rowi * vstride + c16 * 16) = *(const uint4 *)(a.vc[ci] + (int64_t)jc * cb + c16 * 16);
+        constexpr int kU = 4, kStep = 64 * NW;
+        for (int i0 = threadIdx.x; i0 < total; i0 += kU * kStep) {
+            uint4 val[kU];
+            int dst[kU];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                const int i = i0 + u * kStep < total ? i0 + u * kStep : total - 1;
+                const int c16 = i % per_row, rowi = i / per_row, j = rowi % MV, ci = c0 + rowi / MV;
+                const int jc = j < a.M ? j : a.M - 1;
+                val[u] = *(const uint4 *)(a.vc[ci] + (int64_t)jc * cb + c16 * 16);
+                dst[u] = rowi * vstride + c16 * 16;
+            }
+#pragma unroll
+            for (int u = 0; u < kU; ++u)
+                if (i0 + u * kStep < total) *(uint4 *)(vlds + dst[u]) = val[u];
         }
         float *wdst = (float *)(vlds + (size_t)cg * MV * vstride);
         for (int i = threadIdx.x; i < (c1 - c0) * MV; i += 64 * NW) {
@@ -496,11 +508,10 @@ score_stream_mfma_kernel(ScoreArgs a, int64_t rb_each, int64_t rb_extra, int nb,
         }
         __syncthreads();
     }
-    int64_t r_end = rb1 * 8;
-    if (r_end > a.N) r_end = a.N;                // only the last block of all can be partial
+    const int64_t r_end = rb1;
     const uint32_t ones = fp4_ones();
 
-    for (int64_t rp = rb0 * 8; rp < r_end; rp += PASS) {          // wave-uniform loops
+    for (int64_t rp = rb0; rp < r_end; rp += PASS) {              // wave-uniform loops
         const int rows = r_end - rp < PASS ? (int)(r_end - rp) : PASS;
         const int np = (rows + 15) / 16;
         const int ns = (np + PPS - 1) / PPS;     // ring slots per slice
@@ -1657,12 +1668,13 @@ static qless_status launch_stream_mfma(const ScoreArgs &a, int bits, const Strea
     QLESS_LDS_KERNEL((score_stream_mfma_kernel<1, 16, NW, 2>), 158 * 1024);
     QLESS_LDS_KERNEL((score_stream_mfma_kernel<2, 8, NW, 1>), 158 * 1024);
     QLESS_LDS_KERNEL((score_stream_mfma_kernel<2, 16, NW, 1>), 158 * 1024);
-    // at most one workgroup per compute unit; the 8-row blocks are dealt out evenly over all wavefronts
+    // at most one workgroup per compute unit; the rows are dealt out evenly over all wavefronts (a wavefront
+    // with work gets about 8 rows or more, what one of its copies covers)
     const int64_t total_rb = (a.N + 7) / 8;
     int64_t groups = compute_units();
     if (groups * NW > total_rb) groups = (total_rb + NW - 1) / NW;
     const int64_t waves = groups * NW;
-    const int64_t each = total_rb / waves, extra = total_rb % waves;
+    const int64_t each = a.N / waves, extra = a.N % waves;
     const dim3 grid((unsigned)groups), block(64 * NW);
     const unsigned ro = (unsigned)sp.val_bytes;
     for (int c0 = 0; c0 < a.C; c0 += sp.cg) {
