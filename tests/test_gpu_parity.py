@@ -51,7 +51,7 @@ def test_generator_words_match_oracle_and_golden_file():
 @pytest.mark.parametrize("kind", [Q.RADEMACHER, Q.GAUSSIAN])
 @pytest.mark.parametrize("n,d,k", [(70, 5000, 576), (3, 333, 64), (130, 4099, 1088), (66, 5120, 576),
                                    (5, 128, 64), (64, 16384, 2048), (128, 5120, 1088), (256, 4099, 576),
-                                   (200, 8192, 512)])
+                                   (200, 8192, 512), (256, 4096, 576), (500, 2048, 320), (513, 1024, 256)])
 def test_projection_parity_ragged(dtype, kind, n, d, k):
     _say("project n=%d d=%d k=%d kind=%d %s" % (n, d, k, kind, dtype))
     g = torch.Generator().manual_seed(n * 1000 + d)
