@@ -181,10 +181,12 @@ qless_status qless_project_quantize_slice(const void *G, qless_dtype dt, int64_t
  *   full       device, N x M fp32 row-major receiving acc, or NULL (at least one of the two)
  *   ws         device workspace, 16-byte aligned, of at least qless_score_workspace(N, M, k, bits, C)
  *              bytes (0 for the configurations that need none).  It holds the validation codes
- *              expanded for the tiled matrix-core path and the running row maxima; the paths that
- *              stream the train codes once (bit-plane codes, few validation vectors) leave it untouched,
- *              unless the checkpoints are scored in groups of launches (their validation rows do not
- *              all fit in LDS): then it carries N x 16 fp32 sums from one launch to the next.
+ *              expanded for the tiled matrix-core path and the running row maxima; for sign codes
+ *              against 17 .. 192 validation vectors a bit-permuted copy of the validation codes and
+ *              their per-row counts; the path that streams bit-plane codes against at most 16
+ *              validation vectors leaves it untouched, unless the checkpoints are scored in groups of
+ *              launches (their validation rows do not all fit in LDS): then it carries N x 16 fp32
+ *              sums from one launch to the next.
  * N == 0 is valid; M >= 1.  Whichever kernels a shape selects, the results are the same bits.  With
  * more than 64 validation vectors a call may consist of several launches that update score in
  * place: score and full are complete once the stream has run the whole call.

@@ -704,14 +704,43 @@ __device__ inline void wait_vmcnt_upto(int n) {    // n wave-uniform, 0 <= n; wa
     }
 }
 
+// Sign codes with the bits of both operands left where they are (no shifts).  A word's bit 4 n + 3 - jd
+// feeds dword jd, nibble n of the FP4 operand; as FP4 codes the four nibble bits weigh -, 2, 1, 1/2, so
+//   train word w:                 (w & 0x88888888) | 0x11111111 = +-1/2,   w & 0x44444444 = 2 s,   w & 0x22222222 = s,   w & 0x11111111 = s / 2
+//   validation word w'' (a copy   (w'' & 0x88888888) | 0x11111111 = +-1/2, w'' & 0x11111111 = s'/2, w'' & 0x22222222 = s', w'' & 0x44444444 = 2 s'
+//   with bits 0 and 2 of every nibble swapped by the pre-pass, so that dword jd holds the same codes):
+// with s = 1 for a negative code a = 1 - 2 s.  Dword 0 multiplies to a b / 4, the others to s s', and
+//   D = sum a b = 4 acc + 3 k / 4 - 2 St - 2 Sv,   St, Sv = the number of negative codes of a row outside dword 0
+// (a b = 1 - 2 s - 2 s' + 4 s s').  All partial sums are multiples of 1/4 below k: exact in fp32.  St is
+// counted here (two operations per word), Sv by the pre-pass: ten vector-ALU operations per pair of
+// words instead of fourteen.
+__device__ inline i32x8 fp4_train_in_place(uint32_t w, uint32_t halves) {
+    i32x8 r = {0, 0, 0, 0, 0, 0, 0, 0};
+    r[0] = (int)sign_bits_or(w, halves);
+    r[1] = (int)(w & 0x44444444u); r[2] = (int)(w & 0x22222222u); r[3] = (int)(w & 0x11111111u);
+    return r;
+}
+__device__ inline i32x8 fp4_val_in_place(uint32_t w, uint32_t halves) {
+    i32x8 r = {0, 0, 0, 0, 0, 0, 0, 0};
+    r[0] = (int)sign_bits_or(w, halves);
+    r[1] = (int)(w & 0x11111111u); r[2] = (int)(w & 0x22222222u); r[3] = (int)(w & 0x44444444u);
+    return r;
+}
+__device__ inline uint32_t fp4_halves() {
+    uint32_t h = 0x11111111u;                    // eight FP4 codes of +0.5
+    asm volatile("" : "+v"(h));                  // held in a vector register
+    return h;
+}
+
 // One ring slot (64-byte slice of NPAN panels of 32 train rows) against VB blocks of 32 validation
-// rows: 8 K steps.  sb: the slot; vwin: the validation window; vcol: chunk index of the slice's
-// first chunk inside the window; wb: bytes per window row.
+// rows: 8 K steps.  sb: the slot; vwin: the validation window (bit-permuted copy); vcol: chunk index of
+// the slice's first chunk inside the window; wb: bytes per window row; cnt: per panel, this lane's count
+// of negative train codes outside dword 0.
 template <int VB, int NPAN>
 __device__ inline void stream32_slice(const unsigned char *sb, const unsigned char *vwin, int vcol, int wb,
-                                      int l32, int half, uint32_t ones, f32x16 (&acc)[2][VB]) {
+                                      int l32, int half, uint32_t halves, f32x16 (&acc)[2][VB], uint32_t (&cnt)[2]) {
     // K step ks = 4 c + j uses dword j of chunk 2 c + half.  The operands of step ks + 1 are expanded
-    // between the matrix-core instructions of step ks (one instruction, then one operand's 7 vector
+    // between the matrix-core instructions of step ks (one instruction, then one operand's vector
     // ALU operations; scheduling barriers keep that order), so the matrix pipe is not left waiting
     // for a burst of expansions and the vector ALU is not blocked behind queued matrix instructions.
     uint4 tw[2][NPAN], vw[2][VB];
@@ -727,12 +756,17 @@ __device__ inline void stream32_slice(const unsigned char *sb, const unsigned ch
             vw[c][vb] = *(const uint4 *)(vwin + (size_t)(32 * vb + l32) * wb + (((vcol + chunk) ^ (l32 & 7)) << 4));
     };
     auto word = [](const uint4 &w, int j) { return j == 0 ? w.x : j == 1 ? w.y : j == 2 ? w.z : w.w; };
+    auto train = [&](int c, int p, int j) {
+        const uint32_t w = word(tw[c][p], j);
+        cnt[p] += (uint32_t)__popc(w & 0x77777777u);
+        return fp4_train_in_place(w, halves);
+    };
     load_words(0);
     i32x8 tv[NPAN], vv[VB];
 #pragma unroll
-    for (int vb = 0; vb < VB; ++vb) vv[vb] = fp4_codes<1>(word(vw[0][vb], 0), 0u, ones);
+    for (int vb = 0; vb < VB; ++vb) vv[vb] = fp4_val_in_place(word(vw[0][vb], 0), halves);
 #pragma unroll
-    for (int p = 0; p < NPAN; ++p) tv[p] = fp4_codes<1>(word(tw[0][p], 0), 0u, ones);
+    for (int p = 0; p < NPAN; ++p) tv[p] = train(0, p, 0);
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
         if (ks == 1) load_words(1);
@@ -746,13 +780,13 @@ __device__ inline void stream32_slice(const unsigned char *sb, const unsigned ch
                 acc[p][vb] = mfma_fp4(vv[vb], tv[p], acc[p][vb]);
                 const int slot = p * VB + vb;                   // this instruction's share of the expansions
                 if (ks < 7) {
-                    if (slot < VB) vvn[slot] = fp4_codes<1>(word(vw[cn][slot], jn), 0u, ones);
-                    else if (slot < VB + NPAN) tvn[slot - VB] = fp4_codes<1>(word(tw[cn][slot - VB], jn), 0u, ones);
+                    if (slot < VB) vvn[slot] = fp4_val_in_place(word(vw[cn][slot], jn), halves);
+                    else if (slot < VB + NPAN) tvn[slot - VB] = train(cn, slot - VB, jn);
                     if (NPAN * VB < NPAN + VB && slot == NPAN * VB - 1) {   // fewer instructions than operands
 #pragma unroll
                         for (int e = NPAN * VB; e < NPAN + VB; ++e) {
-                            if (e < VB) vvn[e] = fp4_codes<1>(word(vw[cn][e], jn), 0u, ones);
-                            else tvn[e - VB] = fp4_codes<1>(word(tw[cn][e - VB], jn), 0u, ones);
+                            if (e < VB) vvn[e] = fp4_val_in_place(word(vw[cn][e], jn), halves);
+                            else tvn[e - VB] = train(cn, e - VB, jn);
                         }
                     }
                 }
@@ -819,7 +853,7 @@ __device__ inline void stream32_slice_i8(const unsigned char *sb, const unsigned
 // npass: passes of the longest row range (workgroup-uniform)
 template <int BITS, int VB, int VR>
 __global__ void __launch_bounds__(64 * kStream32Waves, 2)
-score_stream_mfma32_kernel(ScoreArgs a, const int8_t *vexp, int32_t Mp, int32_t vrow, int32_t m0, int32_t mc,
+score_stream_mfma32_kernel(ScoreArgs a, const int8_t *vexp, const int32_t *vsum, int32_t Mp, int32_t vrow, int32_t m0, int32_t mc,
                            int64_t rb_each, int64_t rb_extra, int npass, int wb, int nb, unsigned ring_off) {
     static_assert(VR == 32 * VB || (VB == 1 && (VR == 8 || VR == 16)), "staged validation rows");
     constexpr int NW = kStream32Waves;
@@ -845,14 +879,16 @@ score_stream_mfma32_kernel(ScoreArgs a, const int8_t *vexp, int32_t Mp, int32_t 
     const int wbv = BITS == 4 ? 2 * wb : wb;    // validation bytes per window row
     const int wbytes = VR * wbv;                // one window buffer
     float *wlds = (float *)(vlds + (size_t)2 * wbytes);
+    int *blds = (int *)(wlds + a.C * 32 * VB);  // sign codes: 3 k / 4 - 2 Sv per validation column and checkpoint
     unsigned char *ring = vlds + ring_off + (size_t)wv_id * nb * SLOT;
     const unsigned ring_lds = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)ring);
     const unsigned vlds_lds = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)vlds);
-    const uint32_t ones = fp4_ones();
+    const uint32_t halves = fp4_halves();
 
     for (int i = threadIdx.x; i < a.C * 32 * VB; i += 64 * NW) {
         const int j = i % (32 * VB), ci = i / (32 * VB);
         wlds[i] = __fmul_rn(a.eta[ci], a.vr[ci][m0 + (j < mc ? j : mc - 1)]);
+        if (BITS == 1) blds[i] = 3 * (a.k / 4) - 2 * vsum[ci * a.M + m0 + (j < mc ? j : mc - 1)];
     }
     int64_t r_end = rb1 * 8;
     if (r_end > a.N) r_end = a.N;
@@ -898,7 +934,9 @@ score_stream_mfma32_kernel(ScoreArgs a, const int8_t *vexp, int32_t Mp, int32_t 
                 src = (const unsigned char *)vexp + ((size_t)ci * Mp + m0 + row) * (size_t)vrow + (size_t)win * wbv;
             } else {
                 const int jc = m0 + (row < mc ? row : mc - 1);
-                src = a.vc[ci] + (int64_t)jc * cb + (int64_t)win * wb;
+                // sign codes: the pre-pass's copy of the validation rows with bits 0 and 2 of every nibble swapped
+                src = (BITS == 1 ? (const unsigned char *)vexp + ((size_t)ci * a.M + jc) * (size_t)cb : a.vc[ci] + (int64_t)jc * cb) +
+                      (int64_t)win * wb;
             }
             global_to_lds16(src + ((pos ^ (row & 7)) << 4), buf + (unsigned)q * 1024u);
             ++v_cnt;
@@ -914,6 +952,7 @@ score_stream_mfma32_kernel(ScoreArgs a, const int8_t *vexp, int32_t Mp, int32_t 
         const int rows = ps < my_pass ? (r_end - rp < PASS ? (int)(r_end - rp) : PASS) : 0;   // wave-uniform
         const int last = rows - 1;
         typename AccType<BITS == 1>::type acc[NPMAX][VB];
+        uint32_t cnt[2] = {0u, 0u};              // sign codes: negative train codes outside dword 0, this lane's half of K
         float facc[NPMAX][VB][16];
 #pragma unroll
         for (int p = 0; p < NPMAX; ++p)
@@ -939,8 +978,8 @@ score_stream_mfma32_kernel(ScoreArgs a, const int8_t *vexp, int32_t Mp, int32_t 
                         if (f_it < S) fetch();
                         const unsigned char *sb = ring + (size_t)pos * SLOT;
                         if constexpr (BITS == 1) {
-                            if (rows > 32) stream32_slice<VB, 2>(sb, vwin, 4 * s4, wb, l32, half, ones, acc);
-                            else stream32_slice<VB, 1>(sb, vwin, 4 * s4, wb, l32, half, ones, acc);
+                            if (rows > 32) stream32_slice<VB, 2>(sb, vwin, 4 * s4, wb, l32, half, halves, acc, cnt);
+                            else stream32_slice<VB, 1>(sb, vwin, 4 * s4, wb, l32, half, halves, acc, cnt);
                         } else {
                             if (NPMAX == 3 && rows > 64) stream32_slice_i8<BITS, VB, VR, NPMAX, NPMAX>(sb, vwin, s4, wbv, l32, half, acc);
                             else if (rows > 32) stream32_slice_i8<BITS, VB, VR, 2, NPMAX>(sb, vwin, s4, wbv, l32, half, acc);
@@ -958,18 +997,24 @@ score_stream_mfma32_kernel(ScoreArgs a, const int8_t *vexp, int32_t Mp, int32_t 
                 for (int p = 0; p < NPMAX; ++p) {
                     if (32 * p >= rows) continue;                            // wave-uniform
                     const float rt = a.tr[ci][rp + (32 * p + l32 < rows ? 32 * p + l32 : last)];
+                    // sign codes: St of train row l32 = the counts of the two lanes that share the row
+                    int st2 = 0;
+                    if (BITS == 1) { const uint32_t c = cnt[p < 2 ? p : 0]; st2 = 2 * (int)(c + (uint32_t)__shfl_xor((int)c, 32)); }
 #pragma unroll
                     for (int vb = 0; vb < VB; ++vb)
 #pragma unroll
                         for (int v = 0; v < 16; ++v) {
-                            const float wv = wlds[ci * 32 * VB + 32 * vb + 8 * (v >> 2) + 4 * half + (v & 3)];
-                            // 1-bit: acc holds the integer D exactly in fp32; 4-bit: 16 D (train codes scaled)
-                            const float D = BITS == 1 ? (float)acc[p][vb][v] : (float)(BITS == 4 ? ((int)acc[p][vb][v] >> 4) : (int)acc[p][vb][v]);
+                            const int col = 32 * vb + 8 * (v >> 2) + 4 * half + (v & 3);
+                            const float wv = wlds[ci * 32 * VB + col];
+                            // 1-bit: 4 acc + 3 k / 4 - 2 Sv - 2 St (acc is a multiple of 1/4, exact); 4-bit: acc = 16 D (train codes scaled)
+                            const float D = BITS == 1 ? (float)((int)((float)acc[p][vb][v] * 4.0f) + blds[ci * 32 * VB + col] - st2)
+                                          : (float)(BITS == 4 ? ((int)acc[p][vb][v] >> 4) : (int)acc[p][vb][v]);
                             const float t = __fmul_rn(__fmul_rn(D, rt), wv);
                             facc[p][vb][v] = __fadd_rn(facc[p][vb][v], t);
                             acc[p][vb][v] = 0;
                         }
                 }
+                cnt[0] = 0u; cnt[1] = 0u;
             }
         }
         if (rows > 0) {
@@ -1703,7 +1748,7 @@ static Stream32Plan stream_mfma32_plan(int bits, int vb, int vr, int32_t k, int 
         for (int wb = 2048; wb >= 128; wb >>= 1) {
             if (cb % wb) continue;
             const int wbv = bits == 4 ? 2 * wb : wb;
-            const size_t val = (((size_t)2 * vr * wbv + (size_t)C * 32 * vb * 4) + 1023) & ~(size_t)1023;
+            const size_t val = (((size_t)2 * vr * wbv + (size_t)C * 32 * vb * (bits == 1 ? 8 : 4)) + 1023) & ~(size_t)1023;
             if (val + (size_t)kStream32Waves * want * slot > kLdsPerCU) continue;
             best.wb = wb; best.nb = want; best.val_bytes = val;
             best.lds = val + (size_t)kStream32Waves * want * slot;
@@ -1727,17 +1772,50 @@ static qless_status launch_stream32_shape(const ScoreArgs &a, const ScorePrep &w
     const int npass = (int)(((each + (extra > 0 ? 1 : 0)) * 8 + kPass - 1) / kPass);
     const Stream32Plan sp = stream_mfma32_plan(BITS, VB, VR, a.k, a.C);
     hipLaunchKernelGGL((score_stream_mfma32_kernel<BITS, VB, VR>), dim3((unsigned)groups), dim3(64 * NW), sp.lds, st, a,
-                       (const int8_t *)w.vexp, w.Mp, w.vrow, m0, mc, each, extra, npass, sp.wb, sp.nb, (unsigned)sp.val_bytes);
+                       (const int8_t *)w.vexp, (const int32_t *)w.vbias, w.Mp, w.vrow, m0, mc, each, extra, npass, sp.wb, sp.nb,
+                       (unsigned)sp.val_bytes);
     return QLESS_OK;
 }
 
-// 1-bit codes: one launch per chunk of 64 validation vectors
-static qless_status launch_stream_mfma32(const ScoreArgs &a, hipStream_t st) {
-    const ScorePrep none{};
+// Pre-pass of the sign codes' streaming path: a copy of the validation rows with bits 0 and 2 of every
+// nibble swapped, and per row the number of negative codes outside bit 3 of the nibbles (Sv).  One
+// workgroup per (validation row, checkpoint); k is a multiple of 512 here.
+__global__ void __launch_bounds__(256)
+score_permute_kernel(ScoreArgs a, uint32_t *vperm, int32_t *vsum) {
+    __shared__ int total;
+    const int row = blockIdx.x, ci = blockIdx.y, words = a.k / 32;
+    const uint32_t *src = (const uint32_t *)(a.vc[ci] + (int64_t)row * (a.k / 8));
+    uint32_t *dst = vperm + ((size_t)ci * a.M + row) * (size_t)words;
+    if (threadIdx.x == 0) total = 0;
+    __syncthreads();
+    int mine = 0;
+    for (int t = threadIdx.x; t < words; t += 256) {
+        const uint32_t w = src[t];
+        dst[t] = (w & 0xAAAAAAAAu) | ((w & 0x11111111u) << 2) | ((w & 0x44444444u) >> 2);
+        mine += __popc(w & 0x77777777u);
+    }
+    if (mine) atomicAdd(&total, mine);
+    __syncthreads();
+    if (threadIdx.x == 0) vsum[ci * a.M + row] = total;
+}
+struct PermPlan { size_t off_sum, total; };
+static PermPlan perm_plan(int32_t M, int32_t k, int C) {
+    PermPlan p{};
+    p.off_sum = ((size_t)C * M * (size_t)(k / 8) + 255) & ~(size_t)255;
+    p.total = p.off_sum + (((size_t)C * M * 4 + 255) & ~(size_t)255);
+    return p;
+}
+
+// 1-bit codes: the pre-pass, then one launch per chunk of 64 validation vectors
+static qless_status launch_stream_mfma32(const ScoreArgs &a, void *ws, hipStream_t st) {
+    const PermPlan pp = perm_plan(a.M, a.k, a.C);
+    ScorePrep w{};
+    w.vexp = (int8_t *)ws; w.vbias = (int32_t *)((unsigned char *)ws + pp.off_sum);
+    hipLaunchKernelGGL(score_permute_kernel, dim3((unsigned)a.M, (unsigned)a.C), dim3(256), 0, st, a, (uint32_t *)w.vexp, w.vbias);
     for (int32_t m0 = 0; m0 < a.M; m0 += kStream32Val) {
         const int32_t mc = a.M - m0 < kStream32Val ? a.M - m0 : kStream32Val;
-        const qless_status rc = mc > 32 ? launch_stream32_shape<1, 2, 64>(a, none, m0, mc, st)
-                                        : launch_stream32_shape<1, 1, 32>(a, none, m0, mc, st);
+        const qless_status rc = mc > 32 ? launch_stream32_shape<1, 2, 64>(a, w, m0, mc, st)
+                                        : launch_stream32_shape<1, 1, 32>(a, w, m0, mc, st);
         if (rc != QLESS_OK) return rc;
     }
     return launch_status();
@@ -1905,6 +1983,10 @@ extern "C" size_t qless_score_workspace(int64_t N, int32_t M, int32_t k, int bit
     size_t need = 0;
     if (bits <= 2 && M <= kStreamMfmaVal && k % 128 == 0)      // checkpoint groups hand their sums on through the workspace
         need = stream_mfma_partial_bytes(stream_mfma_plan(M, k, bits, C), N, C);
+    if (bits == 1 && M <= kStream32MaxVal && k % 512 == 0 && stream_mfma32_plan(1, 2, 64, k, C).nb >= 2) {
+        const size_t perm = perm_plan(M, k, C).total;           // the streaming path's copy of the validation rows
+        if (perm > need) need = perm;
+    }
     if (!use_mfma_path(bits, M, k)) return need;
     const size_t tiles = mfma_plan(N, M, k, bits, C).total;
     return tiles > need ? tiles : need;
@@ -1940,8 +2022,10 @@ extern "C" qless_status qless_score(const void *const *train_codes, const float 
             return launch_stream_mfma(a, bits, sp, (float *)ws, st);
         }
     }
-    if (bits == 1 && M <= kStream32MaxVal && k % 512 == 0 && stream_mfma32_plan(1, 2, 64, k, C).nb >= 2)
-        return launch_stream_mfma32(a, st);
+    if (bits == 1 && M <= kStream32MaxVal && k % 512 == 0 && stream_mfma32_plan(1, 2, 64, k, C).nb >= 2) {
+        if (!ws || ws_bytes < perm_plan(M, k, C).total || (uintptr_t)ws % 16) return QLESS_ERR_WORKSPACE;
+        return launch_stream_mfma32(a, ws, st);
+    }
     if (use_mfma_path(bits, M, k)) {
         const size_t need = mfma_plan(N, M, k, bits, C).total;
         if (!ws || ws_bytes < need) return QLESS_ERR_WORKSPACE;
