@@ -305,7 +305,11 @@ score_prepare_kernel(ScoreArgs a, ScorePrep w) {
                     if (BITS == 2) {
                         nz = (src[m >> 3] >> (m & 7)) & 1u;
                         neg = (src[a.k / 8 + (m >> 3)] >> (m & 7)) & 1u;
-                        byte |= ((nz << 1) | (neg << 3)) << (4 * e);
+                        // the train side leaves its "non-zero" bit of dwords 1, 2, 3 in place (FP4 2, 1, 1/2):
+                        // the validation magnitudes are 1/2, 1, 2 there, so that every product is a b
+                        const int jd = (p >> 3) & 3;
+                        const unsigned mag = jd == 1 ? 0x1u : (jd == 3 ? 0x4u : 0x2u);
+                        byte |= (nz ? (mag | (neg << 3)) : 0u) << (4 * e);
                     } else {
                         neg = (src[m >> 3] >> (m & 7)) & 1u;
                         const int jd = (p >> 3) & 3;
@@ -427,6 +431,26 @@ __device__ inline i32x8 fp4_codes(uint32_t sg, uint32_t nz, uint32_t ones) {
         const uint32_t mag = BITS == 1 ? ones : ((j >= 2 ? nz << (j - 2) : nz >> (2 - j)) & 0x22222222u);
         r[j] = (int)sign_bits_or(sg << j, mag);
     }
+    return r;
+}
+
+// The ternary codes of the streaming kernel: the train side leaves the "non-zero" bit of dwords 1 .. 3 where
+// it is (FP4 magnitudes 2, 1, 1/2; 12 operations per 32 codes instead of 14), the validation side takes
+// the magnitudes 1/2, 1, 2 there, so that every product is the product of the codes.
+__device__ inline i32x8 fp4_codes2_train(uint32_t sg, uint32_t nz) {
+    i32x8 r = {0, 0, 0, 0, 0, 0, 0, 0};
+    r[0] = (int)sign_bits_or(sg, (nz >> 2) & 0x22222222u);
+    r[1] = (int)sign_bits_or(sg << 1, nz & 0x44444444u);
+    r[2] = (int)sign_bits_or(sg << 2, nz & 0x22222222u);
+    r[3] = (int)sign_bits_or(sg << 3, nz & 0x11111111u);
+    return r;
+}
+__device__ inline i32x8 fp4_codes2_val(uint32_t sg, uint32_t nz) {
+    i32x8 r = {0, 0, 0, 0, 0, 0, 0, 0};
+    r[0] = (int)sign_bits_or(sg, (nz >> 2) & 0x22222222u);
+    r[1] = (int)sign_bits_or(sg << 1, (nz >> 2) & 0x11111111u);
+    r[2] = (int)sign_bits_or(sg << 2, nz & 0x22222222u);
+    r[3] = (int)sign_bits_or(sg << 3, (nz << 2) & 0x44444444u);
     return r;
 }
 
@@ -569,10 +593,10 @@ score_stream_mfma_kernel(ScoreArgs a, int64_t rb_each, int64_t rb_extra, int nb,
                         const int offc = inside ? off : 0;
                         const uint4 sg = *(const uint4 *)(vrow + (NPL - 1) * plane + offc);
                         const uint4 nz = BITS == 2 ? *(const uint4 *)(vrow + offc) : sg;
-                        vf[4 * c2 + 0] = fp4_codes<BITS>(sg.x, nz.x, ones);
-                        vf[4 * c2 + 1] = fp4_codes<BITS>(sg.y, nz.y, ones);
-                        vf[4 * c2 + 2] = fp4_codes<BITS>(sg.z, nz.z, ones);
-                        vf[4 * c2 + 3] = fp4_codes<BITS>(sg.w, nz.w, ones);
+                        vf[4 * c2 + 0] = BITS == 2 ? fp4_codes2_val(sg.x, nz.x) : fp4_codes<BITS>(sg.x, nz.x, ones);
+                        vf[4 * c2 + 1] = BITS == 2 ? fp4_codes2_val(sg.y, nz.y) : fp4_codes<BITS>(sg.y, nz.y, ones);
+                        vf[4 * c2 + 2] = BITS == 2 ? fp4_codes2_val(sg.z, nz.z) : fp4_codes<BITS>(sg.z, nz.z, ones);
+                        vf[4 * c2 + 3] = BITS == 2 ? fp4_codes2_val(sg.w, nz.w) : fp4_codes<BITS>(sg.w, nz.w, ones);
                         if (sl * 128 + 128 > plane) {                        // wave-uniform: last, partial slice
                             const int keep = inside ? -1 : 0;
 #pragma unroll
@@ -611,7 +635,8 @@ score_stream_mfma_kernel(ScoreArgs a, int64_t rb_each, int64_t rb_extra, int nb,
                                     const uint32_t sw = e == 0 ? sg.x : e == 1 ? sg.y : e == 2 ? sg.z : sg.w;
                                     const uint32_t nw = e == 0 ? nz.x : e == 1 ? nz.y : e == 2 ? nz.z : nz.w;
                                     acc[g * PPS + h] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                                        vf[4 * c2 + e], fp4_codes<BITS>(sw, nw, ones), acc[g * PPS + h], 4, 4, 0, 127, 0, 127);
+                                        vf[4 * c2 + e], BITS == 2 ? fp4_codes2_train(sw, nw) : fp4_codes<BITS>(sw, nw, ones),
+                                        acc[g * PPS + h], 4, 4, 0, 127, 0, 127);
                                 }
                         ++it;
                         if (++pos == nb) pos = 0;
@@ -1333,7 +1358,7 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles, AggArgs ag) 
                 }
             } else if constexpr (BITS == 2) {
                 // ternary codes as FP4 {-1.0, 0, +1.0}: nibble bit 3 <- "negative" plane, bit 1 <- "non-zero"
-                // plane (0xA, 0x0, 0x2); 16-byte reads of both planes per four K steps, dword jd of the
+                // plane; 16-byte reads of both planes per four K steps, dword jd of the
                 // expansion takes bits 4 n + 3 - jd of the two plane words
 #pragma unroll
                 for (int q = 0; q < KE / 256; ++q) {
@@ -1350,11 +1375,12 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles, AggArgs ag) 
 #pragma unroll
                         for (int b = 0; b < WR; ++b) {
                             const unsigned int wn = (unsigned int)wnq[b][j], wg = (unsigned int)wgq[b][j];
-#pragma unroll
-                            for (int jd = 0; jd < 4; ++jd) {
-                                const unsigned int zs = jd >= 2 ? wn << (jd - 2) : wn >> (2 - jd);
-                                af[b][jd] = (int)sign_bits_or(wg << jd, zs & 0x22222222u);
-                            }
+                            // dword 0: magnitude 1.0 from the shifted plane; dwords 1 .. 3: the plane bit where it
+                            // is (2, 1, 1/2; the pre-pass scaled the validation codes to match): 12 operations
+                            af[b][0] = (int)sign_bits_or(wg, (wn >> 2) & 0x22222222u);
+                            af[b][1] = (int)sign_bits_or(wg << 1, wn & 0x44444444u);
+                            af[b][2] = (int)sign_bits_or(wg << 2, wn & 0x22222222u);
+                            af[b][3] = (int)sign_bits_or(wg << 3, wn & 0x11111111u);
 #pragma unroll
                             for (int jd = 4; jd < 8; ++jd) af[b][jd] = 0;
                         }
