@@ -1288,12 +1288,23 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles, AggArgs ag) 
                 // validation rows follow the same order and are zero past the end of the vectors.
                 // The validation fragments of K step ks + 1 and the train words of the next four steps are
                 // requested before the matrix instructions of step ks (scheduling barriers keep that
-                // order), so a wave waits for LDS once per stage instead of once per step.
+                // order), so a wave waits for LDS once per stage instead of once per step; the train
+                // fragments of step ks + 1 are expanded between the matrix instructions of step ks, each
+                // instruction followed by its share of the expansions (scheduling groups).
                 i32x4 wq[KE / 256][WR], bq[WC], bn[WC];
 #pragma unroll
                 for (int b = 0; b < WR; ++b) wq[0][b] = *(const i32x4 *)(sb + a_base[b]);
 #pragma unroll
                 for (int c = 0; c < WC; ++c) bq[c] = *(const i32x4 *)(sb + b_base[c]);
+                auto expand = [&](unsigned int wd) {
+                    i32x8 r = {0, 0, 0, 0, 0, 0, 0, 0};
+                    r[0] = (int)sign_bits_or(wd, ones); r[1] = (int)(wd & 0x44444444u);
+                    r[2] = (int)(wd & 0x22222222u); r[3] = (int)(wd & 0x11111111u);
+                    return r;
+                };
+                i32x8 afc[WR], afn[WR];
+#pragma unroll
+                for (int b = 0; b < WR; ++b) afc[b] = expand((unsigned int)wq[0][b][0]);
 #pragma unroll
                 for (int ks = 0; ks < KE / 64; ++ks) {
                     const int q = ks >> 2, j = ks & 3;
@@ -1306,24 +1317,27 @@ score_mfma_kernel(ScoreArgs a, ScorePrep w, int ttiles, int vtiles, AggArgs ag) 
                         for (int b = 0; b < WR; ++b) wq[q + 1][b] = *(const i32x4 *)(sb + (a_base[b] ^ ((q + 1) << 5)));
                     }
                     __builtin_amdgcn_sched_barrier(0);
-                    i32x8 af[WR], bf[WC];
+                    i32x8 bf[WC];
 #pragma unroll
                     for (int c = 0; c < WC; ++c) bf[c] = i32x8{bq[c][0], bq[c][1], bq[c][2], bq[c][3], 0, 0, 0, 0};
 #pragma unroll
-                    for (int b = 0; b < WR; ++b) {
-                        const unsigned int wd = (unsigned int)wq[q][b][j];
-                        af[b][0] = (int)sign_bits_or(wd, ones);        // +-1.0
-                        af[b][1] = (int)(wd & 0x44444444u);            // 2 s
-                        af[b][2] = (int)(wd & 0x22222222u);            // s
-                        af[b][3] = (int)(wd & 0x11111111u);            // s / 2
+                    for (int b = 0; b < WR; ++b)
 #pragma unroll
-                        for (int jd = 4; jd < 8; ++jd) af[b][jd] = 0;
+                        for (int c = 0; c < WC; ++c) acc[b][c] = mfma_fp4(afc[b], bf[c], acc[b][c]);
+                    if (ks + 1 < KE / 64) {
 #pragma unroll
-                        for (int c = 0; c < WC; ++c) acc[b][c] = mfma_fp4(af[b], bf[c], acc[b][c]);
+                        for (int b = 0; b < WR; ++b) afn[b] = expand((unsigned int)wq[(ks + 1) >> 2][b][(ks + 1) & 3]);
+                    }
+#pragma unroll
+                    for (int i = 0; i < WR * WC; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one matrix instruction
+                        __builtin_amdgcn_sched_group_barrier(0x002, 4 / WC > 0 ? 4 / WC : 1, 0);   // its share of the 4 WR expansion operations
                     }
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int c = 0; c < WC; ++c) bq[c] = bn[c];
+#pragma unroll
+                    for (int b = 0; b < WR; ++b) afc[b] = afn[b];
                 }
             } else if constexpr (BITS == 1) {
                 // few validation vectors: both operands are packed rows, read as 4-byte words (K step ks:
