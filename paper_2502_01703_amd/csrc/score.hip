@@ -879,7 +879,7 @@ __device__ inline void stream32_slice_i8(const unsigned char *sb, const unsigned
 template <int BITS, int VB, int VR>
 __global__ void __launch_bounds__(64 * kStream32Waves, 2)
 score_stream_mfma32_kernel(ScoreArgs a, const int8_t *vexp, const int32_t *vsum, int32_t Mp, int32_t vrow, int32_t m0, int32_t mc,
-                           int64_t rb_each, int64_t rb_extra, int npass, int wb, int nb, unsigned ring_off) {
+                           int64_t rb_each, int64_t rb_extra, int unit, int npass, int wb, int nb, unsigned ring_off) {
     static_assert(VR == 32 * VB || (VB == 1 && (VR == 8 || VR == 16)), "staged validation rows");
     constexpr int NW = kStream32Waves;
     // Rows of a pass: two panels of 32; the int8 shapes with one validation block have registers for
@@ -915,9 +915,9 @@ score_stream_mfma32_kernel(ScoreArgs a, const int8_t *vexp, const int32_t *vsum,
         wlds[i] = __fmul_rn(a.eta[ci], a.vr[ci][m0 + (j < mc ? j : mc - 1)]);
         if (BITS == 1) blds[i] = 3 * (a.k / 4) - 2 * vsum[ci * a.M + m0 + (j < mc ? j : mc - 1)];
     }
-    int64_t r_end = rb1 * 8;
+    int64_t r_end = rb1 * unit;                 // blocks of `unit` rows are dealt out
     if (r_end > a.N) r_end = a.N;
-    const int64_t r_begin = rb0 * 8;
+    const int64_t r_begin = rb0 * unit;
     const int64_t my_rows = r_end > r_begin ? r_end - r_begin : 0;
     const int my_pass = (int)((my_rows + PASS - 1) / PASS);  // passes in which this wavefront has rows
     const int T = a.C * nsl;                                 // ring slots of a pass
@@ -1802,17 +1802,21 @@ template <int BITS, int VB, int VR>
 static qless_status launch_stream32_shape(const ScoreArgs &a, const ScorePrep &w, int32_t m0, int32_t mc, hipStream_t st) {
     constexpr int NW = kStream32Waves;
     QLESS_LDS_KERNEL((score_stream_mfma32_kernel<BITS, VB, VR>), (int)kLdsPerCU);
-    // at most one workgroup per compute unit; the 8-row blocks are dealt out evenly over all wavefronts
-    const int64_t total_rb = (a.N + 7) / 8;
-    int64_t groups = compute_units();
-    if (groups * NW > total_rb) groups = (total_rb + NW - 1) / NW;
-    const int64_t waves = groups * NW;
-    const int64_t each = total_rb / waves, extra = total_rb % waves;
+    // at most one workgroup per compute unit; blocks of rows are dealt out evenly over all wavefronts: 8-row
+    // blocks, or, where a wavefront gets more than a pass of two 32-row panels, whole panels -- the rows
+    // beyond full passes then make one more panel for a few wavefronts (one per compute unit first)
+    // instead of a nearly empty extra pass for half of them
     constexpr int kPass = (BITS != 1 && VB == 1) ? 80 : 64;          // rows of a pass, as in the kernel
-    const int npass = (int)(((each + (extra > 0 ? 1 : 0)) * 8 + kPass - 1) / kPass);
+    int64_t groups = compute_units();
+    if (groups * NW > (a.N + 7) / 8) groups = ((a.N + 7) / 8 + NW - 1) / NW;
+    const int64_t waves = groups * NW;
+    const int unit = (kPass == 64 && a.N >= waves * 64) ? 32 : 8;
+    const int64_t total_rb = (a.N + unit - 1) / unit;
+    const int64_t each = total_rb / waves, extra = total_rb % waves;
+    const int npass = (int)(((each + (extra > 0 ? 1 : 0)) * unit + kPass - 1) / kPass);
     const Stream32Plan sp = stream_mfma32_plan(BITS, VB, VR, a.k, a.C);
     hipLaunchKernelGGL((score_stream_mfma32_kernel<BITS, VB, VR>), dim3((unsigned)groups), dim3(64 * NW), sp.lds, st, a,
-                       (const int8_t *)w.vexp, (const int32_t *)w.vbias, w.Mp, w.vrow, m0, mc, each, extra, npass, sp.wb, sp.nb,
+                       (const int8_t *)w.vexp, (const int32_t *)w.vbias, w.Mp, w.vrow, m0, mc, each, extra, unit, npass, sp.wb, sp.nb,
                        (unsigned)sp.val_bytes);
     return QLESS_OK;
 }
