@@ -1796,7 +1796,7 @@ static Stream32Plan stream_mfma32_plan(int bits, int vb, int vr, int32_t k, int 
         }
     return best;
 }
-static int stream32_rows(int32_t mc) { return mc <= 8 ? 8 : (mc <= 16 ? 16 : (mc <= 32 ? 32 : 64)); }
+static int stream32_rows(int32_t mc) { return mc <= 8 ? 8 : (mc <= 16 ? 16 : (mc <= 32 ? 32 : (mc <= 64 ? 64 : 96))); }
 
 template <int BITS, int VB, int VR>
 static qless_status launch_stream32_shape(const ScoreArgs &a, const ScorePrep &w, int32_t m0, int32_t mc, hipStream_t st) {
@@ -1865,13 +1865,14 @@ static qless_status launch_stream_mfma32(const ScoreArgs &a, void *ws, hipStream
     return launch_status();
 }
 
-// 4- and 8-bit codes against at most 64 validation vectors: one launch; the 4-bit validation rows are
+// 4- and 8-bit codes against at most 96 / 32 validation vectors: one launch; the 4-bit validation rows are
 // int8-expanded by the pre-pass into the workspace first
 static bool use_stream_i8(int bits, int32_t M, int32_t k, int C) {
-    // measured against the tile kernel at N = 270 000: ahead up to 64 validation vectors at 4 bits, up to 32 at 8
-    if (bits < 4 || M > (bits == 4 ? 64 : 32) || (k * bits / 8) % 128 != 0) return false;
+    // measured against the tile kernel at N = 270 000: ahead up to 96 validation vectors at 4 bits (one pass of three
+    // 32-wide blocks: 1.33 against 1.45 ms at M = 81), up to 32 at 8 bits (M = 40: 1.77 against 1.65 ms; M = 81: equal)
+    if (bits < 4 || M > (bits == 4 ? 96 : 32) || (k * bits / 8) % 128 != 0) return false;
     const int vr = stream32_rows(M);
-    return stream_mfma32_plan(bits, vr > 32 ? 2 : 1, vr, k, C).nb >= 2;
+    return stream_mfma32_plan(bits, vr > 32 ? vr / 32 : 1, vr, k, C).nb >= 2;
 }
 template <int BITS>
 static qless_status launch_stream_i8(const ScoreArgs &a, void *ws, hipStream_t st) {
@@ -1888,7 +1889,8 @@ static qless_status launch_stream_i8(const ScoreArgs &a, void *ws, hipStream_t s
     if (vr == 8) rc = launch_stream32_shape<BITS, 1, 8>(a, w, 0, a.M, st);
     else if (vr == 16) rc = launch_stream32_shape<BITS, 1, 16>(a, w, 0, a.M, st);
     else if (vr == 32) rc = launch_stream32_shape<BITS, 1, 32>(a, w, 0, a.M, st);
-    else rc = launch_stream32_shape<BITS, 2, 64>(a, w, 0, a.M, st);
+    else if (vr == 64) rc = launch_stream32_shape<BITS, 2, 64>(a, w, 0, a.M, st);
+    else rc = launch_stream32_shape<BITS, 3, 96>(a, w, 0, a.M, st);
     return rc != QLESS_OK ? rc : launch_status();
 }
 

@@ -207,7 +207,8 @@ def _datastore(n, k, bits, C, seed):
                                      (300, 12, 8192, 4), (1000, 16, 8192, 3), (200, 9, 16384, 4), (100, 16, 32768, 4),
                                      (150, 5, 65536, 2),
                                      (300, 256, 16384, 4), (260, 100, 16384, 2), (200, 40, 512, 16), (300, 140, 256, 16),
-                                     (400, 12, 384, 16)])
+                                     (400, 12, 384, 16),
+                                     (9000, 81, 1024, 2), (700, 96, 512, 3), (300, 65, 2048, 4)])
 def test_score_bit_exact(bits, N, M, k, C):
     _say("score bits=%d N=%d M=%d k=%d C=%d" % (bits, N, M, k, C))
     tc, tr = _datastore(N, k, bits, C, 1000 + bits)
