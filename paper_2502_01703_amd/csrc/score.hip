@@ -1627,7 +1627,11 @@ static qless_status launch_mfma_shape(const ScoreArgs &a, const ScorePrep &w, in
     QLESS_LDS_KERNEL((score_mfma_kernel<BITS, WR, WC, WX, NW, F16, VH>), kMaxDynamic);
     if (lds > (size_t)kMaxDynamic) return QLESS_ERR_DEVICE;
     const int64_t ttiles = (a.N + Sh::MT - 1) / Sh::MT;
-    const int vtiles = w.Mp / Sh::VT;
+    // the shape that stages the packed validation rows itself addresses them relative to its first row, which
+    // must exist: no tile may start past the last validation vector (the padded rows of the pre-pass do not
+    // exist for it)
+    const int vtiles = Sh::VPACKED ? (a.M + Sh::VT - 1) / Sh::VT : w.Mp / Sh::VT;
+    if ((int64_t)vtiles * Sh::VT > w.Mp) return QLESS_ERR_DEVICE;      // weights are read up to the padded width
     const int64_t grid = 8 * (int64_t)vtiles * ((ttiles + 7) / 8);
     if (grid > 0x7FFFFFFF) return QLESS_ERR_UNSUPPORTED;
     hipLaunchKernelGGL((score_mfma_kernel<BITS, WR, WC, WX, NW, F16, VH>), dim3((unsigned)grid), dim3(64 * NW), lds, st, a, w,
@@ -1693,14 +1697,21 @@ static qless_status launch_mfma(const ScoreArgs &a, void *ws, hipStream_t st, bo
     unsigned char *base = (unsigned char *)ws;
     w.vexp = (int8_t *)base; w.vw = (float *)(base + p.off_vw); w.vbias = (int32_t *)(base + p.off_vbias);
     w.smax = (unsigned int *)(base + p.off_smax); w.Mp = p.Mp; w.kp = p.kp;
-    w.vrow = BITS == 1 ? (p.vt > 64 ? p.kp / 2 : 0) : (BITS == 2 ? p.kp / 2 : p.kp);
+    // a small datastore leaves most compute units without a 256 x 128 tile: 128 x 64 tiles fill four times as
+    // many (the expanded validation rows are the same for both shapes; the sign codes' narrow shape stages the
+    // packed validation rows itself)
+    const bool small = !F16 && p.vt == 128 && ((a.N + 255) / 256) * (p.Mp / 128) * 2 <= compute_units();
+    w.vrow = BITS == 1 ? (p.vt > 64 && !small ? p.kp / 2 : 0) : (BITS == 2 ? p.kp / 2 : p.kp);
     if (prepare)
         hipLaunchKernelGGL((score_prepare_kernel<BITS, F16>), dim3((unsigned)p.Mp, (unsigned)a.C), dim3(256), 0, st, a, w);
     qless_status rc;
     if (p.vt == 96) {
         if constexpr (BITS == 1) rc = launch_mfma_shape<BITS, 2, 3, 1, 8, F16>(a, w, 0, st);
         else rc = QLESS_ERR_UNSUPPORTED;
-    } else if (p.vt == 128) rc = launch_mfma_shape<BITS, 2, 2, 2, 8, F16>(a, w, 0, st);
+    } else if (p.vt == 128) {
+        if (small) rc = launch_mfma_shape<BITS, 1, 2, 1, 4, F16>(a, w, 0, st);
+        else rc = launch_mfma_shape<BITS, 2, 2, 2, 8, F16>(a, w, 0, st);
+    }
     else if (p.vt == 64) {
         const NarrowChoice c = choose_narrow<BITS, 2>(a.N);
         if (c.nw == 8) rc = launch_mfma_shape<BITS, 1, 2, 1, 8, F16>(a, w, c.per_cu, st);
