@@ -562,3 +562,58 @@ def test_score_groups_is_score_then_aggregate(bits, N, M, k, C, ends, mode):
     dev = lambda arrs: [torch.from_numpy(a).to(DEV) for a in arrs]
     got = Q.score_groups(dev(tc), dev(tr), dev(vc), dev(vr), eta, k, bits, ends, mode)
     np.testing.assert_array_equal(got.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+
+
+def test_variant_calls_replay_in_a_hip_graph():
+    """The variant entry points (sliced datastore build, fused group aggregation, mixed precision, top-k without a
+    workspace) only enqueue kernels as well: captured after qless_init, every replay gives the bits of the eager calls."""
+    _say("graph replay of slice / groups / mixed / noalloc calls")
+    N, M, k, C, d, ksel, bits = 3000, 130, 1024, 2, 8192, 100, 4
+    gen = torch.Generator(device=DEV); gen.manual_seed(99)
+    G = [torch.randn(N, d, generator=gen, device=DEV).to(torch.bfloat16) for _ in range(C)]
+    Pv = [torch.randn(M, k, generator=gen, device=DEV) for _ in range(C)]
+    vq = [Q.quantize(p, bits) for p in Pv]
+    vc, vr = [q[0] for q in vq], [q[2] for q in vq]
+    v16 = [torch.empty(M, k, dtype=torch.bfloat16, device=DEV) for _ in range(C)]
+    for c in range(C):
+        Q.normalize16(Pv[c], out=v16[c])
+    P = [torch.empty(N, k, dtype=torch.float32, device=DEV) for _ in range(C)]
+    tc = [torch.empty(N, Q.code_bytes(k, bits), dtype=torch.uint8, device=DEV) for _ in range(C)]
+    tS = [torch.empty(N, dtype=torch.float32, device=DEV) for _ in range(C)]
+    tr = [torch.empty(N, dtype=torch.float32, device=DEV) for _ in range(C)]
+    ws_p = torch.empty(Q.project_workspace(N, d // 2, k), dtype=torch.uint8, device=DEV)
+    ws_g = torch.empty(Q.score_groups_workspace(N, M, k, bits, C), dtype=torch.uint8, device=DEV)
+    ws_m = torch.empty(Q.score_mixed_workspace(N, M, k, bits, C), dtype=torch.uint8, device=DEV)
+    ends, eta = [30, 64, 130], [1.0, 0.5]
+    grp = torch.empty(N, len(ends), dtype=torch.float32, device=DEV)
+    idx = torch.empty(ksel, dtype=torch.int64, device=DEV)
+    val = torch.empty(ksel, dtype=torch.float32, device=DEV)
+
+    def run():
+        for c in range(C):
+            Q.project_quantize_slice(G[c][:, :d // 2], k, 0, P[c], True, False, seed=4, ws=ws_p)
+            Q.project_quantize_slice(G[c][:, d // 2:], k, d // 2, P[c], False, True, bits=bits, seed=4,
+                                     codes=tc[c], S=tS[c], rnorm=tr[c], ws=ws_p)
+        Q.score_groups(tc, tr, vc, vr, eta, k, bits, ends, Q.AGG_MEAN, out=grp, ws=ws_g)
+        mixed = Q.score_mixed(tc, tr, v16, eta, k, bits, ws=ws_m)
+        Q.topk_noalloc(mixed, idx, val)
+        return mixed
+
+    Q.init()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        g_mixed = run()
+    for rep in range(3):
+        for c in range(C):
+            G[c].copy_(torch.randn(N, d, generator=gen, device=DEV).to(torch.bfloat16))     # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (g_mixed, grp, idx, val, tc[0], tr[1])]
+        for t in (grp, idx, val):
+            t.zero_()
+        e_mixed = run()
+        torch.cuda.synchronize()
+        for a, b in zip(got, (e_mixed, grp, idx, val, tc[0], tr[1])):
+            assert torch.equal(a, b), rep
