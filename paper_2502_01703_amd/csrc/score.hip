@@ -693,14 +693,15 @@ score_stream_mfma_kernel(ScoreArgs a, int64_t rb_each, int64_t rb_extra, int nb,
 // the products are 32 x 32 x 64 FP4 instructions.
 //
 // A wavefront works on tiles of 64 train rows (two panels of 32) x 64 validation vectors (two blocks
-// of 32): per 64-element K step it expands one dword of each panel and block (4 x 7 vector ALU
-// operations) for 4 matrix-core instructions, which keeps the vector ALU below the matrix cores.
+// of 32): per 64-element K step it expands one word of each panel and block (2 x 6 + 2 x 4 vector ALU
+// operations, the bits of both operands left in place: see fp4_train_in_place) for 4 matrix-core instructions.
 // The per-checkpoint sums of the tile stay in registers, so a wavefront walks its rows in passes
 // of up to 64; the wavefronts of a workgroup have equally many passes.
 //   * Train rows: a private ring per wavefront; a slot is a 64-byte slice of the 64 rows (four 1 KB
 //     copies of 16 rows x 64 bytes, chunk (lane % 4) ^ ((row / 2) % 4) at position lane % 4, so that 8
 //     rows read together use all banks).  The ring runs through all passes without a break.
-//   * Validation rows: all of them do not fit in LDS next to the rings, so the workgroup keeps a
+//   * Validation rows (for the sign codes the pre-pass's copy with bits 0 and 2 of every nibble
+//     swapped): all of them do not fit in LDS next to the rings, so the workgroup keeps a
 //     window of WB bytes of every row of one checkpoint, double buffered.  The windows follow each
 //     other in "phases" (pass, checkpoint, window).  The window of phase g + 1 is copied
 //     asynchronously during phase g, each wavefront its share; before the one barrier per phase a
