@@ -762,9 +762,9 @@ __device__ inline uint32_t fp4_halves() {
 // rows: 8 K steps.  sb: the slot; vwin: the validation window (bit-permuted copy); vcol: chunk index of
 // the slice's first chunk inside the window; wb: bytes per window row; cnt: per panel, this lane's count
 // of negative train codes outside dword 0.
-template <int VB, int NPAN>
+template <int VB, int NPAN, int NPMAX>
 __device__ inline void stream32_slice(const unsigned char *sb, const unsigned char *vwin, int vcol, int wb,
-                                      int l32, int half, uint32_t halves, f32x16 (&acc)[2][VB], uint32_t (&cnt)[2]) {
+                                      int l32, int half, uint32_t halves, f32x16 (&acc)[NPMAX][VB], uint32_t (&cnt)[NPMAX]) {
     // K step ks = 4 c + j uses dword j of chunk 2 c + half.  The operands of step ks + 1 are expanded
     // between the matrix-core instructions of step ks (one instruction, then one operand's vector
     // ALU operations; scheduling barriers keep that order), so the matrix pipe is not left waiting
@@ -886,8 +886,9 @@ score_stream_mfma32_kernel(ScoreArgs a, const int8_t *vexp, const int32_t *vsum,
     // Rows of a pass: two panels of 32; the int8 shapes with one validation block have registers for
     // a third panel of 16 rows, which saves a whole pass over K when a wavefront's range is a little
     // more than two tiles (136 rows of 270 000 on 2048 wavefronts).
-    constexpr int NPMAX = (BITS != 1 && VB == 1) ? 3 : 2;
-    constexpr int PASS = NPMAX == 3 ? 80 : 64;
+    // (the sign codes with one validation block take three full panels: 132 rows are then two passes, not three)
+    constexpr int NPMAX = VB == 1 ? 3 : 2;
+    constexpr int PASS = NPMAX == 3 ? (BITS == 1 ? 96 : 80) : 64;
     constexpr int NQ = PASS / 16;               // 1 KB copies per slot
     constexpr int SLOT = NQ * 1024;             // PASS rows x 64 bytes
     // LDS: 2 x [VR][wbv] validation windows | [C][32 VB] weights | rings
@@ -978,7 +979,7 @@ score_stream_mfma32_kernel(ScoreArgs a, const int8_t *vexp, const int32_t *vsum,
         const int rows = ps < my_pass ? (r_end - rp < PASS ? (int)(r_end - rp) : PASS) : 0;   // wave-uniform
         const int last = rows - 1;
         typename AccType<BITS == 1>::type acc[NPMAX][VB];
-        uint32_t cnt[2] = {0u, 0u};              // sign codes: negative train codes outside dword 0, this lane's half of K
+        uint32_t cnt[NPMAX] = {};                // sign codes: negative train codes outside dword 0, this lane's half of K
         float facc[NPMAX][VB][16];
 #pragma unroll
         for (int p = 0; p < NPMAX; ++p)
@@ -1004,8 +1005,9 @@ score_stream_mfma32_kernel(ScoreArgs a, const int8_t *vexp, const int32_t *vsum,
                         if (f_it < S) fetch();
                         const unsigned char *sb = ring + (size_t)pos * SLOT;
                         if constexpr (BITS == 1) {
-                            if (rows > 32) stream32_slice<VB, 2>(sb, vwin, 4 * s4, wb, l32, half, halves, acc, cnt);
-                            else stream32_slice<VB, 1>(sb, vwin, 4 * s4, wb, l32, half, halves, acc, cnt);
+                            if (NPMAX == 3 && rows > 64) stream32_slice<VB, NPMAX, NPMAX>(sb, vwin, 4 * s4, wb, l32, half, halves, acc, cnt);
+                            else if (rows > 32) stream32_slice<VB, 2, NPMAX>(sb, vwin, 4 * s4, wb, l32, half, halves, acc, cnt);
+                            else stream32_slice<VB, 1, NPMAX>(sb, vwin, 4 * s4, wb, l32, half, halves, acc, cnt);
                         } else {
                             if (NPMAX == 3 && rows > 64) stream32_slice_i8<BITS, VB, VR, NPMAX, NPMAX>(sb, vwin, s4, wbv, l32, half, acc);
                             else if (rows > 32) stream32_slice_i8<BITS, VB, VR, 2, NPMAX>(sb, vwin, s4, wbv, l32, half, acc);
@@ -1025,7 +1027,7 @@ score_stream_mfma32_kernel(ScoreArgs a, const int8_t *vexp, const int32_t *vsum,
                     const float rt = a.tr[ci][rp + (32 * p + l32 < rows ? 32 * p + l32 : last)];
                     // sign codes: St of train row l32 = the counts of the two lanes that share the row
                     int st2 = 0;
-                    if (BITS == 1) { const uint32_t c = cnt[p < 2 ? p : 0]; st2 = 2 * (int)(c + (uint32_t)__shfl_xor((int)c, 32)); }
+                    if (BITS == 1) { const uint32_t c = cnt[p]; st2 = 2 * (int)(c + (uint32_t)__shfl_xor((int)c, 32)); }
 #pragma unroll
                     for (int vb = 0; vb < VB; ++vb)
 #pragma unroll
@@ -1040,7 +1042,8 @@ score_stream_mfma32_kernel(ScoreArgs a, const int8_t *vexp, const int32_t *vsum,
                             acc[p][vb][v] = 0;
                         }
                 }
-                cnt[0] = 0u; cnt[1] = 0u;
+#pragma unroll
+                for (int p = 0; p < NPMAX; ++p) cnt[p] = 0u;
             }
         }
         if (rows > 0) {
@@ -1795,7 +1798,7 @@ struct Stream32Plan { int wb, nb; size_t val_bytes, lds; };
 static Stream32Plan stream_mfma32_plan(int bits, int vb, int vr, int32_t k, int C) {
     Stream32Plan best{};
     const int cb = k * bits / 8;
-    const size_t slot = (bits != 1 && vb == 1) ? 5120 : 4096;       // 80 or 64 rows x 64 bytes
+    const size_t slot = vb == 1 ? (bits == 1 ? 6144 : 5120) : 4096;  // 96, 80 or 64 rows x 64 bytes
     for (int want = 3; want >= 2 && best.nb == 0; --want)
         for (int wb = 2048; wb >= 128; wb >>= 1) {
             if (cb % wb) continue;
@@ -1818,11 +1821,11 @@ static qless_status launch_stream32_shape(const ScoreArgs &a, const ScorePrep &w
     // blocks, or, where a wavefront gets more than a pass of two 32-row panels, whole panels -- the rows
     // beyond full passes then make one more panel for a few wavefronts (one per compute unit first)
     // instead of a nearly empty extra pass for half of them
-    constexpr int kPass = (BITS != 1 && VB == 1) ? 80 : 64;          // rows of a pass, as in the kernel
+    constexpr int kPass = VB == 1 ? (BITS == 1 ? 96 : 80) : 64;      // rows of a pass, as in the kernel
     int64_t groups = compute_units();
     if (groups * NW > (a.N + 7) / 8) groups = ((a.N + 7) / 8 + NW - 1) / NW;
     const int64_t waves = groups * NW;
-    const int unit = (kPass == 64 && a.N >= waves * 64) ? 32 : 8;
+    const int unit = (kPass != 80 && a.N >= waves * 64) ? 32 : 8;
     const int64_t total_rb = (a.N + unit - 1) / unit;
     const int64_t each = total_rb / waves, extra = total_rb % waves;
     const int npass = (int)(((each + (extra > 0 ? 1 : 0)) * unit + kPass - 1) / kPass);
