@@ -1799,7 +1799,9 @@ static Stream32Plan stream_mfma32_plan(int bits, int vb, int vr, int32_t k, int 
     Stream32Plan best{};
     const int cb = k * bits / 8;
     const size_t slot = vb == 1 ? (bits == 1 ? 6144 : 5120) : 4096;  // 96, 80 or 64 rows x 64 bytes
-    for (int want = 3; want >= 2 && best.nb == 0; --want)
+    // (the sign codes with one validation block, whose slots are 96 rows, do better with a ring of two and
+    // windows four times as wide: fewer barriers; measured 0.246 -> 0.236 ms at M = 32)
+    for (int want = (bits == 1 && vb == 1) ? 2 : 3; want >= 2 && best.nb == 0; --want)
         for (int wb = 2048; wb >= 128; wb >>= 1) {
             if (cb % wb) continue;
             const int wbv = bits == 4 ? 2 * wb : wb;
