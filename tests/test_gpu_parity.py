@@ -617,3 +617,32 @@ def test_variant_calls_replay_in_a_hip_graph():
         torch.cuda.synchronize()
         for a, b in zip(got, (e_mixed, grp, idx, val, tc[0], tr[1])):
             assert torch.equal(a, b), rep
+
+
+def test_score_and_group_aggregation_random_sweep():
+    """Seeded sweep over code widths, vector lengths (multiples of 64, 128, 512 or not), validation-set sizes on both
+    sides of every kernel boundary (8 / 16 / 32 / 64 / 96 / 192) and 1..5 checkpoints: scores, the full matrix and
+    both group aggregations bit-identical to the oracle."""
+    rng = np.random.default_rng(20250202)
+    dev = lambda arrs: [torch.from_numpy(a).to(DEV) for a in arrs]
+    for case in range(60):
+        bits = int(rng.choice([1, 1, 2, 4, 8]))
+        k = int(rng.choice([64, 128, 192, 256, 384, 512, 1024, 1536, 2048, 4096, 8192]))
+        M = int(rng.choice([1, 7, 8, 9, 16, 17, 32, 33, 63, 64, 65, 96, 97, 128, 160, 192, 193, 256, 300]))
+        C = int(rng.integers(1, 6))
+        N = int(max(1, min(rng.integers(1, 20000), 6e8 / (M * k * C))))
+        eta = [float(x) for x in np.round(rng.uniform(0.1, 1.0, C), 3)]
+        _say("random sweep case %d: bits=%d N=%d M=%d k=%d C=%d" % (case, bits, N, M, k, C))
+        tc, tr = _datastore(N, k, bits, C, 9000 + case)
+        vc, vr = _datastore(M, k, bits, C, 9500 + case)
+        ref_s, ref_f = oracle.score(tc, tr, vc, vr, eta, k, bits, want_full=True)
+        dtc, dtr, dvc, dvr = dev(tc), dev(tr), dev(vc), dev(vr)
+        s, f = Q.score(dtc, dtr, dvc, dvr, eta, k, bits, want_full=True)
+        np.testing.assert_array_equal(f.cpu().numpy().view(np.uint32), ref_f.view(np.uint32), err_msg="case %d" % case)
+        np.testing.assert_array_equal(s.cpu().numpy().view(np.uint32), ref_s.view(np.uint32), err_msg="case %d" % case)
+        T = int(rng.integers(1, min(M, 8) + 1))
+        ends = sorted(set(rng.choice(np.arange(1, M + 1), size=T, replace=False).tolist()) | {M})
+        for mode in (Q.AGG_MAX, Q.AGG_MEAN):
+            g = Q.score_groups(dtc, dtr, dvc, dvr, eta, k, bits, ends, mode)
+            np.testing.assert_array_equal(g.cpu().numpy().view(np.uint32), oracle.aggregate(ref_f, ends, mode).view(np.uint32),
+                                          err_msg="case %d mode %d" % (case, mode))
